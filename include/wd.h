@@ -1,0 +1,154 @@
+/*
+ * wd.h — C ABI of libwd: the batched discrete Tag roll-out path on one MI355X.
+ *
+ * The library runs the three device-side services of a WarpDrive-style roll-out
+ * (arXiv 2108.13976, Sec. 4.4 "Software Layers and Components": the sampler and
+ * reset kernels of the "CUDA Service" and the step kernel of the "CUDA
+ * Environment"; Sec. 4.5 "The WarpDrive RL Workflow", items 2-6) for the discrete
+ * Tag environment of Sec. 5.1, on ONE device-resident struct-of-arrays data store
+ * that is updated in place (Sec. 4.2, "Minimal Communication"; the step signature
+ * figure: float observations and rewards, int actions and done flags).
+ *
+ * Conventions
+ *   - Every function returns WD_OK (0) or a negative wd_status; none throws or
+ *     aborts.  On failure nothing has been enqueued unless stated otherwise.
+ *   - All pointers inside wd_buffers and the `probs` arguments are DEVICE
+ *     pointers (hipMalloc'd or PyTorch-allocated), owned by the caller and only
+ *     borrowed until wd_destroy.  Each must be 256-byte aligned and hold at least
+ *     the element count that wd_query_layout reports.  All other pointers
+ *     (config, layout, handle, out parameters) are HOST pointers.
+ *   - Kernels are enqueued on wd_config.stream (a hipStream_t, borrowed; NULL =
+ *     the default stream) and are NOT synchronised: the caller synchronises
+ *     before reading results on the host.  Calls on one handle must be issued
+ *     from one host thread at a time.
+ *   - The library allocates no device memory for these entry points: all state
+ *     lives in the caller's buffers, the handle holds host metadata only.
+ *   - Random numbers are Philox4x32-10 blocks keyed by (seed, global env id,
+ *     agent, global step g, stream), so results do not depend on launch shape,
+ *     and a run over envs [a, b) with env_offset = a reproduces those envs of the
+ *     full run.
+ *
+ * Array layouts (row-major): per-agent arrays are [E][N]; obs is [E][N][D];
+ * per-env arrays are [E].  int32 and float32 throughout.
+ */
+#ifndef WD_H
+#define WD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum wd_status {
+  WD_OK = 0,
+  WD_E_NULL = -1,   /* a required pointer is NULL                                   */
+  WD_E_CONFIG = -2, /* a config field is out of range or struct_size mismatches     */
+  WD_E_ALIGN = -3,  /* a device buffer is not 256-byte aligned                      */
+  WD_E_STATE = -4,  /* call order: sample/step/reset(DONE) before the first reset(ALL) */
+  WD_E_HIP = -5,    /* a HIP call failed; wd_last_error(handle) has the text        */
+  WD_E_UNSUPPORTED = -6 /* valid config that this build has no kernel for           */
+} wd_status;
+
+enum { WD_RESET_ALL = 0, WD_RESET_DONE = 1 };
+enum { WD_OBS_PARTIAL = 0, WD_OBS_FULL = 1 };
+
+/* Configuration of one batch of Tag environments (Sec. 5.1, Tag paragraph). */
+typedef struct wd_config {
+  uint32_t struct_size;   /* = sizeof(wd_config); ABI check                              */
+  int32_t num_envs;       /* E >= 1 environments in the buffers                          */
+  int32_t env_offset;     /* >= 0: global id of env 0 (shard of a larger run)            */
+  int32_t num_agents;     /* N: 2 <= N <= 32768                                          */
+  int32_t num_taggers;    /* N_tag: 1 <= N_tag <= N-1; agents 0..N_tag-1 are taggers     */
+  int32_t grid_size;      /* G: square grid, 1 <= G <= 32767                             */
+  int32_t num_actions;    /* must be 5: stay, up (y+1), down (y-1), left (x-1), right (x+1) */
+  int32_t episode_length; /* T >= 1: an episode ends after T steps at the latest         */
+  int32_t tag_r2;         /* a runner is tagged iff some tagger is at squared distance
+                             <= tag_r2 after the moves; negative disables tagging        */
+  int32_t obs_mode;       /* WD_OBS_PARTIAL (K nearest agents) or WD_OBS_FULL            */
+  int32_t obs_k;          /* K: 0 <= K <= N-1 (ignored in full mode)                     */
+  float tag_reward;       /* to the credited tagger, per tag ("e.g. +1")                 */
+  float tag_penalty;      /* to the runner on the step it is tagged ("e.g. -1")          */
+  uint64_t seed;
+  void* stream;           /* hipStream_t, borrowed                                       */
+} wd_config;
+
+/* The device-resident data store (Sec. 4.5 item 1: state arrays plus the
+ * observation / action / reward / done placeholders; pos_x0, pos_y0 are the copies
+ * "re-initialised at every reset"). */
+typedef struct wd_buffers {
+  int32_t *pos_x, *pos_y;   /* [E][N] cell coordinates in [0, G)                         */
+  int32_t *pos_x0, *pos_y0; /* [E][N] start positions, written by wd_reset(ALL)          */
+  int32_t* live;            /* [E][N] 1 = in play, 0 = tagged runner                     */
+  int32_t* action;          /* [E][N] written by wd_sample, read by wd_step              */
+  float* reward;            /* [E][N] overwritten for every agent by each step           */
+  float* obs;               /* [E][N][D]                                                 */
+  int32_t *t, *done, *n_live_runners, *tags_step; /* [E]                                 */
+} wd_buffers;
+
+/* Element counts the caller must allocate, and the algorithmic HBM bytes of one
+ * roll-out iteration (sample + step + reset of done envs). */
+typedef struct wd_layout {
+  int32_t obs_dim;            /* D = 5 + 4K (partial) or 5 + 4N (full)                   */
+  int64_t per_agent_elems;    /* E*N      : pos_*, live, action, reward                  */
+  int64_t obs_elems;          /* E*N*D                                                   */
+  int64_t per_env_elems;      /* E        : t, done, n_live_runners, tags_step           */
+  int64_t probs_elems;        /* E*N*5    : the probs argument of wd_sample              */
+  int64_t bytes_per_iteration;/* E*N*(4*5 + 36 + 4*D) + 24*E                             */
+} wd_layout;
+
+typedef struct wd_handle wd_handle;
+
+/* Fills *out for a configuration.  Host only; touches no device. */
+int wd_query_layout(const wd_config* cfg, wd_layout* out);
+
+/* Validates cfg and bufs (range, alignment), chooses the launch geometry and
+ * returns a handle in *out.  Enqueues nothing; the buffers' contents are not read.
+ * WD_E_UNSUPPORTED if no kernel of this build covers the configuration. */
+int wd_create(const wd_config* cfg, const wd_buffers* bufs, wd_handle** out);
+
+/* Environment reset (Sec. 4.5 item 5 "Automatic Environment Resetting").
+ * WD_RESET_ALL : draws pos_x0/pos_y0 uniformly on the grid from the seed, then puts
+ *                every env in its start state; sets the global step g to 0.
+ * WD_RESET_DONE: every env with done == 1 is put back in its start state in place
+ *                (pos <- pos0, live <- 1, t <- 0, n_live_runners <- N - N_tag,
+ *                tags_step <- 0, done <- 0, obs <- observation of that state;
+ *                reward and action untouched); other envs are untouched. */
+int wd_reset(wd_handle* h, int mode);
+
+/* Action sampling (Sec. 4.5 item 6 "Thread-parallelized Action Sampling").
+ * probs: device [E][N][5] float32 policy outputs.  Writes action[e][i] for EVERY
+ * agent of EVERY env by inverse CDF (float32 running sum, left to right, strict
+ * "u < sum", last action as fall-through) with u from the random block of
+ * (seed, env_offset + e, i, g, stream 0).  Does not advance g. */
+int wd_sample(wd_handle* h, const float* probs);
+
+/* One Tag step (Sec. 5.1; Sec. 4.5 items 3-4) for every env with done == 0, in
+ * place: move, tag check, rewards, t / n_live_runners / tags_step / done,
+ * observations.  Envs with done == 1 are left untouched.  Consumes
+ * buffers.action; then advances the global step g by one. */
+int wd_step(wd_handle* h);
+
+/* One whole roll-out iteration in a single launch: wd_sample(probs), wd_step,
+ * wd_reset(WD_RESET_DONE), with identical results. */
+int wd_iterate(wd_handle* h, const float* probs);
+
+/* The global step counter g used as the RNG step index (checkpoint / resume). */
+int wd_get_step(wd_handle* h, uint64_t* g);
+int wd_set_step(wd_handle* h, uint64_t g);
+
+/* Frees the handle (host memory only).  The caller's buffers are not touched;
+ * work already enqueued on the stream is not waited for. */
+int wd_destroy(wd_handle* h);
+
+/* Static text for a status code. */
+const char* wd_strerror(int status);
+
+/* Text of the last HIP failure seen on this handle ("" if none).  The pointer is
+ * valid until the next call on the handle. */
+const char* wd_last_error(wd_handle* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WD_H */

@@ -1,0 +1,294 @@
+// wd_api.hip — host side of libwd: the C ABI of include/wd.h, configuration checks,
+// launch geometry and LDS map, and the calls into the launchers of wd_kernels.hip.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "../../include/wd.h"
+#include "wd_internal.h"
+
+struct wd_handle {
+  wd_config cfg;
+  wd_buffers bufs;
+  wd::Params params;
+  hipStream_t stream;
+  uint64_t g;          // global step: RNG step index
+  bool started;        // wd_reset(WD_RESET_ALL) has run
+  std::string last_error;
+};
+
+namespace {
+
+constexpr int64_t kLdsLimitBytes = 160 * 1024;  // LDS of one gfx950 compute unit
+constexpr int kMaxAgents = 32768;
+constexpr int kMaxGrid = 32767;
+
+int bits_for(uint32_t v) {  // bits needed to hold values 0..v
+  int b = 1;
+  while ((uint64_t(1) << b) <= v) ++b;
+  return b;
+}
+
+uint32_t pow2_ceil(uint32_t v) {
+  uint32_t r = 1;
+  while (r < v) r <<= 1;
+  return r;
+}
+
+int32_t isqrt64(int64_t v) {
+  int64_t r = int64_t(std::sqrt(double(v)));
+  while (r * r > v) --r;
+  while ((r + 1) * (r + 1) <= v) ++r;
+  return int32_t(r);
+}
+
+int64_t align16(int64_t v) { return (v + 15) & ~int64_t(15); }
+
+int check_config(const wd_config* c) {
+  if (!c) return WD_E_NULL;
+  if (c->struct_size != sizeof(wd_config)) return WD_E_CONFIG;
+  if (c->num_envs < 1 || c->env_offset < 0) return WD_E_CONFIG;
+  if (int64_t(c->num_envs) + int64_t(c->env_offset) > int64_t(INT32_MAX)) return WD_E_CONFIG;
+  if (c->num_agents < 2 || c->num_agents > kMaxAgents) return WD_E_CONFIG;
+  if (c->num_taggers < 1 || c->num_taggers > c->num_agents - 1) return WD_E_CONFIG;
+  if (c->grid_size < 1 || c->grid_size > kMaxGrid) return WD_E_CONFIG;
+  if (c->num_actions != wd::kNumActions) return WD_E_CONFIG;
+  if (c->episode_length < 1) return WD_E_CONFIG;
+  if (c->obs_mode != WD_OBS_PARTIAL && c->obs_mode != WD_OBS_FULL) return WD_E_CONFIG;
+  if (c->obs_mode == WD_OBS_PARTIAL && (c->obs_k < 0 || c->obs_k > c->num_agents - 1)) return WD_E_CONFIG;
+  if (!(c->tag_reward == c->tag_reward) || !(c->tag_penalty == c->tag_penalty)) return WD_E_CONFIG;  // NaN
+  if (int64_t(c->num_envs) * c->num_agents > int64_t(INT32_MAX)) return WD_E_CONFIG;
+  return WD_OK;
+}
+
+int32_t obs_dim(const wd_config* c) {
+  return c->obs_mode == WD_OBS_PARTIAL ? 5 + 4 * c->obs_k : 5 + 4 * c->num_agents;
+}
+
+bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+
+// Launch geometry and LDS map of the env-per-team kernels.  Returns false if an env does
+// not fit one workgroup's LDS.
+bool plan_env_kernels(const wd_config& c, wd::Params* p) {
+  const int N = c.num_agents;
+  int ts_log2 = 3;
+  while ((1 << ts_log2) < N && ts_log2 < 8) ++ts_log2;
+  const int ts = 1 << ts_log2;
+  p->ts_log2 = ts_log2;
+  p->teams_per_wg = wd::kWorkgroupSize / ts;
+  p->apt = (N + ts - 1) / ts;
+  uint32_t nb_cap = pow2_ceil(uint32_t(N));
+  if (nb_cap > 4096u) nb_cap = 4096u;
+  if (nb_cap < uint32_t(ts)) nb_cap = uint32_t(ts);
+  p->nb_cap = int32_t(nb_cap);
+  p->scan_chunk = int32_t(nb_cap) / ts;
+  p->lambda_num = 3;
+  p->lambda_den = 1;
+  p->div_N = wd::make_fastdiv(uint32_t(N));
+
+  // (distance, index) keys: 32 bits when they fit, else 64 (signalled by ~idx_bits)
+  const int idx_bits = bits_for(uint32_t(N - 1));
+  const uint64_t d2max = 2ull * uint64_t(c.grid_size - 1) * uint64_t(c.grid_size - 1);
+  const bool narrow = ((d2max + 1) << idx_bits) < (1ull << 32);
+  p->idx_bits = narrow ? idx_bits : ~idx_bits;
+  const int key_bytes = narrow ? 4 : 8;
+  const bool register_path = p->K <= wd::kMaxRegisterK;
+
+  int64_t off = 0;
+  auto take = [&off](int64_t bytes) {
+    const int64_t at = off;
+    off = align16(off + bytes);
+    return int32_t(at);
+  };
+  p->off_pl = take(4ll * N);
+  p->off_sorted = take(8ll * N);
+  p->off_slot = take(2ll * N);
+  p->off_best = take(int64_t(key_bytes) * N);
+  p->off_credits = take(4ll * c.num_taggers);
+  p->off_nbr = take(register_path ? 2ll * N * p->K : 0);
+  p->off_counts = take(4ll * nb_cap);
+  p->off_starts = take(4ll * (nb_cap + 4));
+  p->off_misc = take(32);
+  p->team_stride = int32_t(off);
+  const int64_t stage = register_path ? int64_t(wd::kWorkgroupSize) * p->D * 4 : 0;
+  const int64_t total = int64_t(p->team_stride) * p->teams_per_wg + stage;
+  p->off_stage = p->team_stride * p->teams_per_wg;
+  p->lds_bytes = int32_t(total);
+  return total <= kLdsLimitBytes;
+}
+
+int fill_params(const wd_config& c, const wd_buffers& b, wd::Params* p) {
+  std::memset(p, 0, sizeof(*p));
+  p->E = c.num_envs;
+  p->N = c.num_agents;
+  p->N_tag = c.num_taggers;
+  p->G = c.grid_size;
+  p->T = c.episode_length;
+  const int64_t d2max = 2ll * int64_t(c.grid_size - 1) * int64_t(c.grid_size - 1);
+  p->tag_r2 = c.tag_r2 < 0 ? -1 : int32_t(std::min<int64_t>(c.tag_r2, d2max));  // beyond d2max everything is in range
+  p->tag_rad = c.tag_r2 < 0 ? 0 : isqrt64(p->tag_r2);
+  p->K = c.obs_mode == WD_OBS_PARTIAL ? c.obs_k : 0;
+  p->D = obs_dim(&c);
+  p->obs_mode = c.obs_mode;
+  p->env_offset = uint32_t(c.env_offset);
+  p->seed_lo = uint32_t(c.seed);
+  p->seed_hi = uint32_t(c.seed >> 32);
+  p->tag_reward = c.tag_reward;
+  p->tag_penalty = c.tag_penalty;
+  p->inv_G = float(1.0 / double(c.grid_size));
+  p->inv_T = float(1.0 / double(c.episode_length));
+  p->pos_x = b.pos_x;
+  p->pos_y = b.pos_y;
+  p->pos_x0 = b.pos_x0;
+  p->pos_y0 = b.pos_y0;
+  p->live = b.live;
+  p->action = b.action;
+  p->reward = b.reward;
+  p->obs = b.obs;
+  p->t = b.t;
+  p->done = b.done;
+  p->n_live_runners = b.n_live_runners;
+  p->tags_step = b.tags_step;
+  if (!plan_env_kernels(c, p)) return WD_E_UNSUPPORTED;
+  if (!wd::env_kernel_available(*p)) return WD_E_UNSUPPORTED;
+  return WD_OK;
+}
+
+int hip_failed(wd_handle* h, hipError_t err, const char* what) {
+  h->last_error = std::string(what) + ": " + hipGetErrorString(err);
+  return WD_E_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int wd_query_layout(const wd_config* cfg, wd_layout* out) {
+  if (!cfg || !out) return WD_E_NULL;
+  const int rc = check_config(cfg);
+  if (rc != WD_OK) return rc;
+  const int64_t E = cfg->num_envs, N = cfg->num_agents, D = obs_dim(cfg);
+  out->obs_dim = int32_t(D);
+  out->per_agent_elems = E * N;
+  out->obs_elems = E * N * D;
+  out->per_env_elems = E;
+  out->probs_elems = E * N * wd::kNumActions;
+  out->bytes_per_iteration = E * N * (4 * wd::kNumActions + 36 + 4 * D) + 24 * E;
+  return WD_OK;
+}
+
+int wd_create(const wd_config* cfg, const wd_buffers* bufs, wd_handle** out) {
+  if (!cfg || !bufs || !out) return WD_E_NULL;
+  *out = nullptr;
+  int rc = check_config(cfg);
+  if (rc != WD_OK) return rc;
+  const void* ptrs[] = {bufs->pos_x, bufs->pos_y, bufs->pos_x0, bufs->pos_y0, bufs->live, bufs->action,
+                        bufs->reward, bufs->obs, bufs->t, bufs->done, bufs->n_live_runners, bufs->tags_step};
+  for (const void* ptr : ptrs)
+    if (!ptr) return WD_E_NULL;
+  for (const void* ptr : ptrs)
+    if (!aligned256(ptr)) return WD_E_ALIGN;
+  wd::Params params;
+  rc = fill_params(*cfg, *bufs, &params);
+  if (rc != WD_OK) return rc;
+  wd_handle* h = new (std::nothrow) wd_handle();
+  if (!h) return WD_E_NULL;
+  h->cfg = *cfg;
+  h->bufs = *bufs;
+  h->params = params;
+  h->stream = static_cast<hipStream_t>(cfg->stream);
+  h->g = 0;
+  h->started = false;
+  *out = h;
+  return WD_OK;
+}
+
+int wd_reset(wd_handle* h, int mode) {
+  if (!h) return WD_E_NULL;
+  if (mode != WD_RESET_ALL && mode != WD_RESET_DONE) return WD_E_CONFIG;
+  if (mode == WD_RESET_DONE && !h->started) return WD_E_STATE;
+  hipError_t err;
+  if (mode == WD_RESET_ALL) {
+    if (!h->started) {
+      err = wd::prepare_env_kernels(h->params);
+      if (err != hipSuccess) return hip_failed(h, err, "kernel setup");
+    }
+    err = wd::launch_init_start_positions(h->params, h->stream);
+    if (err != hipSuccess) return hip_failed(h, err, "start-position kernel");
+    err = wd::launch_env_kernel(h->params, wd::kModeResetAll, nullptr, 0, h->stream);
+    if (err != hipSuccess) return hip_failed(h, err, "reset kernel");
+    h->g = 0;
+    h->started = true;
+    return WD_OK;
+  }
+  err = wd::launch_env_kernel(h->params, wd::kModeResetDone, nullptr, 0, h->stream);
+  if (err != hipSuccess) return hip_failed(h, err, "reset kernel");
+  return WD_OK;
+}
+
+int wd_sample(wd_handle* h, const float* probs) {
+  if (!h || !probs) return WD_E_NULL;
+  if (!aligned256(probs)) return WD_E_ALIGN;
+  if (!h->started) return WD_E_STATE;
+  const hipError_t err = wd::launch_sample(h->params, probs, h->g, h->stream);
+  if (err != hipSuccess) return hip_failed(h, err, "sample kernel");
+  return WD_OK;
+}
+
+int wd_step(wd_handle* h) {
+  if (!h) return WD_E_NULL;
+  if (!h->started) return WD_E_STATE;
+  const hipError_t err = wd::launch_env_kernel(h->params, wd::kModeStep, nullptr, h->g, h->stream);
+  if (err != hipSuccess) return hip_failed(h, err, "step kernel");
+  h->g += 1;
+  return WD_OK;
+}
+
+int wd_iterate(wd_handle* h, const float* probs) {
+  if (!h || !probs) return WD_E_NULL;
+  if (!aligned256(probs)) return WD_E_ALIGN;
+  if (!h->started) return WD_E_STATE;
+  const hipError_t err = wd::launch_env_kernel(h->params, wd::kModeIterate, probs, h->g, h->stream);
+  if (err != hipSuccess) return hip_failed(h, err, "iterate kernel");
+  h->g += 1;
+  return WD_OK;
+}
+
+int wd_get_step(wd_handle* h, uint64_t* g) {
+  if (!h || !g) return WD_E_NULL;
+  *g = h->g;
+  return WD_OK;
+}
+
+int wd_set_step(wd_handle* h, uint64_t g) {
+  if (!h) return WD_E_NULL;
+  h->g = g;
+  return WD_OK;
+}
+
+int wd_destroy(wd_handle* h) {
+  if (!h) return WD_E_NULL;
+  delete h;
+  return WD_OK;
+}
+
+const char* wd_strerror(int status) {
+  switch (status) {
+    case WD_OK: return "ok";
+    case WD_E_NULL: return "a required pointer is NULL";
+    case WD_E_CONFIG: return "configuration field out of range";
+    case WD_E_ALIGN: return "device buffer not 256-byte aligned";
+    case WD_E_STATE: return "call before the first wd_reset(WD_RESET_ALL)";
+    case WD_E_HIP: return "HIP call failed";
+    case WD_E_UNSUPPORTED: return "configuration not covered by this build's kernels";
+    default: return "unknown status";
+  }
+}
+
+const char* wd_last_error(wd_handle* h) { return h ? h->last_error.c_str() : ""; }
+
+}  // extern "C"

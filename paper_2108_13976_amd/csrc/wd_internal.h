@@ -1,0 +1,73 @@
+// wd_internal.h — shared between the host API (wd_api.hip) and the device code
+// (wd_kernels.hip) of libwd.  Nothing here is part of the public ABI.
+#ifndef WD_INTERNAL_H
+#define WD_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace wd {
+
+constexpr int kWorkgroupSize = 256;     // four wave64s
+constexpr int kWaveSize = 64;
+constexpr int kWavesPerWorkgroup = kWorkgroupSize / kWaveSize;
+constexpr int kNumActions = 5;
+constexpr int kMaxRegisterK = 8;        // K up to this keeps the candidate list in registers
+constexpr uint32_t kStreamAction = 0;   // random streams (fourth counter word)
+constexpr uint32_t kStreamInit = 1;
+
+// Exact unsigned division by a run-time constant (Granlund & Montgomery 1994):
+// q = (t + ((a - t) >> sh1)) >> sh2 with t = mulhi(a, mul).
+struct FastDiv {
+  uint32_t mul, sh1, sh2, div;
+};
+
+inline FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f;
+  f.div = d;
+  uint32_t l = 0;
+  while ((uint64_t(1) << l) < d) ++l;  // ceil(log2 d)
+  f.mul = uint32_t(((uint64_t(1) << 32) * ((uint64_t(1) << l) - d)) / d + 1);
+  f.sh1 = l < 1 ? l : 1;
+  f.sh2 = l == 0 ? 0 : l - 1;
+  return f;
+}
+
+// Everything a kernel needs: sizes, rule constants, launch geometry, LDS map, buffers.
+struct Params {
+  // sizes and rule constants
+  int32_t E, N, N_tag, G, T, tag_r2, tag_rad, K, D, obs_mode;
+  uint32_t env_offset, seed_lo, seed_hi;
+  float tag_reward, tag_penalty, inv_G, inv_T;
+  // geometry of the env-per-team kernels: a workgroup holds teams_per_wg teams of
+  // (1 << ts_log2) threads; a team owns one env; a thread owns apt agents of it
+  int32_t ts_log2, teams_per_wg, apt;
+  int32_t nb_cap;        // bucket slots per team (power of two, >= team size)
+  int32_t scan_chunk;    // nb_cap / team size
+  int32_t idx_bits;      // bits of an agent index inside a (distance, index) key
+  int32_t lambda_num, lambda_den;  // target live agents per bucket
+  FastDiv div_N;
+  // LDS map: byte offsets inside a team's region, the region stride, and the
+  // workgroup-level staging area behind all team regions
+  int32_t team_stride, off_pl, off_sorted, off_slot, off_best, off_credits, off_nbr,
+      off_counts, off_starts, off_misc, off_stage, lds_bytes;
+  // device buffers (borrowed from the caller)
+  int32_t *pos_x, *pos_y, *pos_x0, *pos_y0, *live, *action;
+  float* reward;
+  float* obs;
+  int32_t *t, *done, *n_live_runners, *tags_step;
+};
+
+enum EnvKernelMode { kModeStep = 0, kModeResetAll = 1, kModeResetDone = 2, kModeIterate = 3 };
+
+// Launchers (wd_kernels.hip).  Each enqueues on `stream` and returns the HIP status of the launch.
+hipError_t launch_sample(const Params& p, const float* probs, uint64_t g, hipStream_t stream);
+hipError_t launch_init_start_positions(const Params& p, hipStream_t stream);
+hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream);
+// One-time per-process setup of kernel attributes (dynamic LDS limit) for a plan.
+hipError_t prepare_env_kernels(const Params& p);
+// True if the env-per-team kernels were compiled for this (key width, K) combination.
+bool env_kernel_available(const Params& p);
+
+}  // namespace wd
+#endif  // WD_INTERNAL_H

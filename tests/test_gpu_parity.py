@@ -1,0 +1,240 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element, on
+the same seeded inputs: bit-exact on positions, actions, live/tag/done flags and counters,
+<= 1e-6 absolute on float32 rewards and observations."""
+import numpy as np
+import pytest
+
+import trace_runner
+from gpu_common import FLOAT_TOL, assert_equal_state, make_gpu, make_oracle, upload
+from invariants import check_obs_invariants, check_step_invariants
+from workloads import CONFIGS, probs_for_step
+
+pytestmark = pytest.mark.gpu
+
+
+# ---- hand traces through the C ABI ------------------------------------------------------------
+class GpuTraceEnv:
+    float_tol = FLOAT_TOL
+
+    def __init__(self, config):
+        import paper_2108_13976_amd as wd
+
+        c = dict(config)
+        self.wd = wd
+        self.env = wd.TagEnvs(1, c["num_agents"], c["num_taggers"], c["grid_size"], c["episode_length"],
+                              seed=0, tag_r2=c["tag_r2"], obs_k=c["obs_k"])
+        self.env.reset(wd.WD_RESET_ALL)
+
+    def set_start(self, start):
+        import torch
+
+        s = torch.tensor(start, dtype=torch.int32, device=self.env.device)
+        self.env.pos_x0[0] = s[:, 0]
+        self.env.pos_y0[0] = s[:, 1]
+        self.env.done[0] = 1
+        self.env.reset(self.wd.WD_RESET_DONE)
+
+    def step(self, actions):
+        import torch
+
+        self.env.action[0] = torch.tensor(actions, dtype=torch.int32, device=self.env.device)
+        self.env.step()
+
+    def reset_done(self):
+        self.env.reset(self.wd.WD_RESET_DONE)
+
+    def get(self, name):
+        return self.env.to_host()[name][0]
+
+
+TRACES = trace_runner.load_traces()
+
+
+@pytest.mark.parametrize("trace", TRACES, ids=[t["name"].split()[0] for t in TRACES])
+def test_hand_trace_on_gpu(trace):
+    trace_runner.run_trace(GpuTraceEnv, trace)
+
+
+# ---- lockstep roll-outs ---------------------------------------------------------------------------
+def lockstep(kw, steps, probs_seed, fused, env_lo=0, env_hi=None, full_envs=None, check_every=1, sharded=0):
+    """Run the GPU on envs [env_lo, env_hi) of a workload of ``full_envs`` envs next to the oracle."""
+    import paper_2108_13976_amd as wd
+    from oracle import tag_oracle
+
+    full_envs = full_envs or kw["num_envs"]
+    env_hi = kw["num_envs"] if env_hi is None else env_hi
+    sub = dict(kw, num_envs=env_hi - env_lo, env_offset=env_lo)
+    gpu = make_gpu(sub)
+    orc = make_oracle(sub)
+    gpu.reset(wd.WD_RESET_ALL)
+    if sharded:
+        tag_oracle.run_sharded(orc, lambda s: s.reset(), sharded)
+    else:
+        orc.reset()
+    assert_equal_state(gpu.to_host(), orc, "after reset(ALL)")
+    resets = 0
+    for g in range(steps):
+        probs = probs_for_step(probs_seed, g, full_envs, kw["num_agents"], env_lo, env_hi)
+        dprobs = upload(probs, gpu.device)
+        if fused:
+            gpu.iterate(dprobs)
+            if sharded:
+                tag_oracle.run_sharded(orc, lambda s: s.iterate(probs[s.cfg.env_offset - env_lo:s.cfg.env_offset - env_lo + s.E], g), sharded)
+            else:
+                orc.iterate(probs, g)
+            if g % check_every == 0 or g == steps - 1:
+                assert_equal_state(gpu.to_host(), orc, f"after iterate {g}")
+        else:
+            gpu.sample(dprobs)
+            orc.sample(probs, g)
+            assert_equal_state(gpu.to_host(), orc, f"after sample {g}", names=("action",))
+            gpu.step()
+            orc.step()
+            assert_equal_state(gpu.to_host(), orc, f"after step {g}")
+            resets += int(orc.done.sum())
+            gpu.reset(wd.WD_RESET_DONE)
+            orc.reset(tag_oracle.RESET_DONE)
+            assert_equal_state(gpu.to_host(), orc, f"after reset(DONE) {g}")
+        assert gpu.global_step == g + 1
+    gpu.close()
+    return resets
+
+
+def test_rollout_10x5_separate_calls():
+    cfg = CONFIGS["tag_10x5"]
+    resets = lockstep(cfg.kwargs(), 260, cfg.seed, fused=False)
+    assert resets >= 10
+
+
+def test_rollout_10x5_fused():
+    cfg = CONFIGS["tag_10x5"]
+    lockstep(cfg.kwargs(), 260, cfg.seed, fused=True)
+
+
+def test_rollout_100x50_separate_calls():
+    cfg = CONFIGS["tag_100x50"]
+    resets = lockstep(cfg.kwargs(), 150, cfg.seed, fused=False)
+    assert resets >= 1
+
+
+def test_rollout_100x50_fused_across_episode_ends():
+    cfg = CONFIGS["tag_100x50"]
+    lockstep(cfg.kwargs(), 2 * cfg.episode_length + 20, cfg.seed, fused=True, check_every=7)
+
+
+def test_rollout_2000x1000_env_slice():
+    """24 envs of the headline workload (global ids 1000..1023), separate calls, 40 steps."""
+    cfg = CONFIGS["tag_2000x1000"]
+    lockstep(cfg.kwargs(), 40, cfg.seed, fused=False, env_lo=1000, env_hi=1024, full_envs=cfg.num_envs)
+
+
+def test_rollout_20000x100_env_slice():
+    """300 envs (an odd count: the last workgroup is ragged) of the many-small-envs workload,
+    fused, across episode ends."""
+    cfg = CONFIGS["tag_20000x100"]
+    lockstep(cfg.kwargs(), 2 * cfg.episode_length + 10, cfg.seed, fused=True, env_lo=7001, env_hi=7302,
+             full_envs=cfg.num_envs, check_every=5, sharded=8)
+
+
+# ---- the headline workload at full size, in the launch configuration the benchmark times ----------
+def test_headline_workload_full_size_sampled_envs_and_invariants():
+    import paper_2108_13976_amd as wd
+    from oracle import tag_oracle
+
+    cfg = CONFIGS["tag_2000x1000"]
+    kw = cfg.kwargs()
+    gpu = make_gpu(kw)
+    gpu.reset(wd.WD_RESET_ALL)
+    rng = np.random.default_rng(5)
+    sample_envs = sorted(int(e) for e in rng.choice(cfg.num_envs, size=12, replace=False)) + [cfg.num_envs - 1]
+    oracles = {e: make_oracle(kw, e, e + 1) for e in sample_envs}
+    for o in oracles.values():
+        o.reset()
+    state = gpu.to_host()
+    for e, o in oracles.items():
+        assert_equal_state(state, o, f"reset env {e}", env_lo=e)
+    check_obs_invariants(cfg, state)
+    steps = 30
+    for g in range(steps):
+        probs = probs_for_step(cfg.seed, g, cfg.num_envs, cfg.num_agents)
+        before = state
+        gpu.iterate(upload(probs, gpu.device))
+        state = gpu.to_host()
+        for e, o in oracles.items():
+            o.iterate(probs[e:e + 1], g)
+            assert_equal_state(state, o, f"iterate {g} env {e}", env_lo=e)
+        if g % 10 == 0:
+            # no env of this workload can finish within 30 steps, so iterate == step here
+            assert (state["done"] == 0).all() and (state["t"] == g + 1).all()
+            check_step_invariants(cfg, before, state)
+    gpu.close()
+
+
+def test_two_runs_are_byte_identical():
+    import paper_2108_13976_amd as wd
+
+    cfg = CONFIGS["tag_100x50"]
+    runs = []
+    for _ in range(2):
+        gpu = make_gpu(cfg.kwargs())
+        gpu.reset(wd.WD_RESET_ALL)
+        for g in range(80):
+            gpu.iterate(upload(probs_for_step(cfg.seed, g, cfg.num_envs, cfg.num_agents), gpu.device))
+        runs.append(gpu.to_host())
+        gpu.close()
+    for n in runs[0]:
+        assert runs[0][n].tobytes() == runs[1][n].tobytes(), n
+
+
+def test_resume_from_saved_state_and_step_counter():
+    """All state lives in the caller's buffers plus the step counter: copying both resumes exactly."""
+    import paper_2108_13976_amd as wd
+
+    cfg = CONFIGS["tag_100x50"]
+    a = make_gpu(cfg.kwargs())
+    a.reset(wd.WD_RESET_ALL)
+    probs = [upload(probs_for_step(cfg.seed, g, cfg.num_envs, cfg.num_agents), a.device) for g in range(40)]
+    for g in range(20):
+        a.iterate(probs[g])
+    b = make_gpu(cfg.kwargs())
+    b.reset(wd.WD_RESET_ALL)
+    a.torch_stream.synchronize()
+    for n, ten in a.tensors.items():
+        b.tensors[n].copy_(ten)
+    b.global_step = a.global_step
+    for g in range(20, 40):
+        a.iterate(probs[g])
+        b.iterate(probs[g])
+    sa, sb = a.to_host(), b.to_host()
+    for n in sa:
+        assert sa[n].tobytes() == sb[n].tobytes(), n
+    a.close(), b.close()
+
+
+# ---- edge cases -------------------------------------------------------------------------------------
+EDGE = {
+    "two_agents": dict(num_envs=70, num_agents=2, num_taggers=1, grid_size=4, episode_length=9, obs_k=1),
+    "k_zero": dict(num_envs=33, num_agents=12, num_taggers=3, grid_size=7, episode_length=15, obs_k=0),
+    "k_three": dict(num_envs=9, num_agents=40, num_taggers=5, grid_size=13, episode_length=30, obs_k=3),
+    "k_eight": dict(num_envs=9, num_agents=40, num_taggers=5, grid_size=11, episode_length=30, obs_k=8),
+    "k_all_others": dict(num_envs=5, num_agents=14, num_taggers=4, grid_size=9, episode_length=25, obs_k=13),
+    "one_cell_grid": dict(num_envs=4, num_agents=6, num_taggers=2, grid_size=1, episode_length=5, obs_k=4),
+    "tagging_disabled": dict(num_envs=6, num_agents=30, num_taggers=6, grid_size=6, episode_length=12, obs_k=4, tag_r2=-1),
+    "whole_grid_in_range": dict(num_envs=6, num_agents=30, num_taggers=6, grid_size=9, episode_length=12, obs_k=4, tag_r2=10**9),
+    "wide_radius": dict(num_envs=6, num_agents=90, num_taggers=3, grid_size=40, episode_length=40, obs_k=4, tag_r2=50),
+    "sparse_big_grid": dict(num_envs=3, num_agents=20, num_taggers=2, grid_size=3000, episode_length=10, obs_k=4),
+    "wide_keys": dict(num_envs=3, num_agents=300, num_taggers=20, grid_size=20000, episode_length=10, obs_k=4, tag_r2=10**8),
+    "thousand_agents_dense": dict(num_envs=3, num_agents=1000, num_taggers=100, grid_size=12, episode_length=20, obs_k=4, tag_r2=0),
+    "thousand_twenty_four": dict(num_envs=2, num_agents=1024, num_taggers=1, grid_size=64, episode_length=8, obs_k=2),
+    "many_agents_one_team": dict(num_envs=2, num_agents=1500, num_taggers=50, grid_size=90, episode_length=8, obs_k=4),
+    "odd_rewards": dict(num_envs=12, num_agents=25, num_taggers=5, grid_size=8, episode_length=20, obs_k=2,
+                        tag_reward=0.3, tag_penalty=-2.5),
+}
+
+
+@pytest.mark.parametrize("name", list(EDGE))
+@pytest.mark.parametrize("fused", [False, True], ids=["separate", "fused"])
+def test_edge_case(name, fused):
+    kw = dict(seed=77, **EDGE[name])
+    steps = min(3 * kw["episode_length"], 60)
+    lockstep(kw, steps, 77, fused=fused)
