@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the Tag roll-out hot path on one MI355X.
+
+A "step" is one roll-out iteration of the whole batch: sample an action for every agent from
+its policy probabilities, advance every environment by one Tag step, reset the environments
+that finished (paper Sec. 4.5 items 3-6), all through libwd's C ABI.  The metric is the paper's
+(Sec. 5.3): environment steps per second at 2000 environments x 1000 agents; agent-steps/s and
+the fraction of the HBM roofline are reported next to it, and the CPU oracle is timed on the
+host cores as a baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--mode fused|separate]
+
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+RING = 8               # steps of policy outputs resident before the timed region
+PAPER_ENV_STEPS_PER_S = 2.9e6  # Sec. 5.3, one A100: context only
+
+
+def read_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch"):
+            return float(line.split()[1])
+    return None
+
+
+def run_iterations(env, ring, first_g, count, mode):
+    import paper_2108_13976_amd as wd
+
+    for k in range(count):
+        probs = ring[(first_g + k) % RING]
+        if mode == "fused":
+            env.iterate(probs)
+        else:
+            env.sample(probs)
+            env.step()
+            env.reset(wd.WD_RESET_DONE)
+
+
+def time_gpu(cfg, ring, steps, warmup, mode, **over):
+    """Returns (seconds for `steps` iterations by the host clock, same by HIP events, final state stats)."""
+    import torch
+    import paper_2108_13976_amd as wd
+
+    kw = cfg.kwargs()
+    kw.update(over)
+    env = wd.TagEnvs(device="cuda:0", **kw)
+    env.reset(wd.WD_RESET_ALL)
+    run_iterations(env, ring, 0, warmup, mode)
+    start_ev, end_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    start_ev.record(env.torch_stream)
+    run_iterations(env, ring, warmup, steps, mode)
+    end_ev.record(env.torch_stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    event_s = start_ev.elapsed_time(end_ev) / 1e3
+    stats = {
+        "live_fraction_at_end": float(env.live.float().mean().item()),
+        "mean_t_at_end": float(env.t.float().mean().item()),
+    }
+    bytes_per_iteration = env.layout.bytes_per_iteration
+    env.close()
+    return wall, event_s, stats, bytes_per_iteration
+
+
+def time_oracle(cfg, ring, envs_per_thread, iterations, threads):
+    """The oracle as it stands on a bounded slice of the same workload: the first envs, from the
+    reset state, the same probabilities.  Returns env-steps/s."""
+    import numpy as np
+    from oracle import tag_oracle
+
+    n_envs = envs_per_thread * threads
+    kw = cfg.kwargs()
+    kw["num_envs"] = n_envs
+    orc = tag_oracle.TagOracle(**kw)
+    host_probs = [ring[g % RING][:n_envs].cpu().numpy() for g in range(min(iterations, RING))]
+
+    def work(shard):
+        lo = shard.cfg.env_offset
+        shard.reset()
+        for g in range(iterations):
+            shard.iterate(np.ascontiguousarray(host_probs[g % len(host_probs)][lo:lo + shard.E]), g)
+
+    t0 = time.perf_counter()
+    used = tag_oracle.run_sharded(orc, work, threads)
+    dt = time.perf_counter() - t0
+    return n_envs * iterations / dt, used, dt
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--workload", default="tag_2000x1000")
+    ap.add_argument("--mode", choices=("fused", "separate"), default="fused")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; envs would shard across GPUs with no exchange, "
+              "but no multi-GPU figure is produced here (use --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2108_13976_amd as wd
+    from workloads import CONFIGS, device_probs_ring
+
+    wd.load_library()  # fails loudly if the HIP library has not been built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    cfg = CONFIGS[args.workload]
+    ring = device_probs_ring(cfg.seed, RING, cfg.num_envs, cfg.num_agents, "cuda:0")
+    torch.cuda.synchronize()
+
+    wall, event_s, stats, bytes_per_iteration = time_gpu(cfg, ring, args.steps, args.warmup, args.mode)
+    iters_per_s = args.steps / wall
+    env_steps = iters_per_s * cfg.num_envs
+    agent_steps = env_steps * cfg.num_agents
+    launch_s = event_s / args.steps  # average duration of one iteration on the launch stream
+    achieved_gbs = bytes_per_iteration / launch_s / 1e9
+    traffic = read_traffic(args.workload)
+
+    out = {
+        "metric": "env_steps_per_s",
+        "value": env_steps,
+        "unit": "env-steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": 1e3 * wall / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32 state, f32 rewards/observations",
+        "data": "synthetic",
+        "config": {
+            "workload": args.workload, "num_envs": cfg.num_envs, "num_agents": cfg.num_agents,
+            "num_taggers": cfg.num_taggers, "grid_size": cfg.grid_size, "episode_length": cfg.episode_length,
+            "obs": f"partial K={cfg.obs_k}", "tag_r2": cfg.tag_r2, "seed": cfg.seed, "mode": args.mode,
+            "probs": f"softmax(N(0,1)) float32, ring of {RING} steps resident in HBM",
+        },
+        "agent_steps_per_s": agent_steps,
+        "paper_env_steps_per_s_a100": PAPER_ENV_STEPS_PER_S,
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "env_kernel (sample + step + reset fused)" if args.mode == "fused" else "sample + step + reset kernels",
+            "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
+            "algorithmic_bytes_per_launch": bytes_per_iteration, "avg_launch_us": launch_s * 1e6,
+            "traffic": traffic,
+        },
+        "state_at_end": stats,
+    }
+
+    if not args.no_extras:
+        extras = {}
+        # worst case for the neighbour search: tagging disabled, every agent live in every step
+        w2, e2, _, _ = time_gpu(cfg, ring, min(args.steps, 300), 20, args.mode, tag_r2=-1)
+        extras["all_live_env_steps_per_s"] = min(args.steps, 300) / w2 * cfg.num_envs
+        extras["all_live_hbm_frac"] = bytes_per_iteration / (e2 / min(args.steps, 300)) / 1e9 / HBM_PEAK_GBS
+        other = "separate" if args.mode == "fused" else "fused"
+        w3, _, _, _ = time_gpu(cfg, ring, min(args.steps, 300), 20, other)
+        extras[f"{other}_env_steps_per_s"] = min(args.steps, 300) / w3 * cfg.num_envs
+        out["extras"] = extras
+
+    if not args.no_cpu_baseline:
+        threads = max(1, min(16, os.cpu_count() or 1))
+        iters = 40
+        # about 12 s of oracle work per thread (its cost grows with the square of the agent count)
+        per_thread = int(12.0 / (iters * 1e-9 * cfg.num_agents ** 2 + 1e-6))
+        per_thread = max(1, min(per_thread, cfg.num_envs // threads))
+        one, _, dt1 = time_oracle(cfg, ring, per_thread, iters, 1)
+        allc, used, dtn = time_oracle(cfg, ring, per_thread, iters, threads)
+        out["cpu_baseline"] = {
+            "value": allc, "unit": "env-steps/s", "cores": used, "kind": "oracle",
+            "sample": f"first {per_thread * used} envs of {args.workload} x {iters} iterations from the reset state, "
+                      f"one single-threaded oracle per core on disjoint envs ({dtn:.1f} s wall)",
+            "value_1core": one,
+            "sample_1core": f"first {per_thread} envs x {iters} iterations ({dt1:.1f} s)",
+            "gpu_over_cpu": env_steps / allc,
+        }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

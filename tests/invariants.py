@@ -6,7 +6,7 @@ tagged runners leave, one reward per tag, termination rule) and the observation 
 import numpy as np
 
 
-def check_step_invariants(cfg, before, after):
+def check_step_invariants(cfg, before, after, float_tol=0.0):
     """``before``/``after``: dicts of numpy arrays around ONE step (no reset in between).
     ``cfg``: object with num_agents, num_taggers, grid_size, episode_length, obs_k, tag_reward,
     tag_penalty."""
@@ -33,20 +33,23 @@ def check_step_invariants(cfg, before, after):
     assert (after["t"] <= T).all()
     want_done = (after["n_live_runners"] == 0) | (after["t"] >= T)
     assert np.array_equal(after["done"][stepped] == 1, want_done[stepped])
-    check_obs_invariants(cfg, after)
+    check_obs_invariants(cfg, after, float_tol)
 
 
-def check_obs_invariants(cfg, s):
+def check_obs_invariants(cfg, s, float_tol=0.0):
     """Observation rows against the state they were computed from (partial mode)."""
     N, n_tag, G, T, K = cfg.num_agents, cfg.num_taggers, cfg.grid_size, cfg.episode_length, cfg.obs_k
     obs = s["obs"]
     E = obs.shape[0]
     assert np.abs(obs).max() <= 1.0
-    assert np.array_equal(obs[..., 0], (s["pos_x"].astype(np.float32) / np.float32(G)))
-    assert np.array_equal(obs[..., 1], (s["pos_y"].astype(np.float32) / np.float32(G)))
+    def close(a, b):
+        return (np.abs(a.astype(np.float64) - b.astype(np.float64)) <= float_tol).all()
+
+    assert close(obs[..., 0], (s["pos_x"].astype(np.float32) / np.float32(G)))
+    assert close(obs[..., 1], (s["pos_y"].astype(np.float32) / np.float32(G)))
     assert np.array_equal(obs[..., 2], np.broadcast_to((np.arange(N) < n_tag).astype(np.float32), (E, N)))
     assert np.array_equal(obs[..., 3], s["live"].astype(np.float32))
-    assert np.array_equal(obs[..., 4], np.broadcast_to((s["t"].astype(np.float32) / np.float32(T))[:, None], (E, N)))
+    assert close(obs[..., 4], np.broadcast_to((s["t"].astype(np.float32) / np.float32(T))[:, None], (E, N)))
     if K == 0:
         return
     slots = obs[..., 5:].reshape(E, N, K, 4)
