@@ -17,7 +17,10 @@
  *  R4  sampling is by inverse CDF in float32, accumulated left to right, with a
  *      strict "u < c" test and the last action as the fall-through.
  *  R5  random numbers are Philox4x32-10 blocks, key = (seed lo, seed hi),
- *      counter = (env, agent, g lo, stream | g hi << 8).
+ *      counter = (env, index, g lo, stream | g hi << 8).  A block has four words: for
+ *      sampling (stream 0) the index is agent / 4 and agent i draws from word i mod 4,
+ *      so no word of a block is thrown away; for start positions (stream 1) the index
+ *      is the agent and words 0 and 1 give x and y.
  *  R6  an env whose done flag is set is not stepped at all.
  *  R7  actions: 0 stay, 1 up (y+1), 2 down (y-1), 3 left (x-1), 4 right (x+1);
  *      any other value is treated as stay.
@@ -129,11 +132,11 @@ void wdo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t ou
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// R5: how (seed, env, agent, step, stream) become key and counter.
-void wdo_random_block(uint64_t seed, uint32_t env, uint32_t agent, uint64_t g,
+// R5: how (seed, env, index, step, stream) become key and counter.
+void wdo_random_block(uint64_t seed, uint32_t env, uint32_t index, uint64_t g,
                       uint32_t stream, uint32_t out[4]) {
   const uint32_t key[2] = {uint32_t(seed), uint32_t(seed >> 32)};
-  const uint32_t ctr[4] = {env, agent, uint32_t(g),
+  const uint32_t ctr[4] = {env, index, uint32_t(g),
                            (stream & 0xFFu) | (uint32_t(g >> 32) << 8)};
   wdo_philox4x32_10(ctr, key, out);
 }
@@ -230,9 +233,9 @@ int wdo_sample(const wdo_config* c, const wdo_state* s, const float* probs, uint
   const int32_t E = c->num_envs, N = c->num_agents, A = 5;
   for (int32_t e = 0; e < E; ++e)
     for (int32_t i = 0; i < N; ++i) {
-      uint32_t w[4];
-      wdo_random_block(c->seed, uint32_t(c->env_offset + e), uint32_t(i), g, kStreamAction, w);
-      const float u = wdo_uniform_from_word(w[0]);
+      uint32_t w[4];  // R5: one block per four consecutive agents, one word each
+      wdo_random_block(c->seed, uint32_t(c->env_offset + e), uint32_t(i) / 4u, g, kStreamAction, w);
+      const float u = wdo_uniform_from_word(w[i % 4]);
       const int64_t a = int64_t(e) * N + i;
       s->action[a] = wdo_sample_from_u(probs + a * A, A, u);
     }

@@ -73,8 +73,9 @@ enum { WDO_RESET_ALL = 0, WDO_RESET_DONE = 1 };
 /* Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): one block. */
 void wdo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
 
-/* The four-word random block of (seed, global env, agent, step g, stream). */
-void wdo_random_block(uint64_t seed, uint32_t env, uint32_t agent, uint64_t g,
+/* The four-word random block of (seed, global env, index, step g, stream); index is
+ * agent / 4 for sampling (agent i uses word i mod 4) and the agent for start positions. */
+void wdo_random_block(uint64_t seed, uint32_t env, uint32_t index, uint64_t g,
                       uint32_t stream, uint32_t out[4]);
 
 /* Uniform in [0,1) from the top 24 bits of a word. */
@@ -90,8 +91,8 @@ int32_t wdo_obs_dim(const wdo_config* cfg);
  * state.  mode DONE: put only envs with done == 1 back in their start state. */
 int wdo_reset(const wdo_config* cfg, const wdo_state* st, int mode);
 
-/* action[e][i] <- categorical draw from probs[e][i][0..4] with the random block of
- * (seed, env_offset + e, i, g, stream 0); every agent of every env. */
+/* action[e][i] <- categorical draw from probs[e][i][0..4] with word i mod 4 of the random
+ * block of (seed, env_offset + e, i / 4, g, stream 0); every agent of every env. */
 int wdo_sample(const wdo_config* cfg, const wdo_state* st, const float* probs, uint64_t g);
 
 /* One Tag step for every env with done == 0 (envs with done == 1 are untouched). */

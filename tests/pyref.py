@@ -22,8 +22,8 @@ def philox4x32_10(ctr, key):
     return c
 
 
-def random_block(seed, env, agent, g, stream):
-    return philox4x32_10([env, agent, g & MASK, (stream & 0xFF) | ((g >> 32) << 8)], [seed & MASK, seed >> 32])
+def random_block(seed, env, index, g, stream):
+    return philox4x32_10([env, index, g & MASK, (stream & 0xFF) | ((g >> 32) << 8)], [seed & MASK, seed >> 32])
 
 
 def start_position(seed, env, agent, G):
@@ -32,8 +32,8 @@ def start_position(seed, env, agent, G):
 
 
 def sample_action(seed, env, agent, g, p):
-    w = random_block(seed, env, agent, g, 0)
-    u = np.float32(w[0] >> 8) * np.float32(2.0 ** -24)
+    w = random_block(seed, env, agent // 4, g, 0)  # four consecutive agents share a block
+    u = np.float32(w[agent % 4] >> 8) * np.float32(2.0 ** -24)
     c = np.float32(0.0)
     for a in range(len(p)):
         c = np.float32(c + np.float32(p[a]))
