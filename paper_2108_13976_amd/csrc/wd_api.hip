@@ -74,27 +74,39 @@ bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) 
 // Launch geometry and LDS map of the env-per-team kernels.  Returns false if an env does
 // not fit one workgroup's LDS.
 bool plan_env_kernels(const wd_config& c, wd::Params* p) {
-  const int N = c.num_agents;
+  const int N = c.num_agents, G = c.grid_size;
+  p->NG = (N + 3) / 4;
   int ts_log2 = 3;
-  while ((1 << ts_log2) < N && ts_log2 < 8) ++ts_log2;
+  while ((1 << ts_log2) < p->NG && ts_log2 < 8) ++ts_log2;
   const int ts = 1 << ts_log2;
   p->ts_log2 = ts_log2;
   p->teams_per_wg = wd::kWorkgroupSize / ts;
-  p->apt = (N + ts - 1) / ts;
-  uint32_t nb_cap = pow2_ceil(uint32_t(N));
+  p->gpt = (p->NG + ts - 1) / ts;
+  p->NPAD = 4 * ts * p->gpt;
+  p->vec4 = (N % 4 == 0) ? 1 : 0;
+  uint32_t nb_cap = pow2_ceil(uint32_t(N)) / 2;
   if (nb_cap > 4096u) nb_cap = 4096u;
   if (nb_cap < uint32_t(ts)) nb_cap = uint32_t(ts);
+  if (nb_cap < 16u) nb_cap = 16u;
   p->nb_cap = int32_t(nb_cap);
   p->scan_chunk = int32_t(nb_cap) / ts;
-  p->lambda_num = 3;
-  p->lambda_den = 1;
+  int shift_min = 0;
+  while (true) {
+    const int64_t nbx = (G + (1 << shift_min) - 1) >> shift_min;
+    if (nbx * nbx <= int64_t(nb_cap)) break;
+    ++shift_min;
+  }
+  p->shift_min = shift_min;
+  p->occupancy_need = 3.0f * float(G) * float(G);  // aim at >= 3 live agents per bucket
   p->div_N = wd::make_fastdiv(uint32_t(N));
+  p->div_NG = wd::make_fastdiv(uint32_t(p->NG));
 
-  // (distance, index) keys: 32 bits when they fit, else 64 (signalled by ~idx_bits)
-  const int idx_bits = bits_for(uint32_t(N - 1));
-  const uint64_t d2max = 2ull * uint64_t(c.grid_size - 1) * uint64_t(c.grid_size - 1);
-  const bool narrow = ((d2max + 1) << idx_bits) < (1ull << 32);
-  p->idx_bits = narrow ? idx_bits : ~idx_bits;
+  // (distance, index) keys and bucket entries: 32 bits when they fit, else 64
+  p->idx_bits = bits_for(uint32_t(N - 1));
+  p->xy_bits = bits_for(uint32_t(G - 1));
+  const uint64_t d2max = 2ull * uint64_t(G - 1) * uint64_t(G - 1);
+  const bool narrow = (1 + 2 * p->xy_bits + p->idx_bits <= 32) && (((d2max + 1) << p->idx_bits) < (1ull << 32));
+  p->wide = narrow ? 0 : 1;
   const int key_bytes = narrow ? 4 : 8;
   const bool register_path = p->K <= wd::kMaxRegisterK;
 
@@ -104,20 +116,24 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p) {
     off = align16(off + bytes);
     return int32_t(at);
   };
-  p->off_pl = take(4ll * N);
-  p->off_sorted = take(8ll * N);
-  p->off_slot = take(2ll * N);
-  p->off_best = take(int64_t(key_bytes) * N);
+  const int64_t NPAD = p->NPAD;
+  p->off_pl = take(4 * NPAD);
+  p->off_nbr = take(register_path ? 2 * NPAD * p->K : 0);
+  p->off_misc = take(32);
+  p->keep_stride = int32_t(off);
+  off = 0;
+  p->off_sorted = take(key_bytes * NPAD);
+  p->off_slot = take(2 * NPAD);
+  p->off_best = take(key_bytes * NPAD);
   p->off_credits = take(4ll * c.num_taggers);
-  p->off_nbr = take(register_path ? 2ll * N * p->K : 0);
   p->off_counts = take(4ll * nb_cap);
   p->off_starts = take(4ll * (nb_cap + 4));
-  p->off_misc = take(32);
-  p->team_stride = int32_t(off);
-  const int64_t stage = register_path ? int64_t(wd::kWorkgroupSize) * p->D * 4 : 0;
-  const int64_t total = int64_t(p->team_stride) * p->teams_per_wg + stage;
-  p->off_stage = p->team_stride * p->teams_per_wg;
-  p->lds_bytes = int32_t(total);
+  p->scratch_stride = int32_t(off);
+  p->scratch_base = p->keep_stride * p->teams_per_wg;
+  const int64_t stage = register_path ? int64_t(wd::kWavesPerWorkgroup) * wd::kStageRows * p->D * 4 : 0;
+  const int64_t scratch = std::max<int64_t>(int64_t(p->scratch_stride) * p->teams_per_wg, stage);
+  const int64_t total = p->scratch_base + scratch;
+  p->lds_bytes = int32_t(std::min<int64_t>(total, INT32_MAX));
   return total <= kLdsLimitBytes;
 }
 

@@ -13,7 +13,8 @@ constexpr int kWaveSize = 64;
 constexpr int kWavesPerWorkgroup = kWorkgroupSize / kWaveSize;
 constexpr int kNumActions = 5;
 constexpr int kMaxRegisterK = 8;        // K up to this keeps the candidate list in registers
-constexpr uint32_t kStreamAction = 0;   // random streams (fourth counter word)
+constexpr int kStageRows = 32;          // rows a wave transposes through LDS per flush
+constexpr uint32_t kStreamAction = 0;   // random streams (low byte of the fourth counter word)
 constexpr uint32_t kStreamInit = 1;
 
 // Exact unsigned division by a run-time constant (Granlund & Montgomery 1994):
@@ -39,18 +40,27 @@ struct Params {
   int32_t E, N, N_tag, G, T, tag_r2, tag_rad, K, D, obs_mode;
   uint32_t env_offset, seed_lo, seed_hi;
   float tag_reward, tag_penalty, inv_G, inv_T;
-  // geometry of the env-per-team kernels: a workgroup holds teams_per_wg teams of
-  // (1 << ts_log2) threads; a team owns one env; a thread owns apt agents of it
-  int32_t ts_log2, teams_per_wg, apt;
+  // Geometry of the env-per-team kernels.  Agents are handled in groups of four
+  // consecutive indices (one 16-byte load per array, one random block per group).  A
+  // workgroup holds teams_per_wg teams of (1 << ts_log2) threads; a team owns one env;
+  // thread lt of a team owns groups lt, lt + ts, ... (gpt of them).
+  int32_t NG;            // groups per env = ceil(N / 4)
+  int32_t NPAD;          // 4 * ts * gpt >= N: per-agent LDS arrays are padded to this
+  int32_t ts_log2, teams_per_wg, gpt;
+  int32_t vec4;          // N % 4 == 0: a group's global slices are 16-byte aligned
   int32_t nb_cap;        // bucket slots per team (power of two, >= team size)
   int32_t scan_chunk;    // nb_cap / team size
-  int32_t idx_bits;      // bits of an agent index inside a (distance, index) key
-  int32_t lambda_num, lambda_den;  // target live agents per bucket
-  FastDiv div_N;
-  // LDS map: byte offsets inside a team's region, the region stride, and the
-  // workgroup-level staging area behind all team regions
-  int32_t team_stride, off_pl, off_sorted, off_slot, off_best, off_credits, off_nbr,
-      off_counts, off_starts, off_misc, off_stage, lds_bytes;
+  int32_t shift_min;     // smallest bucket shift whose table fits nb_cap
+  float occupancy_need;  // lambda * G * G: shift grows until n_live * 4^shift reaches it
+  // (distance, index) keys and bucket entries: 32-bit when wide == 0
+  int32_t wide, idx_bits, xy_bits;
+  FastDiv div_N, div_NG;
+  // LDS map.  Per team a persistent part (positions, neighbour lists, scalars) and a
+  // scratch part (sort and tag tables) that the row staging area overlays once the
+  // neighbour search is done.
+  int32_t keep_stride, off_pl, off_nbr, off_misc;
+  int32_t scratch_base, scratch_stride, off_sorted, off_slot, off_best, off_credits, off_counts, off_starts;
+  int32_t lds_bytes;
   // device buffers (borrowed from the caller)
   int32_t *pos_x, *pos_y, *pos_x0, *pos_y0, *live, *action;
   float* reward;
@@ -66,7 +76,7 @@ hipError_t launch_init_start_positions(const Params& p, hipStream_t stream);
 hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream);
 // One-time per-process setup of kernel attributes (dynamic LDS limit) for a plan.
 hipError_t prepare_env_kernels(const Params& p);
-// True if the env-per-team kernels were compiled for this (key width, K) combination.
+// True if the env-per-team kernels cover this configuration.
 bool env_kernel_available(const Params& p);
 
 }  // namespace wd

@@ -4,16 +4,19 @@
 // kernels of the service layer, step kernel of the environment; Sec. 4.5 items 3-6),
 // for the discrete Tag rules of Sec. 5.1.  The paper maps one thread block to an env
 // and one thread to an agent; here a TEAM of 8..256 threads owns an env (several small
-// envs share a 256-thread workgroup, a thread owns several agents of a large env), the
-// env's positions are staged in LDS, the pairwise passes (tag check, K-nearest search)
-// run over a bucket-sorted copy of the live agents instead of over all pairs, and
-// observation rows leave through an LDS transpose so that HBM sees whole lines.
+// envs share a 256-thread workgroup), a thread owns groups of four consecutive agents
+// (16-byte loads and stores, one random block per group), the env's positions are staged
+// in LDS, the pairwise passes (tag check, K-nearest search) run over a bucket-sorted copy
+// of the live agents instead of over all pairs, and observation rows leave through an LDS
+// transpose so that HBM sees whole lines.
+#include <type_traits>
+
 #include "wd_internal.h"
 
 namespace wd {
 namespace {
 
-constexpr uint32_t kDeadBit = 0x80000000u;  // in a packed position: agent is out of play
+constexpr uint32_t kDeadBit = 0x80000000u;  // in a packed position or entry: agent is out of play
 constexpr uint32_t kNoNeighbour = 0xFFFFu;
 
 // ----------------------------------------------------------------------------------
@@ -21,7 +24,7 @@ constexpr uint32_t kNoNeighbour = 0xFFFFu;
 // two 32x32->64 multiplies and a word permutation, the key bumped by Weyl constants.
 // ----------------------------------------------------------------------------------
 struct Block4 {
-  uint32_t w0, w1, w2, w3;
+  uint32_t w[4];
 };
 
 __device__ __forceinline__ Block4 philox_block(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
@@ -37,13 +40,15 @@ __device__ __forceinline__ Block4 philox_block(uint32_t c0, uint32_t c1, uint32_
     k0 += 0x9E3779B9u;
     k1 += 0xBB67AE85u;
   }
-  return Block4{c0, c1, c2, c3};
+  return Block4{{c0, c1, c2, c3}};
 }
 
-// Counter layout: (global env id, agent, g low word, stream | g high word << 8).
-__device__ __forceinline__ Block4 random_block(const Params& p, uint32_t env_local, uint32_t agent,
+// Counter layout: (global env id, index, g low word, stream | g high word << 8).  For
+// sampling the index is the group (agent / 4) and agent i takes word i mod 4; for start
+// positions the index is the agent and words 0, 1 give x, y.
+__device__ __forceinline__ Block4 random_block(const Params& p, uint32_t env_local, uint32_t index,
                                                uint32_t g_lo, uint32_t g_hi, uint32_t stream) {
-  return philox_block(p.env_offset + env_local, agent, g_lo, stream | (g_hi << 8), p.seed_lo, p.seed_hi);
+  return philox_block(p.env_offset + env_local, index, g_lo, stream | (g_hi << 8), p.seed_lo, p.seed_hi);
 }
 
 __device__ __forceinline__ uint32_t fastdiv(uint32_t a, const FastDiv& f) {
@@ -52,27 +57,88 @@ __device__ __forceinline__ uint32_t fastdiv(uint32_t a, const FastDiv& f) {
 }
 
 // Inverse-CDF draw: float32 running sum left to right, strict "<", last action as fall-through.
-__device__ __forceinline__ int32_t sample_action(const float* __restrict__ pr, uint32_t word) {
+__device__ __forceinline__ int32_t sample_action(float p0, float p1, float p2, float p3, uint32_t word) {
   const float u = static_cast<float>(word >> 8) * (1.0f / 16777216.0f);
-  const float c0 = 0.0f + pr[0];
-  const float c1 = c0 + pr[1];
-  const float c2 = c1 + pr[2];
-  const float c3 = c2 + pr[3];
+  const float c0 = 0.0f + p0;
+  const float c1 = c0 + p1;
+  const float c2 = c1 + p2;
+  const float c3 = c2 + p3;
   return (u < c0) ? 0 : (u < c1) ? 1 : (u < c2) ? 2 : (u < c3) ? 3 : 4;
 }
 
+// Actions of the four agents of a group from their 20 probabilities and one random block.
+// a0 = flat index of the group's first agent, n = how many of the four agents exist.
+__device__ __forceinline__ void sample_group(const float* __restrict__ probs, int64_t a0, int n, bool vec,
+                                             const Block4& r, int act[4]) {
+  float f[20];
+  if (vec) {
+    const float4* src = reinterpret_cast<const float4*>(probs + a0 * kNumActions);
+#pragma unroll
+    for (int q = 0; q < 5; ++q) {
+      const float4 v = src[q];
+      f[4 * q + 0] = v.x;
+      f[4 * q + 1] = v.y;
+      f[4 * q + 2] = v.z;
+      f[4 * q + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int q = 0; q < 20; ++q) f[q] = (q < n * kNumActions) ? probs[a0 * kNumActions + q] : 0.0f;
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) act[j] = sample_action(f[5 * j], f[5 * j + 1], f[5 * j + 2], f[5 * j + 3], r.w[j]);
+}
+
+__device__ __forceinline__ void load4(const int32_t* __restrict__ src, int64_t a0, int n, bool vec, int v[4]) {
+  if (vec) {
+    const int4 q = *reinterpret_cast<const int4*>(src + a0);
+    v[0] = q.x;
+    v[1] = q.y;
+    v[2] = q.z;
+    v[3] = q.w;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = j < n ? src[a0 + j] : 0;
+  }
+}
+
+__device__ __forceinline__ void store4(int32_t* __restrict__ dst, int64_t a0, int n, bool vec, const int v[4]) {
+  if (vec) {
+    *reinterpret_cast<int4*>(dst + a0) = make_int4(v[0], v[1], v[2], v[3]);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (j < n) dst[a0 + j] = v[j];
+  }
+}
+
+__device__ __forceinline__ void store4(float* __restrict__ dst, int64_t a0, int n, bool vec, const float v[4]) {
+  if (vec) {
+    *reinterpret_cast<float4*>(dst + a0) = make_float4(v[0], v[1], v[2], v[3]);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (j < n) dst[a0 + j] = v[j];
+  }
+}
+
 // ----------------------------------------------------------------------------------
-// Flat per-agent kernels
+// Flat kernels: the separately callable sampler (one thread per group of four agents)
+// and the start positions (one thread per agent)
 // ----------------------------------------------------------------------------------
 __global__ __launch_bounds__(kWorkgroupSize) void sample_kernel(const Params p, const float* __restrict__ probs,
                                                                 uint32_t g_lo, uint32_t g_hi) {
-  const int64_t total = int64_t(p.E) * p.N;
-  const int64_t a = int64_t(blockIdx.x) * kWorkgroupSize + threadIdx.x;
-  if (a >= total) return;
-  const uint32_t e = fastdiv(uint32_t(a), p.div_N);
-  const uint32_t i = uint32_t(a) - e * uint32_t(p.N);
-  const Block4 r = random_block(p, e, i, g_lo, g_hi, kStreamAction);
-  p.action[a] = sample_action(probs + a * kNumActions, r.w0);
+  const int64_t total = int64_t(p.E) * p.NG;
+  const int64_t gid = int64_t(blockIdx.x) * kWorkgroupSize + threadIdx.x;
+  if (gid >= total) return;
+  const uint32_t e = fastdiv(uint32_t(gid), p.div_NG);
+  const uint32_t grp = uint32_t(gid) - e * uint32_t(p.NG);
+  const int i0 = int(grp) * 4;
+  const int64_t a0 = int64_t(e) * p.N + i0;
+  const Block4 r = random_block(p, e, grp, g_lo, g_hi, kStreamAction);
+  int act[4];
+  sample_group(probs, a0, min(4, p.N - i0), p.vec4 != 0, r, act);
+  store4(p.action, a0, min(4, p.N - i0), p.vec4 != 0, act);
 }
 
 __global__ __launch_bounds__(kWorkgroupSize) void init_start_positions_kernel(const Params p) {
@@ -82,17 +148,67 @@ __global__ __launch_bounds__(kWorkgroupSize) void init_start_positions_kernel(co
   const uint32_t e = fastdiv(uint32_t(a), p.div_N);
   const uint32_t i = uint32_t(a) - e * uint32_t(p.N);
   const Block4 r = random_block(p, e, i, 0u, 0u, kStreamInit);
-  p.pos_x0[a] = int32_t(__umulhi(r.w0, uint32_t(p.G)));
-  p.pos_y0[a] = int32_t(__umulhi(r.w1, uint32_t(p.G)));
+  p.pos_x0[a] = int32_t(__umulhi(r.w[0], uint32_t(p.G)));
+  p.pos_y0[a] = int32_t(__umulhi(r.w[1], uint32_t(p.G)));
 }
+
+// ----------------------------------------------------------------------------------
+// Keys and bucket entries.  A key is (squared distance << idx_bits) | agent index, so
+// unsigned comparison orders by distance first and index second.  A bucket entry holds
+// a live agent's position and index.  Both are 32-bit when the grid and agent count
+// allow (NARROW), else 64-bit (WIDE).
+// ----------------------------------------------------------------------------------
+struct Bits {
+  int ib, xb;             // bits of an agent index, bits of a coordinate
+  uint32_t imask, xmask;
+};
+
+template <bool WIDE>
+struct Rep;
+
+template <>
+struct Rep<false> {
+  using Key = uint32_t;
+  using Entry = uint32_t;
+  static __device__ __forceinline__ Entry make(int x, int y, int i, const Bits& b) {
+    return uint32_t(i) | (uint32_t(x) << b.ib) | (uint32_t(y) << (b.ib + b.xb));
+  }
+  static __device__ __forceinline__ int x(Entry e, const Bits& b) { return int((e >> b.ib) & b.xmask); }
+  static __device__ __forceinline__ int y(Entry e, const Bits& b) { return int((e >> (b.ib + b.xb)) & b.xmask); }
+  static __device__ __forceinline__ uint32_t idx(Entry e, const Bits& b) { return e & b.imask; }
+  static __device__ __forceinline__ bool dead(Entry e) { return (e & kDeadBit) != 0; }
+  static __device__ __forceinline__ void mark_dead(Entry* e) { *e |= kDeadBit; }
+};
+
+template <>
+struct Rep<true> {
+  using Key = unsigned long long;
+  using Entry = uint2;
+  static __device__ __forceinline__ Entry make(int x, int y, int i, const Bits&) {
+    return make_uint2(uint32_t(x) | (uint32_t(y) << 16), uint32_t(i));
+  }
+  static __device__ __forceinline__ int x(Entry e, const Bits&) { return int(e.x & 0x7FFFu); }
+  static __device__ __forceinline__ int y(Entry e, const Bits&) { return int((e.x >> 16) & 0x7FFFu); }
+  static __device__ __forceinline__ uint32_t idx(Entry e, const Bits&) { return e.y; }
+  static __device__ __forceinline__ bool dead(Entry e) { return (e.x & kDeadBit) != 0; }
+  static __device__ __forceinline__ void mark_dead(Entry* e) { e->x |= kDeadBit; }
+};
+
+template <typename Key>
+__device__ __forceinline__ Key key_none() {
+  return ~Key(0);
+}
+
+// Positions by agent index: x | y << 16 | dead bit.
+__device__ __forceinline__ uint32_t pack_pos(int x, int y, bool is_live) {
+  return uint32_t(x) | (uint32_t(y) << 16) | (is_live ? 0u : kDeadBit);
+}
+__device__ __forceinline__ int pos_x_of(uint32_t pl) { return int(pl & 0x7FFFu); }
+__device__ __forceinline__ int pos_y_of(uint32_t pl) { return int((pl >> 16) & 0x7FFFu); }
 
 // ----------------------------------------------------------------------------------
 // Team helpers
 // ----------------------------------------------------------------------------------
-template <typename KeyT>
-struct KeyLimits {
-  static constexpr KeyT kNone = ~KeyT(0);
-};
 
 // Exclusive prefix sum of one value per thread across a team of (1 << ts_log2) threads.
 // Teams of up to one wave use lane shuffles; larger teams add per-wave totals through LDS
@@ -130,16 +246,15 @@ struct Buckets {
   int nbx;    // buckets per grid side
 };
 
-// Bucket width for `n_live` agents on a G x G grid: the smallest power of two that keeps
-// the bucket count within nb_cap and the mean occupancy at or above lambda.  Any choice
-// gives the same results; this one only trades search rings against candidates per ring.
+// Bucket width for n_live agents on the grid: the smallest power of two that fits the
+// bucket table and keeps the mean occupancy near the target.  Any choice gives the same
+// results; it only trades search rings against candidates per ring.
 __device__ __forceinline__ Buckets choose_buckets(const Params& p, int n_live) {
-  int s = 0;
-  for (; s < 15; ++s) {
-    const int64_t nbx = (p.G + (1 << s) - 1) >> s;
-    if (nbx * nbx <= p.nb_cap &&
-        (int64_t(n_live) << (2 * s)) * p.lambda_den >= int64_t(p.lambda_num) * p.G * p.G)
-      break;
+  int s = p.shift_min;
+  float have = static_cast<float>(n_live) * static_cast<float>(1 << (2 * s));
+  while (s < 15 && have < p.occupancy_need) {
+    ++s;
+    have *= 4.0f;
   }
   Buckets b;
   b.shift = s;
@@ -147,53 +262,45 @@ __device__ __forceinline__ Buckets choose_buckets(const Params& p, int n_live) {
   return b;
 }
 
-__device__ __forceinline__ uint32_t pack_pos(int x, int y, bool is_live) {
-  return uint32_t(x) | (uint32_t(y) << 16) | (is_live ? 0u : kDeadBit);
+__device__ __forceinline__ int bucket_of(int x, int y, const Buckets bk) {
+  return (y >> bk.shift) * bk.nbx + (x >> bk.shift);
 }
-__device__ __forceinline__ int pos_x_of(uint32_t pl) { return int(pl & 0x7FFFu); }
-__device__ __forceinline__ int pos_y_of(uint32_t pl) { return int((pl >> 16) & 0x7FFFu); }
 
-// LDS views of one team's region.
-template <typename KeyT>
+// LDS views of one team's regions.
+template <bool WIDE>
 struct TeamLds {
-  uint32_t* pl;       // [N] packed position + dead bit, by agent index
-  uint2* sorted;      // [N] (packed position, agent index) of live agents, grouped by bucket
-  uint16_t* slot;     // [N] where agent i sits in `sorted`
-  KeyT* best;         // [N] per runner: smallest (distance, tagger) key in range
-  int32_t* credits;   // [N_tag]
-  uint16_t* nbr;      // [N][K] neighbour indices
-  uint32_t* counts;   // [nb_cap] bucket counts, then scatter cursors
-  uint32_t* starts;   // [nb_cap + 1] bucket start offsets in `sorted`
-  int32_t* misc;      // [0] tags this step, [1] t after the call, [2] rows to be written, [4..7] scan scratch
-  __device__ __forceinline__ TeamLds(unsigned char* base, const Params& p)
-      : pl(reinterpret_cast<uint32_t*>(base + p.off_pl)),
-        sorted(reinterpret_cast<uint2*>(base + p.off_sorted)),
-        slot(reinterpret_cast<uint16_t*>(base + p.off_slot)),
-        best(reinterpret_cast<KeyT*>(base + p.off_best)),
-        credits(reinterpret_cast<int32_t*>(base + p.off_credits)),
-        nbr(reinterpret_cast<uint16_t*>(base + p.off_nbr)),
-        counts(reinterpret_cast<uint32_t*>(base + p.off_counts)),
-        starts(reinterpret_cast<uint32_t*>(base + p.off_starts)),
-        misc(reinterpret_cast<int32_t*>(base + p.off_misc)) {}
+  using Key = typename Rep<WIDE>::Key;
+  using Entry = typename Rep<WIDE>::Entry;
+  uint32_t* pl;      // [NPAD] packed position + dead bit, by agent index
+  uint16_t* nbr;     // [NPAD][K] neighbour indices
+  int32_t* misc;     // [0] tags this step, [1] t after the call, [2] rows to be written, [4..7] scan scratch
+  Entry* sorted;     // [NPAD] entries of the live agents, grouped by bucket
+  uint16_t* slot;    // [NPAD] where agent i sits in `sorted`
+  Key* best;         // [NPAD] per runner: smallest (distance, tagger) key in range
+  int32_t* credits;  // [N_tag]
+  uint32_t* counts;  // [nb_cap] bucket counts, then scatter cursors
+  uint32_t* starts;  // [nb_cap + 1] bucket start offsets in `sorted`
+  __device__ __forceinline__ TeamLds(unsigned char* smem, int team, const Params& p) {
+    unsigned char* keep = smem + team * p.keep_stride;
+    unsigned char* scr = smem + p.scratch_base + team * p.scratch_stride;
+    pl = reinterpret_cast<uint32_t*>(keep + p.off_pl);
+    nbr = reinterpret_cast<uint16_t*>(keep + p.off_nbr);
+    misc = reinterpret_cast<int32_t*>(keep + p.off_misc);
+    sorted = reinterpret_cast<Entry*>(scr + p.off_sorted);
+    slot = reinterpret_cast<uint16_t*>(scr + p.off_slot);
+    best = reinterpret_cast<Key*>(scr + p.off_best);
+    credits = reinterpret_cast<int32_t*>(scr + p.off_credits);
+    counts = reinterpret_cast<uint32_t*>(scr + p.off_counts);
+    starts = reinterpret_cast<uint32_t*>(scr + p.off_starts);
+  }
 };
 
-// Counting sort of the team's live agents by bucket: counts -> starts -> sorted/slot.
-// `act` marks teams that take part; every thread of the workgroup must call (barriers inside).
-// Requires pl[] written and counts[] zeroed before the call (and a barrier after that).
-template <typename KeyT>
-__device__ __forceinline__ void build_buckets(const Params& p, const TeamLds<KeyT>& L, bool act, int lt, int ts,
-                                              const Buckets bk) {
-  if (act) {
-    for (int k = 0; k < p.apt; ++k) {
-      const int i = lt + k * ts;
-      if (i < p.N) {
-        const uint32_t v = L.pl[i];
-        if (!(v & kDeadBit))
-          atomicAdd(&L.counts[(pos_y_of(v) >> bk.shift) * bk.nbx + (pos_x_of(v) >> bk.shift)], 1u);
-      }
-    }
-  }
-  __syncthreads();
+// Second half of the counting sort: bucket counts -> start offsets -> entries in bucket
+// order.  `act` marks teams that take part; every thread of the workgroup must call
+// (barriers inside).  Requires pl[] written and counts[] filled, and a barrier after that.
+template <bool WIDE>
+__device__ __forceinline__ void scan_and_scatter(const Params& p, const TeamLds<WIDE>& L, bool act, int lt, int ts,
+                                                 const Buckets bk, const Bits& bits) {
   int part = 0;
   const int j0 = lt * p.scan_chunk;
   if (act)
@@ -211,15 +318,19 @@ __device__ __forceinline__ void build_buckets(const Params& p, const TeamLds<Key
   }
   __syncthreads();
   if (act) {
-    for (int k = 0; k < p.apt; ++k) {
-      const int i = lt + k * ts;
-      if (i < p.N) {
-        const uint32_t v = L.pl[i];
-        if (!(v & kDeadBit)) {
-          const uint32_t at =
-              atomicAdd(&L.counts[(pos_y_of(v) >> bk.shift) * bk.nbx + (pos_x_of(v) >> bk.shift)], 1u);
-          L.sorted[at] = make_uint2(v, uint32_t(i));
-          L.slot[i] = uint16_t(at);
+    for (int k = 0; k < p.gpt; ++k) {
+      const int i0 = 4 * (lt + k * ts);
+      if (i0 < p.N) {
+        const uint4 v4 = *reinterpret_cast<const uint4*>(L.pl + i0);
+        const uint32_t v[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (!(v[j] & kDeadBit)) {
+            const int x = pos_x_of(v[j]), y = pos_y_of(v[j]);
+            const uint32_t at = atomicAdd(&L.counts[bucket_of(x, y, bk)], 1u);
+            L.sorted[at] = Rep<WIDE>::make(x, y, i0 + j, bits);
+            L.slot[i0 + j] = uint16_t(at);
+          }
         }
       }
     }
@@ -227,12 +338,25 @@ __device__ __forceinline__ void build_buckets(const Params& p, const TeamLds<Key
   __syncthreads();
 }
 
+__device__ __forceinline__ uint32_t med3(uint32_t a, uint32_t b, uint32_t c) {
+  uint32_t r;
+  asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 // Sorted insertion of `key` into an ascending list of KT keys (the largest falls off).
-template <typename KeyT, int KT>
-__device__ __forceinline__ void insert_key(KeyT (&keys)[KT], KeyT key) {
+template <int KT>
+__device__ __forceinline__ void insert_key(uint32_t (&keys)[KT], uint32_t key) {
+#pragma unroll
+  for (int k = KT - 1; k >= 1; --k) keys[k] = med3(keys[k - 1], keys[k], key);  // clamp key into [k-1, k]
+  keys[0] = keys[0] < key ? keys[0] : key;
+}
+
+template <int KT>
+__device__ __forceinline__ void insert_key(unsigned long long (&keys)[KT], unsigned long long key) {
 #pragma unroll
   for (int k = KT - 1; k >= 1; --k) {
-    const KeyT hi = keys[k - 1] > key ? keys[k - 1] : key;
+    const unsigned long long hi = keys[k - 1] > key ? keys[k - 1] : key;
     keys[k] = keys[k] < hi ? keys[k] : hi;
   }
   keys[0] = keys[0] < key ? keys[0] : key;
@@ -243,42 +367,85 @@ __device__ __forceinline__ void insert_key(KeyT (&keys)[KT], KeyT key) {
 // farther than r bucket widths in x or in y, so once the K-th key is below (r*B+1)^2 (or
 // the block covers the grid) no unseen agent can enter the list; otherwise r doubles and
 // the scan restarts.
-template <typename KeyT, int KT>
-__device__ __forceinline__ void nearest_keys(KeyT (&keys)[KT], int K, int x, int y, uint32_t self_slot,
-                                             const Buckets bk, int idx_bits, const uint2* sorted,
-                                             const uint32_t* starts) {
+template <bool WIDE, int KT>
+__device__ __forceinline__ void nearest_keys(typename Rep<WIDE>::Key (&keys)[KT], int K, int x, int y,
+                                             uint32_t self_slot, const Buckets bk, const Bits& bits,
+                                             const typename Rep<WIDE>::Entry* sorted, const uint32_t* starts) {
+  using Key = typename Rep<WIDE>::Key;
   const int bx = x >> bk.shift, by = y >> bk.shift, last = bk.nbx - 1;
   for (int r = 1;; r *= 2) {
 #pragma unroll
-    for (int k = 0; k < KT; ++k) keys[k] = KeyLimits<KeyT>::kNone;
+    for (int k = 0; k < KT; ++k) keys[k] = key_none<Key>();
     const int x0 = max(bx - r, 0), x1 = min(bx + r, last);
     const int y0 = max(by - r, 0), y1 = min(by + r, last);
     for (int row = y0; row <= y1; ++row) {
       const uint32_t q_end = starts[row * bk.nbx + x1 + 1];
       for (uint32_t q = starts[row * bk.nbx + x0]; q < q_end; ++q) {
-        const uint2 ent = sorted[q];
-        const int dx = pos_x_of(ent.x) - x, dy = pos_y_of(ent.x) - y;
+        const typename Rep<WIDE>::Entry ent = sorted[q];
+        const int dx = Rep<WIDE>::x(ent, bits) - x, dy = Rep<WIDE>::y(ent, bits) - y;
         const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
-        KeyT key = (KeyT(d2) << idx_bits) | KeyT(ent.y);
-        if (q == self_slot || (ent.x & kDeadBit)) key = KeyLimits<KeyT>::kNone;
-        insert_key<KeyT, KT>(keys, key);
+        Key key = (Key(d2) << bits.ib) | Key(Rep<WIDE>::idx(ent, bits));
+        if (q == self_slot || Rep<WIDE>::dead(ent)) key = key_none<Key>();
+        insert_key<KT>(keys, key);
       }
     }
     if (bx - r <= 0 && bx + r >= last && by - r <= 0 && by + r >= last) break;
     const uint64_t reach = uint64_t(r) * (uint64_t(1) << bk.shift) + 1;
-    if (uint64_t(keys[K - 1]) < ((reach * reach) << idx_bits)) break;
+    if (uint64_t(keys[K - 1]) < ((reach * reach) << bits.ib)) break;
   }
+}
+
+// One observation row (own features + K neighbour slots) written to `row` (registers, LDS
+// or global).  KC > 0 fixes K at compile time so that the row can live in registers.
+template <int KC, typename Ptr>
+__device__ __forceinline__ void write_row(Ptr row, const Params& p, const uint32_t* pl, const uint16_t* nbr, int i,
+                                          int k_runtime, float t_frac) {
+  const int K = KC > 0 ? KC : k_runtime;
+  const uint32_t me = pl[i];
+  const int x = pos_x_of(me), y = pos_y_of(me);
+  const bool lv = !(me & kDeadBit);
+  row[0] = static_cast<float>(x) * p.inv_G;
+  row[1] = static_cast<float>(y) * p.inv_G;
+  row[2] = i < p.N_tag ? 1.0f : 0.0f;
+  row[3] = lv ? 1.0f : 0.0f;
+  row[4] = t_frac;
+#pragma unroll
+  for (int kk = 0; kk < K; ++kk) {
+    const uint32_t j = lv ? uint32_t(nbr[i * K + kk]) : kNoNeighbour;
+    float f0 = 0.0f, f1 = 0.0f, f2 = 0.0f, f3 = 0.0f;
+    if (j != kNoNeighbour) {
+      const uint32_t other = pl[j];
+      f0 = static_cast<float>(pos_x_of(other) - x) * p.inv_G;
+      f1 = static_cast<float>(pos_y_of(other) - y) * p.inv_G;
+      f2 = int(j) < p.N_tag ? 1.0f : 0.0f;
+      f3 = 1.0f;
+    }
+    row[5 + 4 * kk + 0] = f0;
+    row[5 + 4 * kk + 1] = f1;
+    row[5 + 4 * kk + 2] = f2;
+    row[5 + 4 * kk + 3] = f3;
+  }
+}
+
+__device__ __forceinline__ void wave_sync_lds() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // ----------------------------------------------------------------------------------
 // The env-per-team kernel: step, reset, or a whole iteration (sample + step + reset).
-// KT > 0: K <= KT nearest neighbours kept in registers, rows leave through the LDS
-// transpose.  KT == 0: any K, by repeated selection, rows written directly (slow path).
+// KX > 0: K == KX known at compile time.  KX == 0: K <= 8 at run time.  Both keep the
+// neighbour list in registers and send rows through the LDS transpose.  KX < 0: any K,
+// by repeated selection, rows written directly (slow path).
 // ----------------------------------------------------------------------------------
-template <typename KeyT, int KT>
+template <bool WIDE, int KX>
 __global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, const int mode,
                                                              const float* __restrict__ probs, uint32_t g_lo,
                                                              uint32_t g_hi) {
+  using R = Rep<WIDE>;
+  using Key = typename R::Key;
+  using Entry = typename R::Entry;
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x;
   const int ts = 1 << p.ts_log2;
@@ -286,11 +453,18 @@ __global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, con
   const int lt = tid & (ts - 1);
   const int e0 = blockIdx.x * p.teams_per_wg;
   const int e = e0 + team;
-  const int N = p.N, N_tag = p.N_tag, G = p.G, K = p.K;
+  const int N = p.N, N_tag = p.N_tag, G = p.G, NG = p.NG;
+  const int K = KX > 0 ? KX : p.K;
+  const bool vec = p.vec4 != 0;
   const bool valid = e < p.E;
   const int64_t abase = int64_t(valid ? e : 0) * N;
-  const TeamLds<KeyT> L(smem + team * p.team_stride, p);
-  const KeyT idx_mask = (KeyT(1) << p.idx_bits) - 1;
+  const TeamLds<WIDE> L(smem, team, p);
+  Bits bits;
+  bits.ib = p.idx_bits;
+  bits.xb = p.xy_bits;
+  bits.imask = (1u << p.idx_bits) - 1u;
+  bits.xmask = (1u << p.xy_bits) - 1u;
+  const Key idx_mask = (Key(1) << p.idx_bits) - 1;
 
   int done_in = 0, t_in = 0, nlr_in = 0;
   if (valid) {
@@ -300,102 +474,136 @@ __global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, con
   }
   const bool stepping = (mode == kModeStep || mode == kModeIterate);
   const bool step_act = stepping && valid && !done_in;
-  bool out_act = false;   // this team's env gets new observation rows
+  bool out_act = false;  // this team's env gets new observation rows
   int t_out = t_in;
   bool done_now = done_in != 0;
   Buckets bk = choose_buckets(p, nlr_in + N_tag);
 
   if (stepping) {
-    // ---- sample (iterate mode) and move; stage positions in LDS -------------------
-    for (int k = 0; k < p.apt; ++k) {
-      const int i = lt + k * ts;
-      if (valid && i < N) {
-        int act = 0;
-        if (mode == kModeIterate) {
-          const Block4 r = random_block(p, uint32_t(e), uint32_t(i), g_lo, g_hi, kStreamAction);
-          act = sample_action(probs + (abase + i) * kNumActions, r.w0);
-          p.action[abase + i] = act;
-        } else if (step_act) {
-          act = p.action[abase + i];
-        }
-        if (step_act) {
-          // positions are kept on the grid by every writer; the clamp only keeps a caller's
-          // stray value from indexing outside the bucket table
-          int x = min(max(p.pos_x[abase + i], 0), G - 1), y = min(max(p.pos_y[abase + i], 0), G - 1);
-          const bool lv = p.live[abase + i] != 0;
-          if (lv) {
-            const int nx = min(max(x + (act == 4) - (act == 3), 0), G - 1);
-            const int ny = min(max(y + (act == 1) - (act == 2), 0), G - 1);
-            if (nx != x) p.pos_x[abase + i] = nx;
-            if (ny != y) p.pos_y[abase + i] = ny;
-            x = nx;
-            y = ny;
-          }
-          L.pl[i] = pack_pos(x, y, lv);
-          L.best[i] = KeyLimits<KeyT>::kNone;
-        }
-      }
-    }
     if (step_act) {
       for (int j = lt; j < p.nb_cap; j += ts) L.counts[j] = 0u;
       for (int j = lt; j < N_tag; j += ts) L.credits[j] = 0;
       if (lt == 0) L.misc[0] = 0;
     }
     __syncthreads();
-    build_buckets<KeyT>(p, L, step_act, lt, ts, bk);
+    // ---- sample (iterate mode), move, stage positions in LDS, count buckets -------------
+    for (int k = 0; k < p.gpt; ++k) {
+      const int grp = lt + k * ts;
+      if (valid && grp < NG) {
+        const int i0 = 4 * grp, n = min(4, N - i0);
+        const int64_t a0 = abase + i0;
+        int act[4] = {0, 0, 0, 0};
+        if (mode == kModeIterate) {
+          const Block4 r = random_block(p, uint32_t(e), uint32_t(grp), g_lo, g_hi, kStreamAction);
+          sample_group(probs, a0, n, vec, r, act);
+          store4(p.action, a0, n, vec, act);
+        } else if (step_act) {
+          load4(p.action, a0, n, vec, act);
+        }
+        if (step_act) {
+          int x[4], y[4], lv[4];
+          load4(p.pos_x, a0, n, vec, x);
+          load4(p.pos_y, a0, n, vec, y);
+          load4(p.live, a0, n, vec, lv);
+          bool moved = false;
+          uint32_t packed[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const bool is_live = j < n && lv[j] != 0;
+            // positions are kept on the grid by every writer; the clamp also keeps a
+            // caller's stray value from indexing outside the bucket table
+            const int dxm = is_live ? (act[j] == 4) - (act[j] == 3) : 0;
+            const int dym = is_live ? (act[j] == 1) - (act[j] == 2) : 0;
+            const int nx = min(max(x[j] + dxm, 0), G - 1);
+            const int ny = min(max(y[j] + dym, 0), G - 1);
+            moved |= (nx != x[j]) | (ny != y[j]);
+            x[j] = nx;
+            y[j] = ny;
+            packed[j] = pack_pos(nx, ny, is_live);
+            if (is_live) atomicAdd(&L.counts[bucket_of(nx, ny, bk)], 1u);
+            L.best[i0 + j] = key_none<Key>();
+          }
+          if (moved) {
+            store4(p.pos_x, a0, n, vec, x);
+            store4(p.pos_y, a0, n, vec, y);
+          }
+          *reinterpret_cast<uint4*>(L.pl + i0) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+        }
+      }
+    }
+    __syncthreads();
+    scan_and_scatter<WIDE>(p, L, step_act, lt, ts, bk, bits);
 
     // ---- tag check, from the tagger's side: runners in range get the smallest
     //      (distance, tagger) key; min is order-independent, so the result is unique ----
     if (step_act && p.tag_r2 >= 0) {
-      for (int k = 0; k < p.apt; ++k) {
-        const int i = lt + k * ts;
-        if (i < N_tag) {
-          const uint32_t me = L.pl[i];
-          const int x = pos_x_of(me), y = pos_y_of(me);
-          const int bx0 = max(x - p.tag_rad, 0) >> bk.shift, bx1 = min(x + p.tag_rad, G - 1) >> bk.shift;
-          const int by0 = max(y - p.tag_rad, 0) >> bk.shift, by1 = min(y + p.tag_rad, G - 1) >> bk.shift;
-          for (int row = by0; row <= by1; ++row) {
-            const uint32_t q_end = L.starts[row * bk.nbx + bx1 + 1];
-            for (uint32_t q = L.starts[row * bk.nbx + bx0]; q < q_end; ++q) {
-              const uint2 ent = L.sorted[q];
-              if (int(ent.y) < N_tag) continue;
-              const int dx = pos_x_of(ent.x) - x, dy = pos_y_of(ent.x) - y;
-              const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
-              if (d2 <= uint32_t(p.tag_r2)) atomicMin(&L.best[ent.y], (KeyT(d2) << p.idx_bits) | KeyT(i));
-            }
+      for (int i = lt; i < N_tag; i += ts) {
+        const uint32_t me = L.pl[i];
+        const int x = pos_x_of(me), y = pos_y_of(me);
+        const int bx0 = max(x - p.tag_rad, 0) >> bk.shift, bx1 = min(x + p.tag_rad, G - 1) >> bk.shift;
+        const int by0 = max(y - p.tag_rad, 0) >> bk.shift, by1 = min(y + p.tag_rad, G - 1) >> bk.shift;
+        for (int row = by0; row <= by1; ++row) {
+          const uint32_t q_end = L.starts[row * bk.nbx + bx1 + 1];
+          for (uint32_t q = L.starts[row * bk.nbx + bx0]; q < q_end; ++q) {
+            const Entry ent = L.sorted[q];
+            const int j = int(R::idx(ent, bits));
+            if (j < N_tag) continue;
+            const int dx = R::x(ent, bits) - x, dy = R::y(ent, bits) - y;
+            const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
+            if (d2 <= uint32_t(p.tag_r2)) atomicMin(&L.best[j], (Key(d2) << p.idx_bits) | Key(i));
           }
         }
       }
     }
     __syncthreads();
-    // ---- runners: leave the game if tagged, credit the tagger, take the penalty ------
+    // ---- runners in range leave the game and credit their tagger ---------------------------
     if (step_act) {
-      for (int k = 0; k < p.apt; ++k) {
-        const int i = lt + k * ts;
-        if (i >= N_tag && i < N) {
-          const uint32_t me = L.pl[i];
-          float rew = 0.0f;
-          if (!(me & kDeadBit)) {
-            const KeyT b = L.best[i];
-            if (b != KeyLimits<KeyT>::kNone) {
-              p.live[abase + i] = 0;
-              L.pl[i] = me | kDeadBit;
-              L.sorted[L.slot[i]].x = me | kDeadBit;
-              rew = p.tag_penalty;
-              atomicAdd(&L.credits[int(b & idx_mask)], 1);
-              atomicAdd(&L.misc[0], 1);
+      int my_tags = 0;
+      for (int k = 0; k < p.gpt; ++k) {
+        const int i0 = 4 * (lt + k * ts);
+        if (i0 + 3 >= N_tag && i0 < N) {
+          bool any = false;
+          int lv[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int i = i0 + j;
+            uint32_t me = L.pl[i];
+            if (i >= N_tag && i < N) {
+              const Key b = L.best[i];
+              if (b != key_none<Key>()) {
+                me |= kDeadBit;
+                L.pl[i] = me;
+                R::mark_dead(&L.sorted[L.slot[i]]);
+                atomicAdd(&L.credits[int(b & idx_mask)], 1);
+                ++my_tags;
+                any = true;
+              }
             }
+            lv[j] = (me & kDeadBit) ? 0 : 1;
           }
-          p.reward[abase + i] = rew;
+          if (any) store4(p.live, abase + i0, min(4, N - i0), vec, lv);
         }
       }
+      if (my_tags) atomicAdd(&L.misc[0], my_tags);
     }
     __syncthreads();
-    // ---- tagger rewards, env clock and termination ------------------------------------
+    // ---- rewards, env clock and termination -----------------------------------------------
     if (step_act) {
-      for (int k = 0; k < p.apt; ++k) {
-        const int i = lt + k * ts;
-        if (i < N_tag) p.reward[abase + i] = static_cast<float>(L.credits[i]) * p.tag_reward;
+      for (int k = 0; k < p.gpt; ++k) {
+        const int i0 = 4 * (lt + k * ts);
+        if (i0 < N) {
+          float rew[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int i = i0 + j;
+            rew[j] = 0.0f;
+            if (i < N_tag)
+              rew[j] = static_cast<float>(L.credits[i]) * p.tag_reward;
+            else if (i < N && L.best[i] != key_none<Key>())
+              rew[j] = p.tag_penalty;
+          }
+          store4(p.reward, abase + i0, min(4, N - i0), vec, rew);
+        }
       }
       const int tags = L.misc[0];
       const int nlr = nlr_in - tags;
@@ -412,23 +620,40 @@ __global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, con
   }
 
   if (mode != kModeStep) {
-    // ---- reset: restore the start state of envs that are done (or of all) -------------
+    // ---- reset: restore the start state of envs that are done (or of all) ------------------
     const bool reset_act = valid && (mode == kModeResetAll || done_now);
     const bool any_reset = (mode == kModeIterate) ? (__syncthreads_or(reset_act ? 1 : 0) != 0) : true;
     if (any_reset) {
-      bk = reset_act ? choose_buckets(p, N) : bk;
       if (reset_act) {
-        for (int k = 0; k < p.apt; ++k) {
-          const int i = lt + k * ts;
-          if (i < N) {
-            const int x = min(max(p.pos_x0[abase + i], 0), G - 1), y = min(max(p.pos_y0[abase + i], 0), G - 1);
-            p.pos_x[abase + i] = x;
-            p.pos_y[abase + i] = y;
-            p.live[abase + i] = 1;
-            L.pl[i] = pack_pos(x, y, true);
+        bk = choose_buckets(p, N);
+        for (int j = lt; j < p.nb_cap; j += ts) L.counts[j] = 0u;
+      }
+      __syncthreads();
+      if (reset_act) {
+        for (int k = 0; k < p.gpt; ++k) {
+          const int grp = lt + k * ts;
+          if (grp < NG) {
+            const int i0 = 4 * grp, n = min(4, N - i0);
+            const int64_t a0 = abase + i0;
+            int x[4], y[4];
+            load4(p.pos_x0, a0, n, vec, x);
+            load4(p.pos_y0, a0, n, vec, y);
+            uint32_t packed[4];
+            int ones[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              x[j] = min(max(x[j], 0), G - 1);
+              y[j] = min(max(y[j], 0), G - 1);
+              packed[j] = pack_pos(x[j], y[j], j < n);
+              ones[j] = 1;
+              if (j < n) atomicAdd(&L.counts[bucket_of(x[j], y[j], bk)], 1u);
+            }
+            store4(p.pos_x, a0, n, vec, x);
+            store4(p.pos_y, a0, n, vec, y);
+            store4(p.live, a0, n, vec, ones);
+            *reinterpret_cast<uint4*>(L.pl + i0) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
           }
         }
-        for (int j = lt; j < p.nb_cap; j += ts) L.counts[j] = 0u;
         t_out = 0;
         if (lt == 0) {
           p.t[e] = 0;
@@ -439,96 +664,108 @@ __global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, con
         out_act = true;
       }
       __syncthreads();
-      build_buckets<KeyT>(p, L, reset_act, lt, ts, bk);
+      scan_and_scatter<WIDE>(p, L, reset_act, lt, ts, bk, bits);
     }
   }
 
-  // ---- observations --------------------------------------------------------------------
+  // ---- observations ---------------------------------------------------------------------------
   if (lt == 0) {
     L.misc[1] = t_out;
     L.misc[2] = out_act ? 1 : 0;
   }
-  if constexpr (KT > 0) {
+  if constexpr (KX >= 0) {
+    constexpr int KT = KX > 0 ? KX : kMaxRegisterK;
     // K nearest, in bucket order (neighbouring lanes search neighbouring cells)
     if (out_act && K > 0) {
       const int n_sorted = int(L.starts[p.nb_cap]);
-      for (int k = 0; k < p.apt; ++k) {
-        const int q = lt + k * ts;
-        if (q < n_sorted) {
-          const uint2 ent = L.sorted[q];
-          if (!(ent.x & kDeadBit)) {
-            KeyT keys[KT];
-            nearest_keys<KeyT, KT>(keys, K, pos_x_of(ent.x), pos_y_of(ent.x), uint32_t(q), bk, p.idx_bits,
-                                   L.sorted, L.starts);
+      for (int q = lt; q < n_sorted; q += ts) {
+        const Entry ent = L.sorted[q];
+        if (!R::dead(ent)) {
+          Key keys[KT];
+          nearest_keys<WIDE, KT>(keys, K, R::x(ent, bits), R::y(ent, bits), uint32_t(q), bk, bits, L.sorted,
+                                 L.starts);
+          const uint32_t me = R::idx(ent, bits);
 #pragma unroll
-            for (int kk = 0; kk < KT; ++kk)
-              if (kk < K)
-                L.nbr[ent.y * K + kk] =
-                    keys[kk] == KeyLimits<KeyT>::kNone ? uint16_t(kNoNeighbour) : uint16_t(keys[kk] & idx_mask);
-          }
+          for (int kk = 0; kk < KT; ++kk)
+            if (kk < K)
+              L.nbr[me * K + kk] =
+                  keys[kk] == key_none<Key>() ? uint16_t(kNoNeighbour) : uint16_t(keys[kk] & idx_mask);
         }
       }
     }
     const bool all_out = __syncthreads_and((out_act || !valid) ? 1 : 0) != 0;  // also the barrier before the rows
 
-    // rows, in index order; a wave builds 64 rows, transposes them through LDS and
-    // writes them as one contiguous run
+    // Rows, in index order.  A wave builds 64 rows in registers and sends them, 32 at a
+    // time, through an LDS transpose (which overlays the sort tables) so that each store
+    // instruction writes a contiguous run.
     const int wave = tid >> 6, lane = tid & (kWaveSize - 1);
-    const int D = p.D;
-    float* stage = reinterpret_cast<float*>(smem + p.off_stage) + wave * kWaveSize * D;
+    const int D = KX > 0 ? 5 + 4 * KX : p.D;
     const int rows_total = min(p.teams_per_wg, p.E - e0) * N;
-    const int64_t obs_base = int64_t(e0) * N * D;
-    const bool vec_ok = (obs_base & 3) == 0;
-    for (int c = wave; c * kWaveSize < rows_total; c += kWavesPerWorkgroup) {
-      const int R = c * kWaveSize + lane;
-      if (R < rows_total) {
-        const int tm = int(fastdiv(uint32_t(R), p.div_N));
-        const int i = R - tm * N;
-        const TeamLds<KeyT> Lr(smem + tm * p.team_stride, p);
-        if (all_out || Lr.misc[2]) {
-          float* row = all_out ? stage + lane * D : p.obs + obs_base + int64_t(R) * D;
-          const uint32_t me = Lr.pl[i];
-          const int x = pos_x_of(me), y = pos_y_of(me);
-          const bool lv = !(me & kDeadBit);
-          row[0] = static_cast<float>(x) * p.inv_G;
-          row[1] = static_cast<float>(y) * p.inv_G;
-          row[2] = i < N_tag ? 1.0f : 0.0f;
-          row[3] = lv ? 1.0f : 0.0f;
-          row[4] = static_cast<float>(Lr.misc[1]) * p.inv_T;
-          for (int kk = 0; kk < K; ++kk) {
-            const uint32_t j = lv ? uint32_t(Lr.nbr[i * K + kk]) : kNoNeighbour;
-            float f0 = 0.0f, f1 = 0.0f, f2 = 0.0f, f3 = 0.0f;
-            if (j != kNoNeighbour) {
-              const uint32_t other = Lr.pl[j];
-              f0 = static_cast<float>(pos_x_of(other) - x) * p.inv_G;
-              f1 = static_cast<float>(pos_y_of(other) - y) * p.inv_G;
-              f2 = int(j) < N_tag ? 1.0f : 0.0f;
-              f3 = 1.0f;
+    float* const obs_wg = p.obs + int64_t(e0) * N * D;
+    if (all_out) {
+      float* stage = reinterpret_cast<float*>(smem + p.scratch_base) + wave * kStageRows * D;
+      const bool vec_ok = ((int64_t(e0) * N * D) & 3) == 0;
+      for (int c = wave; c * kWaveSize < rows_total; c += kWavesPerWorkgroup) {
+        const int R0 = c * kWaveSize;
+        const int Rr = R0 + lane;
+        const bool have = Rr < rows_total;
+        int tm = 0, i = Rr;
+        if (p.teams_per_wg > 1) {
+          tm = int(fastdiv(uint32_t(Rr), p.div_N));
+          i = Rr - tm * N;
+        }
+        const TeamLds<WIDE> Lr(smem, have ? tm : 0, p);
+        const float t_frac = static_cast<float>(Lr.misc[1]) * p.inv_T;
+        if constexpr (KX > 0) {
+          float row[5 + 4 * (KX > 0 ? KX : 1)];
+          if (have) write_row<KX>(row, p, Lr.pl, Lr.nbr, i, KX, t_frac);
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            if (have && (lane >> 5) == h) {
+              float* dst = stage + (lane & 31) * D;
+#pragma unroll
+              for (int d = 0; d < 5 + 4 * KX; ++d) dst[d] = row[d];
             }
-            row[5 + 4 * kk + 0] = f0;
-            row[5 + 4 * kk + 1] = f1;
-            row[5 + 4 * kk + 2] = f2;
-            row[5 + 4 * kk + 3] = f3;
+            wave_sync_lds();
+            const int nfl = min(max(rows_total - (R0 + h * kStageRows), 0), kStageRows) * D;
+            float* out = obs_wg + int64_t(R0 + h * kStageRows) * D;
+            if (vec_ok) {
+              const int nvec = nfl >> 2;
+              for (int v = lane; v < nvec; v += kWaveSize)
+                reinterpret_cast<float4*>(out)[v] = reinterpret_cast<const float4*>(stage)[v];
+              for (int f = (nvec << 2) + lane; f < nfl; f += kWaveSize) out[f] = stage[f];
+            } else {
+              for (int f = lane; f < nfl; f += kWaveSize) out[f] = stage[f];
+            }
+            wave_sync_lds();
+          }
+        } else {
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            if (have && (lane >> 5) == h) write_row<0>(stage + (lane & 31) * D, p, Lr.pl, Lr.nbr, i, K, t_frac);
+            wave_sync_lds();
+            const int nfl = min(max(rows_total - (R0 + h * kStageRows), 0), kStageRows) * D;
+            float* out = obs_wg + int64_t(R0 + h * kStageRows) * D;
+            if (vec_ok) {
+              const int nvec = nfl >> 2;
+              for (int v = lane; v < nvec; v += kWaveSize)
+                reinterpret_cast<float4*>(out)[v] = reinterpret_cast<const float4*>(stage)[v];
+              for (int f = (nvec << 2) + lane; f < nfl; f += kWaveSize) out[f] = stage[f];
+            } else {
+              for (int f = lane; f < nfl; f += kWaveSize) out[f] = stage[f];
+            }
+            wave_sync_lds();
           }
         }
       }
-      if (all_out) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const int nfl = min(kWaveSize, rows_total - c * kWaveSize) * D;
-        float* dst = p.obs + obs_base + int64_t(c) * kWaveSize * D;
-        if (vec_ok) {
-          const int nvec = nfl >> 2;
-          for (int v = lane; v < nvec; v += kWaveSize)
-            reinterpret_cast<float4*>(dst)[v] = reinterpret_cast<const float4*>(stage)[v];
-          for (int f = (nvec << 2) + lane; f < nfl; f += kWaveSize) dst[f] = stage[f];
-        } else {
-          for (int f = lane; f < nfl; f += kWaveSize) dst[f] = stage[f];
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    } else {
+      // some envs of this workgroup keep their rows: each lane writes its own row in place
+      for (int Rr = tid; Rr < rows_total; Rr += kWorkgroupSize) {
+        const int tm = int(fastdiv(uint32_t(Rr), p.div_N));
+        const int i = Rr - tm * N;
+        const TeamLds<WIDE> Lr(smem, tm, p);
+        if (Lr.misc[2])
+          write_row<0>(obs_wg + int64_t(Rr) * D, p, Lr.pl, Lr.nbr, i, K, static_cast<float>(Lr.misc[1]) * p.inv_T);
       }
     }
   } else {
@@ -538,9 +775,7 @@ __global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, con
       const int D = p.D;
       const int n_sorted = int(L.starts[p.nb_cap]);
       const float tf = static_cast<float>(t_out) * p.inv_T;
-      for (int k = 0; k < p.apt; ++k) {
-        const int i = lt + k * ts;
-        if (i >= N) continue;
+      for (int i = lt; i < N; i += ts) {
         float* row = p.obs + (abase + i) * D;
         const uint32_t me = L.pl[i];
         const int x = pos_x_of(me), y = pos_y_of(me);
@@ -551,21 +786,21 @@ __global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, con
         row[3] = lv ? 1.0f : 0.0f;
         row[4] = tf;
         bool have_prev = false, exhausted = !lv;
-        KeyT prev = 0;
+        Key prev = 0;
         for (int kk = 0; kk < K; ++kk) {
-          KeyT bestk = KeyLimits<KeyT>::kNone;
+          Key bestk = key_none<Key>();
           if (!exhausted) {
             for (int q = 0; q < n_sorted; ++q) {
-              const uint2 ent = L.sorted[q];
-              if (int(ent.y) == i || (ent.x & kDeadBit)) continue;
-              const int dx = pos_x_of(ent.x) - x, dy = pos_y_of(ent.x) - y;
+              const Entry ent = L.sorted[q];
+              if (int(R::idx(ent, bits)) == i || R::dead(ent)) continue;
+              const int dx = R::x(ent, bits) - x, dy = R::y(ent, bits) - y;
               const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
-              const KeyT key = (KeyT(d2) << p.idx_bits) | KeyT(ent.y);
+              const Key key = (Key(d2) << p.idx_bits) | Key(R::idx(ent, bits));
               if ((!have_prev || key > prev) && key < bestk) bestk = key;
             }
           }
           float f0 = 0.0f, f1 = 0.0f, f2 = 0.0f, f3 = 0.0f;
-          if (bestk != KeyLimits<KeyT>::kNone) {
+          if (bestk != key_none<Key>()) {
             const int j = int(bestk & idx_mask);
             const uint32_t other = L.pl[j];
             f0 = static_cast<float>(pos_x_of(other) - x) * p.inv_G;
@@ -587,58 +822,40 @@ __global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, con
   }
 }
 
-template <typename KeyT, int KT>
+template <bool WIDE, int KX>
 hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream) {
   const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
-  hipLaunchKernelGGL((env_kernel<KeyT, KT>), dim3(groups), dim3(kWorkgroupSize), size_t(p.lds_bytes), stream, p,
+  hipLaunchKernelGGL((env_kernel<WIDE, KX>), dim3(groups), dim3(kWorkgroupSize), size_t(p.lds_bytes), stream, p,
                      mode, probs, uint32_t(g), uint32_t(g >> 32));
   return hipGetLastError();
 }
 
-template <typename KeyT, int KT>
+template <bool WIDE, int KX>
 hipError_t prepare_env_variant(const Params& p) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&env_kernel<KeyT, KT>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&env_kernel<WIDE, KX>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
 }
 
-// Register list length for K: the smallest compiled size that holds it; 0 = any-K path.
-int register_k(const Params& p) {
-  if (p.K > kMaxRegisterK) return 0;
-  if (p.K <= 1) return 1;
-  if (p.K <= 2) return 2;
-  if (p.K <= 4) return 4;
-  return 8;
+// Which compiled variant serves K: 4 (the benchmark shape), 0 (K <= 8 at run time), -1 (any K).
+int variant_of(const Params& p) {
+  if (p.K == 4) return 4;
+  if (p.K <= kMaxRegisterK) return 0;
+  return -1;
 }
-
-bool wide_keys(const Params& p) { return p.idx_bits < 0; }
 
 }  // namespace
 
-// The key width is chosen by the host: idx_bits >= 0 with a 32-bit key when
-// (max squared distance + 1) << idx_bits fits below 2^32, else 64-bit keys and ~idx_bits.
-#define WD_DISPATCH(fn, ...)                                                   \
-  do {                                                                         \
-    const int kt = register_k(p);                                              \
-    Params q = p;                                                              \
-    const bool wide = wide_keys(p);                                            \
-    if (wide) q.idx_bits = ~p.idx_bits;                                        \
-    if (!wide) {                                                               \
-      switch (kt) {                                                            \
-        case 0: return fn<uint32_t, 0>(q, ##__VA_ARGS__);                      \
-        case 1: return fn<uint32_t, 1>(q, ##__VA_ARGS__);                      \
-        case 2: return fn<uint32_t, 2>(q, ##__VA_ARGS__);                      \
-        case 4: return fn<uint32_t, 4>(q, ##__VA_ARGS__);                      \
-        default: return fn<uint32_t, 8>(q, ##__VA_ARGS__);                     \
-      }                                                                        \
-    } else {                                                                   \
-      switch (kt) {                                                            \
-        case 0: return fn<unsigned long long, 0>(q, ##__VA_ARGS__);            \
-        case 1: return fn<unsigned long long, 1>(q, ##__VA_ARGS__);            \
-        case 2: return fn<unsigned long long, 2>(q, ##__VA_ARGS__);            \
-        case 4: return fn<unsigned long long, 4>(q, ##__VA_ARGS__);            \
-        default: return fn<unsigned long long, 8>(q, ##__VA_ARGS__);           \
-      }                                                                        \
-    }                                                                          \
+#define WD_DISPATCH(fn, ...)                                      \
+  do {                                                            \
+    const int kx = variant_of(p);                                 \
+    if (!p.wide) {                                                \
+      if (kx == 4) return fn<false, 4>(p, ##__VA_ARGS__);         \
+      if (kx == 0) return fn<false, 0>(p, ##__VA_ARGS__);         \
+      return fn<false, -1>(p, ##__VA_ARGS__);                     \
+    }                                                             \
+    if (kx == 4) return fn<true, 4>(p, ##__VA_ARGS__);            \
+    if (kx == 0) return fn<true, 0>(p, ##__VA_ARGS__);            \
+    return fn<true, -1>(p, ##__VA_ARGS__);                        \
   } while (0)
 
 hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream) {
@@ -650,7 +867,7 @@ hipError_t prepare_env_kernels(const Params& p) { WD_DISPATCH(prepare_env_varian
 bool env_kernel_available(const Params& p) { return p.obs_mode == 0; }
 
 hipError_t launch_sample(const Params& p, const float* probs, uint64_t g, hipStream_t stream) {
-  const int64_t total = int64_t(p.E) * p.N;
+  const int64_t total = int64_t(p.E) * p.NG;
   const int groups = int((total + kWorkgroupSize - 1) / kWorkgroupSize);
   hipLaunchKernelGGL(sample_kernel, dim3(groups), dim3(kWorkgroupSize), 0, stream, p, probs, uint32_t(g),
                      uint32_t(g >> 32));
