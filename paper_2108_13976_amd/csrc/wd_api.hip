@@ -78,11 +78,12 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p) {
   p->NG = (N + 3) / 4;
   int ts_log2 = 3;
   while ((1 << ts_log2) < p->NG && ts_log2 < 8) ++ts_log2;
+  p->wg_size = 256;
   const int ts = 1 << ts_log2;
   p->ts_log2 = ts_log2;
-  p->teams_per_wg = wd::kWorkgroupSize / ts;
+  p->teams_per_wg = p->wg_size / ts;
   p->gpt = (p->NG + ts - 1) / ts;
-  p->NPAD = 4 * ts * p->gpt;
+  p->NPAD = (4 * p->NG + 63) / 64 * 64;
   p->vec4 = (N % 4 == 0) ? 1 : 0;
   uint32_t nb_cap = pow2_ceil(uint32_t(N)) / 2;
   if (nb_cap > 4096u) nb_cap = 4096u;
@@ -90,14 +91,15 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p) {
   if (nb_cap < 16u) nb_cap = 16u;
   p->nb_cap = int32_t(nb_cap);
   p->scan_chunk = int32_t(nb_cap) / ts;
-  int shift_min = 0;
-  while (true) {
-    const int64_t nbx = (G + (1 << shift_min) - 1) >> shift_min;
-    if (nbx * nbx <= int64_t(nb_cap)) break;
-    ++shift_min;
-  }
-  p->shift_min = shift_min;
-  p->occupancy_need = 3.0f * float(G) * float(G);  // aim at >= 3 live agents per bucket
+  // buckets are 65536 / mul cells wide; the table holds nbx^2 <= nb_cap of them
+  uint32_t side = 1;
+  while ((side + 1) * (side + 1) <= nb_cap) ++side;
+  // largest mul with ((G - 1) * mul >> 16) + 1 <= side
+  uint32_t mul_max = 65536u;
+  if (G > 1) mul_max = uint32_t(std::min<uint64_t>(65536u, ((uint64_t(side) << 16) - 1) / uint64_t(G - 1)));
+  p->bucket_mul_max = mul_max;
+  const double lambda = 3.0;  // target live agents per bucket
+  p->bucket_scale = float(65536.0 / (double(G) * std::sqrt(lambda)));
   p->div_N = wd::make_fastdiv(uint32_t(N));
   p->div_NG = wd::make_fastdiv(uint32_t(p->NG));
 
@@ -105,7 +107,7 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p) {
   p->idx_bits = bits_for(uint32_t(N - 1));
   p->xy_bits = bits_for(uint32_t(G - 1));
   const uint64_t d2max = 2ull * uint64_t(G - 1) * uint64_t(G - 1);
-  const bool narrow = (1 + 2 * p->xy_bits + p->idx_bits <= 32) && (((d2max + 1) << p->idx_bits) < (1ull << 32));
+  const bool narrow = (1 + 2 * p->xy_bits + p->idx_bits <= 32) && (((d2max + 1) << p->idx_bits) <= (1ull << 31));
   p->wide = narrow ? 0 : 1;
   const int key_bytes = narrow ? 4 : 8;
   const bool register_path = p->K <= wd::kMaxRegisterK;
@@ -117,22 +119,33 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p) {
     return int32_t(at);
   };
   const int64_t NPAD = p->NPAD;
+  const int tpw = p->teams_per_wg;
   p->off_pl = take(4 * NPAD);
-  p->off_nbr = take(register_path ? 2 * NPAD * p->K : 0);
-  p->off_misc = take(32);
+  p->off_misc = take(64);
   p->keep_stride = int32_t(off);
   off = 0;
-  p->off_sorted = take(key_bytes * NPAD);
+  p->off_sorted = take(key_bytes * (NPAD + 4));  // padded: the search reads one entry ahead
+  p->off_starts = take(4ll * (nb_cap + 4));
+  p->x_stride = int32_t(off);
+  off = 0;
   p->off_slot = take(2 * NPAD);
   p->off_best = take(key_bytes * NPAD);
   p->off_credits = take(4ll * c.num_taggers);
   p->off_counts = take(4ll * nb_cap);
-  p->off_starts = take(4ll * (nb_cap + 4));
-  p->scratch_stride = int32_t(off);
-  p->scratch_base = p->keep_stride * p->teams_per_wg;
-  const int64_t stage = register_path ? int64_t(wd::kWavesPerWorkgroup) * wd::kStageRows * p->D * 4 : 0;
-  const int64_t scratch = std::max<int64_t>(int64_t(p->scratch_stride) * p->teams_per_wg, stage);
-  const int64_t total = p->scratch_base + scratch;
+  const int64_t nbr_bytes = register_path ? align16(2 * NPAD * p->K) : 0;
+  p->y_stride = int32_t(std::max<int64_t>(off, nbr_bytes));
+  // the staging area overlays the X parts: 32 rows per wave and flush if that fits, else 16
+  const int64_t x_area = int64_t(p->x_stride) * tpw;
+  const int64_t waves = p->wg_size / wd::kWaveSize;
+  p->stage_rows_log2 = 5;
+  int64_t stage = register_path ? waves * 32 * p->D * 4 : 0;
+  if (stage > x_area) {
+    p->stage_rows_log2 = 4;
+    stage = waves * 16 * p->D * 4;
+  }
+  p->x_base = p->keep_stride * tpw;
+  p->y_base = int32_t(p->x_base + std::max<int64_t>(x_area, stage));
+  const int64_t total = int64_t(p->y_base) + int64_t(p->y_stride) * tpw;
   p->lds_bytes = int32_t(std::min<int64_t>(total, INT32_MAX));
   return total <= kLdsLimitBytes;
 }

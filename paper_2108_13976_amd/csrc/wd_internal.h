@@ -8,12 +8,11 @@
 
 namespace wd {
 
-constexpr int kWorkgroupSize = 256;     // four wave64s
+constexpr int kWorkgroupSize = 256;     // flat per-agent kernels: four wave64s
+constexpr int kMaxEnvWorkgroupSize = 512;  // env-per-team kernels run 256 or 512 threads
 constexpr int kWaveSize = 64;
-constexpr int kWavesPerWorkgroup = kWorkgroupSize / kWaveSize;
 constexpr int kNumActions = 5;
 constexpr int kMaxRegisterK = 8;        // K up to this keeps the candidate list in registers
-constexpr int kStageRows = 32;          // rows a wave transposes through LDS per flush
 constexpr uint32_t kStreamAction = 0;   // random streams (low byte of the fourth counter word)
 constexpr uint32_t kStreamInit = 1;
 
@@ -45,21 +44,25 @@ struct Params {
   // workgroup holds teams_per_wg teams of (1 << ts_log2) threads; a team owns one env;
   // thread lt of a team owns groups lt, lt + ts, ... (gpt of them).
   int32_t NG;            // groups per env = ceil(N / 4)
-  int32_t NPAD;          // 4 * ts * gpt >= N: per-agent LDS arrays are padded to this
+  int32_t NPAD;          // 4 * NG rounded up to 64: per-agent LDS arrays are padded to this
+  int32_t wg_size;       // 256, or 512 when one env fills the workgroup (more lanes per env)
+  int32_t stage_rows_log2;  // rows a wave transposes through LDS per flush: 32 or 16
   int32_t ts_log2, teams_per_wg, gpt;
   int32_t vec4;          // N % 4 == 0: a group's global slices are 16-byte aligned
   int32_t nb_cap;        // bucket slots per team (power of two, >= team size)
   int32_t scan_chunk;    // nb_cap / team size
-  int32_t shift_min;     // smallest bucket shift whose table fits nb_cap
-  float occupancy_need;  // lambda * G * G: shift grows until n_live * 4^shift reaches it
+  float bucket_scale;    // 65536 / (G * sqrt(lambda)): bucket multiplier = scale * sqrt(n_live)
+  uint32_t bucket_mul_max;  // largest multiplier whose bucket table fits nb_cap
   // (distance, index) keys and bucket entries: 32-bit when wide == 0
   int32_t wide, idx_bits, xy_bits;
   FastDiv div_N, div_NG;
-  // LDS map.  Per team a persistent part (positions, neighbour lists, scalars) and a
-  // scratch part (sort and tag tables) that the row staging area overlays once the
-  // neighbour search is done.
-  int32_t keep_stride, off_pl, off_nbr, off_misc;
-  int32_t scratch_base, scratch_stride, off_sorted, off_slot, off_best, off_credits, off_counts, off_starts;
+  // LDS map.  Per team: a kept part (positions, scalars); an X part (bucket-sorted entries
+  // and bucket starts) that the row staging area overlays once the neighbour search is done;
+  // a Y part (slots, tag keys, credits, bucket counters) that the neighbour lists overlay
+  // once the rewards are out.
+  int32_t keep_stride, off_pl, off_misc;
+  int32_t x_base, x_stride, off_sorted, off_starts;
+  int32_t y_base, y_stride, off_slot, off_best, off_credits, off_counts;
   int32_t lds_bytes;
   // device buffers (borrowed from the caller)
   int32_t *pos_x, *pos_y, *pos_x0, *pos_y0, *live, *action;

@@ -198,6 +198,9 @@ template <typename Key>
 __device__ __forceinline__ Key key_none() {
   return ~Key(0);
 }
+// A 32-bit list slot is empty if it holds the initial value or a dead candidate's key.
+__device__ __forceinline__ bool key_is_none(uint32_t k) { return (k & kDeadBit) != 0; }
+__device__ __forceinline__ bool key_is_none(unsigned long long k) { return k == ~0ull; }
 
 // Positions by agent index: x | y << 16 | dead bit.
 __device__ __forceinline__ uint32_t pack_pos(int x, int y, bool is_live) {
@@ -242,28 +245,32 @@ __device__ __forceinline__ int team_exclusive_scan(int v, int lt, int ts_log2, i
 }
 
 struct Buckets {
-  int shift;  // a bucket is (1 << shift) cells wide
-  int nbx;    // buckets per grid side
+  uint32_t mul;  // bucket coordinate of cell x is (x * mul) >> 16: buckets are 65536 / mul cells wide
+  int nbx;       // buckets per grid side
+  int bmin;      // width in cells of the narrowest bucket = floor(65536 / mul)
 };
 
-// Bucket width for n_live agents on the grid: the smallest power of two that fits the
-// bucket table and keeps the mean occupancy near the target.  Any choice gives the same
-// results; it only trades search rings against candidates per ring.
+// Bucket width for n_live agents on the grid: about sqrt(lambda / density) cells, so that a
+// bucket holds about lambda live agents, limited by the size of the bucket table.  Any choice
+// gives the same results; it only trades search rings against candidates per ring.
 __device__ __forceinline__ Buckets choose_buckets(const Params& p, int n_live) {
-  int s = p.shift_min;
-  float have = static_cast<float>(n_live) * static_cast<float>(1 << (2 * s));
-  while (s < 15 && have < p.occupancy_need) {
-    ++s;
-    have *= 4.0f;
-  }
+  const float want = p.bucket_scale * sqrtf(static_cast<float>(max(n_live, 1)));
+  uint32_t mul = static_cast<uint32_t>(fminf(want, 65536.0f) + 0.5f);
+  mul = min(max(mul, 2u), p.bucket_mul_max);
   Buckets b;
-  b.shift = s;
-  b.nbx = (p.G + (1 << s) - 1) >> s;
+  b.mul = mul;
+  b.nbx = int((uint32_t(p.G - 1) * mul) >> 16) + 1;
+  uint32_t w = static_cast<uint32_t>(65536.0f / static_cast<float>(mul));
+  if (w * mul > 65536u) --w;
+  if ((w + 1) * mul <= 65536u) ++w;
+  b.bmin = int(w);
   return b;
 }
 
+__device__ __forceinline__ int bucket_coord(int x, const Buckets bk) { return int(__umul24(uint32_t(x), bk.mul) >> 16); }
+
 __device__ __forceinline__ int bucket_of(int x, int y, const Buckets bk) {
-  return (y >> bk.shift) * bk.nbx + (x >> bk.shift);
+  return bucket_coord(y, bk) * bk.nbx + bucket_coord(x, bk);
 }
 
 // LDS views of one team's regions.
@@ -272,8 +279,8 @@ struct TeamLds {
   using Key = typename Rep<WIDE>::Key;
   using Entry = typename Rep<WIDE>::Entry;
   uint32_t* pl;      // [NPAD] packed position + dead bit, by agent index
-  uint16_t* nbr;     // [NPAD][K] neighbour indices
-  int32_t* misc;     // [0] tags this step, [1] t after the call, [2] rows to be written, [4..7] scan scratch
+  uint16_t* nbr;     // [NPAD][K] neighbour indices; overlays slot/best/credits/counts
+  int32_t* misc;     // [0] tags this step, [1] t after the call, [2] rows to be written, [4..11] scan scratch
   Entry* sorted;     // [NPAD] entries of the live agents, grouped by bucket
   uint16_t* slot;    // [NPAD] where agent i sits in `sorted`
   Key* best;         // [NPAD] per runner: smallest (distance, tagger) key in range
@@ -282,16 +289,17 @@ struct TeamLds {
   uint32_t* starts;  // [nb_cap + 1] bucket start offsets in `sorted`
   __device__ __forceinline__ TeamLds(unsigned char* smem, int team, const Params& p) {
     unsigned char* keep = smem + team * p.keep_stride;
-    unsigned char* scr = smem + p.scratch_base + team * p.scratch_stride;
+    unsigned char* xr = smem + p.x_base + team * p.x_stride;
+    unsigned char* yr = smem + p.y_base + team * p.y_stride;
     pl = reinterpret_cast<uint32_t*>(keep + p.off_pl);
-    nbr = reinterpret_cast<uint16_t*>(keep + p.off_nbr);
     misc = reinterpret_cast<int32_t*>(keep + p.off_misc);
-    sorted = reinterpret_cast<Entry*>(scr + p.off_sorted);
-    slot = reinterpret_cast<uint16_t*>(scr + p.off_slot);
-    best = reinterpret_cast<Key*>(scr + p.off_best);
-    credits = reinterpret_cast<int32_t*>(scr + p.off_credits);
-    counts = reinterpret_cast<uint32_t*>(scr + p.off_counts);
-    starts = reinterpret_cast<uint32_t*>(scr + p.off_starts);
+    sorted = reinterpret_cast<Entry*>(xr + p.off_sorted);
+    starts = reinterpret_cast<uint32_t*>(xr + p.off_starts);
+    nbr = reinterpret_cast<uint16_t*>(yr);  // overlays the tables below
+    slot = reinterpret_cast<uint16_t*>(yr + p.off_slot);
+    best = reinterpret_cast<Key*>(yr + p.off_best);
+    credits = reinterpret_cast<int32_t*>(yr + p.off_credits);
+    counts = reinterpret_cast<uint32_t*>(yr + p.off_counts);
   }
 };
 
@@ -364,33 +372,60 @@ __device__ __forceinline__ void insert_key(unsigned long long (&keys)[KT], unsig
 
 // The K smallest (squared distance, index) keys among the other live agents, exactly.
 // Scans the (2r+1)^2 buckets around the agent's own; every agent outside that block is
-// farther than r bucket widths in x or in y, so once the K-th key is below (r*B+1)^2 (or
+// farther than r bucket widths in x or in y, so once the K-th key is below (r*bmin+1)^2 (or
 // the block covers the grid) no unseen agent can enter the list; otherwise r doubles and
-// the scan restarts.
+// the scan restarts.  The agent's own entry is left out by splitting its bucket row at
+// its slot.
+template <int KT>
+__device__ __forceinline__ void scan_range(unsigned long long (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y,
+                                           const Bits& bits, const uint2* sorted) {
+  for (uint32_t q = qb; q < qe; ++q) {
+    const uint2 ent = sorted[q];
+    const int dx = Rep<true>::x(ent, bits) - x, dy = Rep<true>::y(ent, bits) - y;
+    const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
+    unsigned long long key = ((unsigned long long)(d2) << bits.ib) | (unsigned long long)(ent.y);
+    if (Rep<true>::dead(ent)) key = key_none<unsigned long long>();
+    insert_key<KT>(keys, key);
+  }
+}
+
+// 32-bit entries carry the dead bit in bit 31, above every live key: a dead candidate's key
+// (distance part | index | dead bit) sorts behind all live ones and reads as "none".
+template <int KT>
+__device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y,
+                                           const Bits& bits, const uint32_t* sorted) {
+  if (qb >= qe) return;
+  const uint32_t keep = bits.imask | kDeadBit;
+  uint32_t cur = sorted[qb];
+  for (uint32_t q = qb; q < qe; ++q) {
+    const uint32_t nxt = sorted[q + 1];  // one entry ahead; the table is padded by one
+    const int dx = int(__builtin_amdgcn_ubfe(cur, uint32_t(bits.ib), uint32_t(bits.xb))) - x;
+    const int dy = int(__builtin_amdgcn_ubfe(cur, uint32_t(bits.ib + bits.xb), uint32_t(bits.xb))) - y;
+    const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
+    insert_key<KT>(keys, (d2 << bits.ib) | (cur & keep));
+    cur = nxt;
+  }
+}
+
 template <bool WIDE, int KT>
 __device__ __forceinline__ void nearest_keys(typename Rep<WIDE>::Key (&keys)[KT], int K, int x, int y,
                                              uint32_t self_slot, const Buckets bk, const Bits& bits,
                                              const typename Rep<WIDE>::Entry* sorted, const uint32_t* starts) {
   using Key = typename Rep<WIDE>::Key;
-  const int bx = x >> bk.shift, by = y >> bk.shift, last = bk.nbx - 1;
+  const int bx = bucket_coord(x, bk), by = bucket_coord(y, bk), last = bk.nbx - 1;
   for (int r = 1;; r *= 2) {
 #pragma unroll
     for (int k = 0; k < KT; ++k) keys[k] = key_none<Key>();
     const int x0 = max(bx - r, 0), x1 = min(bx + r, last);
     const int y0 = max(by - r, 0), y1 = min(by + r, last);
     for (int row = y0; row <= y1; ++row) {
-      const uint32_t q_end = starts[row * bk.nbx + x1 + 1];
-      for (uint32_t q = starts[row * bk.nbx + x0]; q < q_end; ++q) {
-        const typename Rep<WIDE>::Entry ent = sorted[q];
-        const int dx = Rep<WIDE>::x(ent, bits) - x, dy = Rep<WIDE>::y(ent, bits) - y;
-        const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
-        Key key = (Key(d2) << bits.ib) | Key(Rep<WIDE>::idx(ent, bits));
-        if (q == self_slot || Rep<WIDE>::dead(ent)) key = key_none<Key>();
-        insert_key<KT>(keys, key);
-      }
+      const uint32_t qb = starts[row * bk.nbx + x0], qe = starts[row * bk.nbx + x1 + 1];
+      const uint32_t split = row == by ? self_slot : qe;
+      scan_range<KT>(keys, qb, split, x, y, bits, sorted);
+      scan_range<KT>(keys, split + 1, qe, x, y, bits, sorted);
     }
     if (bx - r <= 0 && bx + r >= last && by - r <= 0 && by + r >= last) break;
-    const uint64_t reach = uint64_t(r) * (uint64_t(1) << bk.shift) + 1;
+    const uint64_t reach = uint64_t(r) * uint64_t(bk.bmin) + 1;
     if (uint64_t(keys[K - 1]) < ((reach * reach) << bits.ib)) break;
   }
 }
@@ -440,7 +475,7 @@ __device__ __forceinline__ void wave_sync_lds() {
 // by repeated selection, rows written directly (slow path).
 // ----------------------------------------------------------------------------------
 template <bool WIDE, int KX>
-__global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, const int mode,
+__global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_per_eu(8, 8))) void env_kernel(const Params p, const int mode,
                                                              const float* __restrict__ probs, uint32_t g_lo,
                                                              uint32_t g_hi) {
   using R = Rep<WIDE>;
@@ -540,8 +575,8 @@ __global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, con
       for (int i = lt; i < N_tag; i += ts) {
         const uint32_t me = L.pl[i];
         const int x = pos_x_of(me), y = pos_y_of(me);
-        const int bx0 = max(x - p.tag_rad, 0) >> bk.shift, bx1 = min(x + p.tag_rad, G - 1) >> bk.shift;
-        const int by0 = max(y - p.tag_rad, 0) >> bk.shift, by1 = min(y + p.tag_rad, G - 1) >> bk.shift;
+        const int bx0 = bucket_coord(max(x - p.tag_rad, 0), bk), bx1 = bucket_coord(min(x + p.tag_rad, G - 1), bk);
+        const int by0 = bucket_coord(max(y - p.tag_rad, 0), bk), by1 = bucket_coord(min(y + p.tag_rad, G - 1), bk);
         for (int row = by0; row <= by1; ++row) {
           const uint32_t q_end = L.starts[row * bk.nbx + bx1 + 1];
           for (uint32_t q = L.starts[row * bk.nbx + bx0]; q < q_end; ++q) {
@@ -617,6 +652,7 @@ __global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, con
       }
       out_act = true;
     }
+    __syncthreads();  // tag keys and credits are read; the neighbour lists may overlay them
   }
 
   if (mode != kModeStep) {
@@ -688,8 +724,7 @@ __global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, con
 #pragma unroll
           for (int kk = 0; kk < KT; ++kk)
             if (kk < K)
-              L.nbr[me * K + kk] =
-                  keys[kk] == key_none<Key>() ? uint16_t(kNoNeighbour) : uint16_t(keys[kk] & idx_mask);
+              L.nbr[me * K + kk] = key_is_none(keys[kk]) ? uint16_t(kNoNeighbour) : uint16_t(keys[kk] & idx_mask);
         }
       }
     }
@@ -703,9 +738,11 @@ __global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, con
     const int rows_total = min(p.teams_per_wg, p.E - e0) * N;
     float* const obs_wg = p.obs + int64_t(e0) * N * D;
     if (all_out) {
-      float* stage = reinterpret_cast<float*>(smem + p.scratch_base) + wave * kStageRows * D;
+      const int srl = p.stage_rows_log2, stage_rows = 1 << srl, flushes = kWaveSize >> srl;
+      float* stage = reinterpret_cast<float*>(smem + p.x_base) + wave * stage_rows * D;
       const bool vec_ok = ((int64_t(e0) * N * D) & 3) == 0;
-      for (int c = wave; c * kWaveSize < rows_total; c += kWavesPerWorkgroup) {
+      const int waves = p.wg_size >> 6;
+      for (int c = wave; c * kWaveSize < rows_total; c += waves) {
         const int R0 = c * kWaveSize;
         const int Rr = R0 + lane;
         const bool have = Rr < rows_total;
@@ -716,51 +753,37 @@ __global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, con
         }
         const TeamLds<WIDE> Lr(smem, have ? tm : 0, p);
         const float t_frac = static_cast<float>(Lr.misc[1]) * p.inv_T;
+        float row[5 + 4 * (KX > 0 ? KX : 1)];
         if constexpr (KX > 0) {
-          float row[5 + 4 * (KX > 0 ? KX : 1)];
           if (have) write_row<KX>(row, p, Lr.pl, Lr.nbr, i, KX, t_frac);
-#pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            if (have && (lane >> 5) == h) {
-              float* dst = stage + (lane & 31) * D;
+        }
+        for (int h = 0; h < flushes; ++h) {
+          if (have && (lane >> srl) == h) {
+            float* dst = stage + (lane & (stage_rows - 1)) * D;
+            if constexpr (KX > 0) {
 #pragma unroll
               for (int d = 0; d < 5 + 4 * KX; ++d) dst[d] = row[d];
-            }
-            wave_sync_lds();
-            const int nfl = min(max(rows_total - (R0 + h * kStageRows), 0), kStageRows) * D;
-            float* out = obs_wg + int64_t(R0 + h * kStageRows) * D;
-            if (vec_ok) {
-              const int nvec = nfl >> 2;
-              for (int v = lane; v < nvec; v += kWaveSize)
-                reinterpret_cast<float4*>(out)[v] = reinterpret_cast<const float4*>(stage)[v];
-              for (int f = (nvec << 2) + lane; f < nfl; f += kWaveSize) out[f] = stage[f];
             } else {
-              for (int f = lane; f < nfl; f += kWaveSize) out[f] = stage[f];
+              write_row<0>(dst, p, Lr.pl, Lr.nbr, i, K, t_frac);
             }
-            wave_sync_lds();
           }
-        } else {
-#pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            if (have && (lane >> 5) == h) write_row<0>(stage + (lane & 31) * D, p, Lr.pl, Lr.nbr, i, K, t_frac);
-            wave_sync_lds();
-            const int nfl = min(max(rows_total - (R0 + h * kStageRows), 0), kStageRows) * D;
-            float* out = obs_wg + int64_t(R0 + h * kStageRows) * D;
-            if (vec_ok) {
-              const int nvec = nfl >> 2;
-              for (int v = lane; v < nvec; v += kWaveSize)
-                reinterpret_cast<float4*>(out)[v] = reinterpret_cast<const float4*>(stage)[v];
-              for (int f = (nvec << 2) + lane; f < nfl; f += kWaveSize) out[f] = stage[f];
-            } else {
-              for (int f = lane; f < nfl; f += kWaveSize) out[f] = stage[f];
-            }
-            wave_sync_lds();
+          wave_sync_lds();
+          const int nfl = min(max(rows_total - (R0 + h * stage_rows), 0), stage_rows) * D;
+          float* out = obs_wg + int64_t(R0 + h * stage_rows) * D;
+          if (vec_ok) {
+            const int nvec = nfl >> 2;
+            for (int v = lane; v < nvec; v += kWaveSize)
+              reinterpret_cast<float4*>(out)[v] = reinterpret_cast<const float4*>(stage)[v];
+            for (int f = (nvec << 2) + lane; f < nfl; f += kWaveSize) out[f] = stage[f];
+          } else {
+            for (int f = lane; f < nfl; f += kWaveSize) out[f] = stage[f];
           }
+          wave_sync_lds();
         }
       }
     } else {
       // some envs of this workgroup keep their rows: each lane writes its own row in place
-      for (int Rr = tid; Rr < rows_total; Rr += kWorkgroupSize) {
+      for (int Rr = tid; Rr < rows_total; Rr += p.wg_size) {
         const int tm = int(fastdiv(uint32_t(Rr), p.div_N));
         const int i = Rr - tm * N;
         const TeamLds<WIDE> Lr(smem, tm, p);
@@ -825,7 +848,7 @@ __global__ __launch_bounds__(kWorkgroupSize) void env_kernel(const Params p, con
 template <bool WIDE, int KX>
 hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream) {
   const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
-  hipLaunchKernelGGL((env_kernel<WIDE, KX>), dim3(groups), dim3(kWorkgroupSize), size_t(p.lds_bytes), stream, p,
+  hipLaunchKernelGGL((env_kernel<WIDE, KX>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, p,
                      mode, probs, uint32_t(g), uint32_t(g >> 32));
   return hipGetLastError();
 }
