@@ -132,19 +132,37 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p) {
   p->off_best = take(key_bytes * NPAD);
   p->off_credits = take(4ll * c.num_taggers);
   p->off_counts = take(4ll * nb_cap);
-  const int64_t nbr_bytes = register_path ? align16(2 * NPAD * p->K) : 0;
-  p->y_stride = int32_t(std::max<int64_t>(off, nbr_bytes));
-  // the staging area overlays the X parts: 32 rows per wave and flush if that fits, else 16
+  const int64_t y_tables = off;
+  // neighbour lists: K 16-bit ids per agent, or 40 bits per agent when K = 4 and ids fit 10 bits
+  p->compact_nbr = (narrow && p->K == 4 && N < 1024) ? 1 : 0;
+  const int64_t nbr_bytes = !register_path ? 0 : align16(p->compact_nbr ? 5 * NPAD : 2 * NPAD * p->K);
+  // The staging area of the rows (32 or 16 rows per wave and flush) overlays the X parts and,
+  // in a one-team workgroup, the head of the Y part in front of the neighbour lists.
   const int64_t x_area = int64_t(p->x_stride) * tpw;
   const int64_t waves = p->wg_size / wd::kWaveSize;
-  p->stage_rows_log2 = 5;
-  int64_t stage = register_path ? waves * 32 * p->D * 4 : 0;
-  if (stage > x_area) {
-    p->stage_rows_log2 = 4;
-    stage = waves * 16 * p->D * 4;
-  }
+  const int64_t stage32 = register_path ? waves * 32 * p->D * 4 : 0;
+  const int64_t stage16 = register_path ? waves * 16 * p->D * 4 : 0;
+  auto plan_with = [&](int64_t stage, int64_t* x_span, int64_t* y_stride) {
+    if (tpw == 1) {
+      *x_span = x_area;
+      *y_stride = align16(std::max<int64_t>(std::max<int64_t>(y_tables, nbr_bytes), stage + nbr_bytes - x_area));
+    } else {
+      *x_span = std::max<int64_t>(x_area, stage);
+      *y_stride = align16(std::max<int64_t>(y_tables, nbr_bytes));
+    }
+    return p->keep_stride * int64_t(tpw) + *x_span + *y_stride * tpw;
+  };
+  int64_t xs32, ys32, xs16, ys16;
+  const int64_t total32 = plan_with(stage32, &xs32, &ys32);
+  const int64_t total16 = plan_with(stage16, &xs16, &ys16);
+  // 32 rows unless that costs LDS that 16 rows would not (fewer workgroups per compute unit)
+  const bool use32 = total32 <= total16 || (kLdsLimitBytes / total32 == kLdsLimitBytes / total16);
+  p->stage_rows_log2 = use32 ? 5 : 4;
+  const int64_t x_span = use32 ? xs32 : xs16;
+  p->y_stride = int32_t(use32 ? ys32 : ys16);
+  p->off_nbr = int32_t(p->y_stride - nbr_bytes);
   p->x_base = p->keep_stride * tpw;
-  p->y_base = int32_t(p->x_base + std::max<int64_t>(x_area, stage));
+  p->y_base = int32_t(p->x_base + x_span);
   const int64_t total = int64_t(p->y_base) + int64_t(p->y_stride) * tpw;
   p->lds_bytes = int32_t(std::min<int64_t>(total, INT32_MAX));
   return total <= kLdsLimitBytes;

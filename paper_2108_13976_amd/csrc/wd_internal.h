@@ -62,7 +62,8 @@ struct Params {
   // once the rewards are out.
   int32_t keep_stride, off_pl, off_misc;
   int32_t x_base, x_stride, off_sorted, off_starts;
-  int32_t y_base, y_stride, off_slot, off_best, off_credits, off_counts;
+  int32_t y_base, y_stride, off_slot, off_best, off_credits, off_counts, off_nbr;
+  int32_t compact_nbr;   // K = 4 neighbour ids of an agent packed into 40 bits (N < 1024)
   int32_t lds_bytes;
   // device buffers (borrowed from the caller)
   int32_t *pos_x, *pos_y, *pos_x0, *pos_y0, *live, *action;

@@ -279,7 +279,9 @@ struct TeamLds {
   using Key = typename Rep<WIDE>::Key;
   using Entry = typename Rep<WIDE>::Entry;
   uint32_t* pl;      // [NPAD] packed position + dead bit, by agent index
-  uint16_t* nbr;     // [NPAD][K] neighbour indices; overlays slot/best/credits/counts
+  uint16_t* nbr;     // [NPAD][K] neighbour indices; overlays the tail of slot/best/credits/counts
+  uint32_t* nbr_lo;  // compact form for K = 4, N < 1024: ids 0..2 and two bits of id 3 per agent,
+  uint8_t* nbr_hi;   // and the other eight bits of id 3 (same memory as nbr)
   int32_t* misc;     // [0] tags this step, [1] t after the call, [2] rows to be written, [4..11] scan scratch
   Entry* sorted;     // [NPAD] entries of the live agents, grouped by bucket
   uint16_t* slot;    // [NPAD] where agent i sits in `sorted`
@@ -295,7 +297,9 @@ struct TeamLds {
     misc = reinterpret_cast<int32_t*>(keep + p.off_misc);
     sorted = reinterpret_cast<Entry*>(xr + p.off_sorted);
     starts = reinterpret_cast<uint32_t*>(xr + p.off_starts);
-    nbr = reinterpret_cast<uint16_t*>(yr);  // overlays the tables below
+    nbr = reinterpret_cast<uint16_t*>(yr + p.off_nbr);
+    nbr_lo = reinterpret_cast<uint32_t*>(yr + p.off_nbr);
+    nbr_hi = reinterpret_cast<uint8_t*>(yr + p.off_nbr) + 4 * p.NPAD;
     slot = reinterpret_cast<uint16_t*>(yr + p.off_slot);
     best = reinterpret_cast<Key*>(yr + p.off_best);
     credits = reinterpret_cast<int32_t*>(yr + p.off_credits);
@@ -430,13 +434,16 @@ __device__ __forceinline__ void nearest_keys(typename Rep<WIDE>::Key (&keys)[KT]
   }
 }
 
+constexpr uint32_t kCompactNone = 1023u;  // "no neighbour" in the compact 10-bit form
+
 // One observation row (own features + K neighbour slots) written to `row` (registers, LDS
-// or global).  KC > 0 fixes K at compile time so that the row can live in registers.
-template <int KC, typename Ptr>
-__device__ __forceinline__ void write_row(Ptr row, const Params& p, const uint32_t* pl, const uint16_t* nbr, int i,
-                                          int k_runtime, float t_frac) {
+// or global).  KC > 0 fixes K at compile time so that the row can live in registers.  CN:
+// the neighbour ids of agent i come from the compact form (K = 4).
+template <int KC, bool CN, bool WIDE, typename Ptr>
+__device__ __forceinline__ void write_row(Ptr row, const Params& p, const TeamLds<WIDE>& L, int i, int k_runtime,
+                                          float t_frac) {
   const int K = KC > 0 ? KC : k_runtime;
-  const uint32_t me = pl[i];
+  const uint32_t me = L.pl[i];
   const int x = pos_x_of(me), y = pos_y_of(me);
   const bool lv = !(me & kDeadBit);
   row[0] = static_cast<float>(x) * p.inv_G;
@@ -444,12 +451,25 @@ __device__ __forceinline__ void write_row(Ptr row, const Params& p, const uint32
   row[2] = i < p.N_tag ? 1.0f : 0.0f;
   row[3] = lv ? 1.0f : 0.0f;
   row[4] = t_frac;
+  uint32_t lo = 0, hi = 0;
+  if constexpr (CN) {
+    lo = L.nbr_lo[i];
+    hi = L.nbr_hi[i];
+  }
 #pragma unroll
   for (int kk = 0; kk < K; ++kk) {
-    const uint32_t j = lv ? uint32_t(nbr[i * K + kk]) : kNoNeighbour;
+    uint32_t j;
+    bool none;
+    if constexpr (CN) {
+      j = kk < 3 ? ((lo >> (10 * kk)) & 1023u) : ((lo >> 30) | (hi << 2));
+      none = !lv || j == kCompactNone;
+    } else {
+      j = lv ? uint32_t(L.nbr[i * K + kk]) : kNoNeighbour;
+      none = j == kNoNeighbour;
+    }
     float f0 = 0.0f, f1 = 0.0f, f2 = 0.0f, f3 = 0.0f;
-    if (j != kNoNeighbour) {
-      const uint32_t other = pl[j];
+    if (!none) {
+      const uint32_t other = L.pl[j];
       f0 = static_cast<float>(pos_x_of(other) - x) * p.inv_G;
       f1 = static_cast<float>(pos_y_of(other) - y) * p.inv_G;
       f2 = int(j) < p.N_tag ? 1.0f : 0.0f;
@@ -474,7 +494,7 @@ __device__ __forceinline__ void wave_sync_lds() {
 // neighbour list in registers and send rows through the LDS transpose.  KX < 0: any K,
 // by repeated selection, rows written directly (slow path).
 // ----------------------------------------------------------------------------------
-template <bool WIDE, int KX>
+template <bool WIDE, int KX, bool CN>
 __global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_per_eu(8, 8))) void env_kernel(const Params p, const int mode,
                                                              const float* __restrict__ probs, uint32_t g_lo,
                                                              uint32_t g_hi) {
@@ -721,10 +741,18 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_p
           nearest_keys<WIDE, KT>(keys, K, R::x(ent, bits), R::y(ent, bits), uint32_t(q), bk, bits, L.sorted,
                                  L.starts);
           const uint32_t me = R::idx(ent, bits);
+          if constexpr (CN) {
+            uint32_t id[4];
 #pragma unroll
-          for (int kk = 0; kk < KT; ++kk)
-            if (kk < K)
-              L.nbr[me * K + kk] = key_is_none(keys[kk]) ? uint16_t(kNoNeighbour) : uint16_t(keys[kk] & idx_mask);
+            for (int kk = 0; kk < 4; ++kk) id[kk] = key_is_none(keys[kk]) ? kCompactNone : uint32_t(keys[kk] & idx_mask);
+            L.nbr_lo[me] = id[0] | (id[1] << 10) | (id[2] << 20) | (id[3] << 30);
+            L.nbr_hi[me] = uint8_t(id[3] >> 2);
+          } else {
+#pragma unroll
+            for (int kk = 0; kk < KT; ++kk)
+              if (kk < K)
+                L.nbr[me * K + kk] = key_is_none(keys[kk]) ? uint16_t(kNoNeighbour) : uint16_t(keys[kk] & idx_mask);
+          }
         }
       }
     }
@@ -755,7 +783,7 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_p
         const float t_frac = static_cast<float>(Lr.misc[1]) * p.inv_T;
         float row[5 + 4 * (KX > 0 ? KX : 1)];
         if constexpr (KX > 0) {
-          if (have) write_row<KX>(row, p, Lr.pl, Lr.nbr, i, KX, t_frac);
+          if (have) write_row<KX, CN>(row, p, Lr, i, KX, t_frac);
         }
         for (int h = 0; h < flushes; ++h) {
           if (have && (lane >> srl) == h) {
@@ -764,7 +792,7 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_p
 #pragma unroll
               for (int d = 0; d < 5 + 4 * KX; ++d) dst[d] = row[d];
             } else {
-              write_row<0>(dst, p, Lr.pl, Lr.nbr, i, K, t_frac);
+              write_row<0, false>(dst, p, Lr, i, K, t_frac);
             }
           }
           wave_sync_lds();
@@ -772,8 +800,16 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_p
           float* out = obs_wg + int64_t(R0 + h * stage_rows) * D;
           if (vec_ok) {
             const int nvec = nfl >> 2;
-            for (int v = lane; v < nvec; v += kWaveSize)
-              reinterpret_cast<float4*>(out)[v] = reinterpret_cast<const float4*>(stage)[v];
+            if constexpr (KX > 0 && KX <= 4) {  // at most 32 * 21 / 4 = 168 vectors: three predicated stores
+#pragma unroll
+              for (int it = 0; it < 3; ++it) {
+                const int v = lane + it * kWaveSize;
+                if (v < nvec) reinterpret_cast<float4*>(out)[v] = reinterpret_cast<const float4*>(stage)[v];
+              }
+            } else {
+              for (int v = lane; v < nvec; v += kWaveSize)
+                reinterpret_cast<float4*>(out)[v] = reinterpret_cast<const float4*>(stage)[v];
+            }
             for (int f = (nvec << 2) + lane; f < nfl; f += kWaveSize) out[f] = stage[f];
           } else {
             for (int f = lane; f < nfl; f += kWaveSize) out[f] = stage[f];
@@ -788,7 +824,7 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_p
         const int i = Rr - tm * N;
         const TeamLds<WIDE> Lr(smem, tm, p);
         if (Lr.misc[2])
-          write_row<0>(obs_wg + int64_t(Rr) * D, p, Lr.pl, Lr.nbr, i, K, static_cast<float>(Lr.misc[1]) * p.inv_T);
+          write_row<(KX > 0 ? KX : 0), CN>(obs_wg + int64_t(Rr) * D, p, Lr, i, K, static_cast<float>(Lr.misc[1]) * p.inv_T);
       }
     }
   } else {
@@ -845,17 +881,17 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_p
   }
 }
 
-template <bool WIDE, int KX>
+template <bool WIDE, int KX, bool CN>
 hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream) {
   const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
-  hipLaunchKernelGGL((env_kernel<WIDE, KX>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, p,
+  hipLaunchKernelGGL((env_kernel<WIDE, KX, CN>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, p,
                      mode, probs, uint32_t(g), uint32_t(g >> 32));
   return hipGetLastError();
 }
 
-template <bool WIDE, int KX>
+template <bool WIDE, int KX, bool CN>
 hipError_t prepare_env_variant(const Params& p) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&env_kernel<WIDE, KX>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&env_kernel<WIDE, KX, CN>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
 }
 
@@ -868,17 +904,18 @@ int variant_of(const Params& p) {
 
 }  // namespace
 
-#define WD_DISPATCH(fn, ...)                                      \
-  do {                                                            \
-    const int kx = variant_of(p);                                 \
-    if (!p.wide) {                                                \
-      if (kx == 4) return fn<false, 4>(p, ##__VA_ARGS__);         \
-      if (kx == 0) return fn<false, 0>(p, ##__VA_ARGS__);         \
-      return fn<false, -1>(p, ##__VA_ARGS__);                     \
-    }                                                             \
-    if (kx == 4) return fn<true, 4>(p, ##__VA_ARGS__);            \
-    if (kx == 0) return fn<true, 0>(p, ##__VA_ARGS__);            \
-    return fn<true, -1>(p, ##__VA_ARGS__);                        \
+#define WD_DISPATCH(fn, ...)                                             \
+  do {                                                                   \
+    const int kx = variant_of(p);                                        \
+    if (!p.wide) {                                                       \
+      if (kx == 4 && p.compact_nbr) return fn<false, 4, true>(p, ##__VA_ARGS__); \
+      if (kx == 4) return fn<false, 4, false>(p, ##__VA_ARGS__);         \
+      if (kx == 0) return fn<false, 0, false>(p, ##__VA_ARGS__);         \
+      return fn<false, -1, false>(p, ##__VA_ARGS__);                     \
+    }                                                                    \
+    if (kx == 4) return fn<true, 4, false>(p, ##__VA_ARGS__);            \
+    if (kx == 0) return fn<true, 0, false>(p, ##__VA_ARGS__);            \
+    return fn<true, -1, false>(p, ##__VA_ARGS__);                        \
   } while (0)
 
 hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream) {
