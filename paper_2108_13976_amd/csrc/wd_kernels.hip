@@ -378,8 +378,8 @@ __device__ __forceinline__ void insert_key(unsigned long long (&keys)[KT], unsig
 // Scans the (2r+1)^2 buckets around the agent's own; every agent outside that block is
 // farther than r bucket widths in x or in y, so once the K-th key is below (r*bmin+1)^2 (or
 // the block covers the grid) no unseen agent can enter the list; otherwise r doubles and
-// the scan restarts.  The agent's own entry is left out by splitting its bucket row at
-// its slot.
+// only the buckets that the wider block adds are scanned.  The agent's own entry is left
+// out by splitting its bucket row at its slot.
 template <int KT>
 __device__ __forceinline__ void scan_range(unsigned long long (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y,
                                            const Bits& bits, const uint2* sorted) {
@@ -417,20 +417,34 @@ __device__ __forceinline__ void nearest_keys(typename Rep<WIDE>::Key (&keys)[KT]
                                              const typename Rep<WIDE>::Entry* sorted, const uint32_t* starts) {
   using Key = typename Rep<WIDE>::Key;
   const int bx = bucket_coord(x, bk), by = bucket_coord(y, bk), last = bk.nbx - 1;
-  for (int r = 1;; r *= 2) {
 #pragma unroll
-    for (int k = 0; k < KT; ++k) keys[k] = key_none<Key>();
+  for (int k = 0; k < KT; ++k) keys[k] = key_none<Key>();
+  int px0 = 1, px1 = 0, py0 = 1, py1 = 0;  // block already scanned (empty)
+  for (int r = 1;; r *= 2) {
     const int x0 = max(bx - r, 0), x1 = min(bx + r, last);
     const int y0 = max(by - r, 0), y1 = min(by + r, last);
     for (int row = y0; row <= y1; ++row) {
-      const uint32_t qb = starts[row * bk.nbx + x0], qe = starts[row * bk.nbx + x1 + 1];
-      const uint32_t split = row == by ? self_slot : qe;
-      scan_range<KT>(keys, qb, split, x, y, bits, sorted);
-      scan_range<KT>(keys, split + 1, qe, x, y, bits, sorted);
+      const uint32_t* rs = starts + row * bk.nbx;
+      if (row < py0 || row > py1) {
+        // a row the earlier block did not touch; the agent's own row (first ring only) is
+        // split at its slot so that it does not meet itself
+        const uint32_t qb = rs[x0], qe = rs[x1 + 1];
+        const uint32_t split = row == by ? self_slot : qe;
+        scan_range<KT>(keys, qb, split, x, y, bits, sorted);
+        scan_range<KT>(keys, split + 1, qe, x, y, bits, sorted);
+      } else {
+        // only the buckets left and right of the earlier block are new
+        if (x0 < px0) scan_range<KT>(keys, rs[x0], rs[px0], x, y, bits, sorted);
+        if (x1 > px1) scan_range<KT>(keys, rs[px1 + 1], rs[x1 + 1], x, y, bits, sorted);
+      }
     }
     if (bx - r <= 0 && bx + r >= last && by - r <= 0 && by + r >= last) break;
     const uint64_t reach = uint64_t(r) * uint64_t(bk.bmin) + 1;
     if (uint64_t(keys[K - 1]) < ((reach * reach) << bits.ib)) break;
+    px0 = x0;
+    px1 = x1;
+    py0 = y0;
+    py1 = y1;
   }
 }
 
@@ -495,7 +509,7 @@ __device__ __forceinline__ void wave_sync_lds() {
 // by repeated selection, rows written directly (slow path).
 // ----------------------------------------------------------------------------------
 template <bool WIDE, int KX, bool CN>
-__global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_per_eu(8, 8))) void env_kernel(const Params p, const int mode,
+__global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_per_eu(WIDE ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
                                                              const float* __restrict__ probs, uint32_t g_lo,
                                                              uint32_t g_hi) {
   using R = Rep<WIDE>;
