@@ -112,6 +112,9 @@ def main():
     ap.add_argument("--mode", choices=("fused", "separate"), default="fused")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="instead of the benchmark, run a plain device copy of this many MiB ten times "
+                         "(the known-size kernel that calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; envs would shard across GPUs with no exchange, "
@@ -126,6 +129,16 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
+    if args.copy_probe_mib:
+        n = args.copy_probe_mib * 1024 * 1024 // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_mib": args.copy_probe_mib, "reads_kib": args.copy_probe_mib * 1024,
+                          "writes_kib": args.copy_probe_mib * 1024}))
+        return
     cfg = CONFIGS[args.workload]
     ring = device_probs_ring(cfg.seed, RING, cfg.num_envs, cfg.num_agents, "cuda:0")
     torch.cuda.synchronize()
