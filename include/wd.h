@@ -21,8 +21,10 @@
  *     the default stream) and are NOT synchronised: the caller synchronises
  *     before reading results on the host.  Calls on one handle must be issued
  *     from one host thread at a time.
- *   - The library allocates no device memory for these entry points: all state
- *     lives in the caller's buffers, the handle holds host metadata only.
+ *   - All state lives in the caller's buffers.  The library allocates no device
+ *     memory, with one exception: for envs too large for a workgroup's LDS
+ *     (thousands of agents) wd_create allocates per-env work tables once on the
+ *     current device (about 18 bytes per agent) and wd_destroy frees them.
  *   - Random numbers are Philox4x32-10 blocks keyed by (seed, global env id,
  *     agent, global step g, stream), so results do not depend on launch shape,
  *     and a run over envs [a, b) with env_offset = a reproduces those envs of the
@@ -104,7 +106,8 @@ int wd_query_layout(const wd_config* cfg, wd_layout* out);
 
 /* Validates cfg and bufs (range, alignment), chooses the launch geometry and
  * returns a handle in *out.  Enqueues nothing; the buffers' contents are not read.
- * WD_E_UNSUPPORTED if no kernel of this build covers the configuration. */
+ * WD_E_UNSUPPORTED if no kernel of this build covers the configuration; WD_E_HIP
+ * if the work tables of a large-env configuration cannot be allocated. */
 int wd_create(const wd_config* cfg, const wd_buffers* bufs, wd_handle** out);
 
 /* Environment reset (Sec. 4.5 item 5 "Automatic Environment Resetting").
@@ -119,8 +122,8 @@ int wd_reset(wd_handle* h, int mode);
 /* Action sampling (Sec. 4.5 item 6 "Thread-parallelized Action Sampling").
  * probs: device [E][N][5] float32 policy outputs.  Writes action[e][i] for EVERY
  * agent of EVERY env by inverse CDF (float32 running sum, left to right, strict
- * "u < sum", last action as fall-through) with u from the random block of
- * (seed, env_offset + e, i, g, stream 0).  Does not advance g. */
+ * "u < sum", last action as fall-through) with u from word i mod 4 of the random
+ * block of (seed, env_offset + e, i / 4, g, stream 0).  Does not advance g. */
 int wd_sample(wd_handle* h, const float* probs);
 
 /* One Tag step (Sec. 5.1; Sec. 4.5 items 3-4) for every env with done == 0, in
@@ -137,8 +140,9 @@ int wd_iterate(wd_handle* h, const float* probs);
 int wd_get_step(wd_handle* h, uint64_t* g);
 int wd_set_step(wd_handle* h, uint64_t g);
 
-/* Frees the handle (host memory only).  The caller's buffers are not touched;
- * work already enqueued on the stream is not waited for. */
+/* Frees the handle and, for large-env configurations, its work tables (the caller
+ * must have synchronised the stream first in that case).  The caller's buffers are
+ * not touched. */
 int wd_destroy(wd_handle* h);
 
 /* Static text for a status code. */

@@ -18,6 +18,7 @@ struct wd_handle {
   hipStream_t stream;
   uint64_t g;          // global step: RNG step index
   bool started;        // wd_reset(WD_RESET_ALL) has run
+  void* scratch;       // device memory of the large-env tables (NULL for the small layout)
   std::string last_error;
 };
 
@@ -73,12 +74,17 @@ bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) 
 
 // Launch geometry and LDS map of the env-per-team kernels.  Returns false if an env does
 // not fit one workgroup's LDS.
-bool plan_env_kernels(const wd_config& c, wd::Params* p) {
+bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   const int N = c.num_agents, G = c.grid_size;
   p->NG = (N + 3) / 4;
+  p->big = big ? 1 : 0;
   int ts_log2 = 3;
   while ((1 << ts_log2) < p->NG && ts_log2 < 8) ++ts_log2;
   p->wg_size = 256;
+  if (big) {  // one env per 1024-thread workgroup
+    ts_log2 = 10;
+    p->wg_size = wd::kBigEnvWorkgroupSize;
+  }
   const int ts = 1 << ts_log2;
   p->ts_log2 = ts_log2;
   p->teams_per_wg = p->wg_size / ts;
@@ -121,21 +127,27 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p) {
   const int64_t NPAD = p->NPAD;
   const int tpw = p->teams_per_wg;
   p->off_pl = take(4 * NPAD);
-  p->off_misc = take(64);
+  p->off_misc = take(128);
   p->keep_stride = int32_t(off);
   off = 0;
   p->off_sorted = take(key_bytes * (NPAD + 4));  // padded: the search reads one entry ahead
   p->off_starts = take(4ll * (nb_cap + 4));
   p->x_stride = int32_t(off);
   off = 0;
-  p->off_slot = take(2 * NPAD);
-  p->off_best = take(key_bytes * NPAD);
-  p->off_credits = take(4ll * c.num_taggers);
+  if (!big) {
+    p->off_slot = take(2 * NPAD);
+    p->off_best = take(key_bytes * NPAD);
+    p->off_credits = take(4ll * c.num_taggers);
+  }
   p->off_counts = take(4ll * nb_cap);
   const int64_t y_tables = off;
   // neighbour lists: K 16-bit ids per agent, or 40 bits per agent when K = 4 and ids fit 10 bits
-  p->compact_nbr = (narrow && p->K == 4 && N < 1024) ? 1 : 0;
-  const int64_t nbr_bytes = !register_path ? 0 : align16(p->compact_nbr ? 5 * NPAD : 2 * NPAD * p->K);
+  p->compact_nbr = (!big && narrow && p->K == 4 && N < 1024) ? 1 : 0;
+  const int64_t nbr_bytes = (!register_path || big) ? 0 : align16(p->compact_nbr ? 5 * NPAD : 2 * NPAD * p->K);
+  // per-env strides of the tables a large env keeps in device memory
+  p->g_stride_agents = NPAD;
+  p->g_stride_credits = (c.num_taggers + 3) / 4 * 4;
+  p->g_stride_nbr = NPAD * int64_t(std::max(p->K, 1));
   // The staging area of the rows (32 or 16 rows per wave and flush) overlays the X parts and,
   // in a one-team workgroup, the head of the Y part in front of the neighbour lists.
   const int64_t x_area = int64_t(p->x_stride) * tpw;
@@ -200,7 +212,7 @@ int fill_params(const wd_config& c, const wd_buffers& b, wd::Params* p) {
   p->done = b.done;
   p->n_live_runners = b.n_live_runners;
   p->tags_step = b.tags_step;
-  if (!plan_env_kernels(c, p)) return WD_E_UNSUPPORTED;
+  if (!plan_env_kernels(c, p, false) && !plan_env_kernels(c, p, true)) return WD_E_UNSUPPORTED;
   if (!wd::env_kernel_available(*p)) return WD_E_UNSUPPORTED;
   return WD_OK;
 }
@@ -244,6 +256,23 @@ int wd_create(const wd_config* cfg, const wd_buffers* bufs, wd_handle** out) {
   if (rc != WD_OK) return rc;
   wd_handle* h = new (std::nothrow) wd_handle();
   if (!h) return WD_E_NULL;
+  h->scratch = nullptr;
+  if (params.big) {
+    // large envs: slots, tag keys, credits and neighbour lists of every env, in one allocation
+    const int64_t E = cfg->num_envs, key_bytes = params.wide ? 8 : 4;
+    const int64_t slot_b = align16(2 * params.g_stride_agents * E), best_b = align16(key_bytes * params.g_stride_agents * E);
+    const int64_t cred_b = align16(4 * params.g_stride_credits * E), nbr_b = align16(2 * params.g_stride_nbr * E);
+    if (hipMalloc(&h->scratch, size_t(slot_b + best_b + cred_b + nbr_b)) != hipSuccess) {
+      (void)hipGetLastError();
+      delete h;
+      return WD_E_HIP;
+    }
+    unsigned char* base = static_cast<unsigned char*>(h->scratch);
+    params.g_best = base;
+    params.g_credits = reinterpret_cast<int32_t*>(base + best_b);
+    params.g_slot = reinterpret_cast<uint16_t*>(base + best_b + cred_b);
+    params.g_nbr = reinterpret_cast<uint16_t*>(base + best_b + cred_b + slot_b);
+  }
   h->cfg = *cfg;
   h->bufs = *bufs;
   h->params = params;
@@ -319,6 +348,7 @@ int wd_set_step(wd_handle* h, uint64_t g) {
 
 int wd_destroy(wd_handle* h) {
   if (!h) return WD_E_NULL;
+  if (h->scratch) (void)hipFree(h->scratch);
   delete h;
   return WD_OK;
 }

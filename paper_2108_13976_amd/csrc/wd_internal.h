@@ -9,7 +9,8 @@
 namespace wd {
 
 constexpr int kWorkgroupSize = 256;     // flat per-agent kernels: four wave64s
-constexpr int kMaxEnvWorkgroupSize = 512;  // env-per-team kernels run 256 or 512 threads
+constexpr int kMaxEnvWorkgroupSize = 512;  // env-per-team kernels run 256 or 512 threads,
+constexpr int kBigEnvWorkgroupSize = 1024; // or 1024 for an env too large for the small layout
 constexpr int kWaveSize = 64;
 constexpr int kNumActions = 5;
 constexpr int kMaxRegisterK = 8;        // K up to this keeps the candidate list in registers
@@ -65,6 +66,15 @@ struct Params {
   int32_t y_base, y_stride, off_slot, off_best, off_credits, off_counts, off_nbr;
   int32_t compact_nbr;   // K = 4 neighbour ids of an agent packed into 40 bits (N < 1024)
   int32_t lds_bytes;
+  // Large envs (big != 0): one 1024-thread workgroup per env; slots, tag keys, credits and
+  // neighbour lists live in library-owned device memory instead of LDS (per-env strides in
+  // elements of each array's type).
+  int32_t big;
+  uint16_t* g_slot;
+  void* g_best;
+  int32_t* g_credits;
+  uint16_t* g_nbr;
+  int64_t g_stride_agents, g_stride_credits, g_stride_nbr;
   // device buffers (borrowed from the caller)
   int32_t *pos_x, *pos_y, *pos_x0, *pos_y0, *live, *action;
   float* reward;

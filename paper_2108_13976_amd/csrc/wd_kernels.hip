@@ -273,8 +273,9 @@ __device__ __forceinline__ int bucket_of(int x, int y, const Buckets bk) {
   return bucket_coord(y, bk) * bk.nbx + bucket_coord(x, bk);
 }
 
-// LDS views of one team's regions.
-template <bool WIDE>
+// Views of one team's tables: in LDS, except that a large env (BIG) keeps slots, tag keys,
+// credits and neighbour lists in device memory.
+template <bool WIDE, bool BIG>
 struct TeamLds {
   using Key = typename Rep<WIDE>::Key;
   using Entry = typename Rep<WIDE>::Entry;
@@ -289,7 +290,7 @@ struct TeamLds {
   int32_t* credits;  // [N_tag]
   uint32_t* counts;  // [nb_cap] bucket counts, then scatter cursors
   uint32_t* starts;  // [nb_cap + 1] bucket start offsets in `sorted`
-  __device__ __forceinline__ TeamLds(unsigned char* smem, int team, const Params& p) {
+  __device__ __forceinline__ TeamLds(unsigned char* smem, int team, const Params& p, int env) {
     unsigned char* keep = smem + team * p.keep_stride;
     unsigned char* xr = smem + p.x_base + team * p.x_stride;
     unsigned char* yr = smem + p.y_base + team * p.y_stride;
@@ -297,21 +298,30 @@ struct TeamLds {
     misc = reinterpret_cast<int32_t*>(keep + p.off_misc);
     sorted = reinterpret_cast<Entry*>(xr + p.off_sorted);
     starts = reinterpret_cast<uint32_t*>(xr + p.off_starts);
-    nbr = reinterpret_cast<uint16_t*>(yr + p.off_nbr);
-    nbr_lo = reinterpret_cast<uint32_t*>(yr + p.off_nbr);
-    nbr_hi = reinterpret_cast<uint8_t*>(yr + p.off_nbr) + 4 * p.NPAD;
-    slot = reinterpret_cast<uint16_t*>(yr + p.off_slot);
-    best = reinterpret_cast<Key*>(yr + p.off_best);
-    credits = reinterpret_cast<int32_t*>(yr + p.off_credits);
     counts = reinterpret_cast<uint32_t*>(yr + p.off_counts);
+    if constexpr (BIG) {
+      nbr = p.g_nbr + env * p.g_stride_nbr;
+      nbr_lo = nullptr;
+      nbr_hi = nullptr;
+      slot = p.g_slot + env * p.g_stride_agents;
+      best = reinterpret_cast<Key*>(p.g_best) + env * p.g_stride_agents;
+      credits = p.g_credits + env * p.g_stride_credits;
+    } else {
+      nbr = reinterpret_cast<uint16_t*>(yr + p.off_nbr);
+      nbr_lo = reinterpret_cast<uint32_t*>(yr + p.off_nbr);
+      nbr_hi = reinterpret_cast<uint8_t*>(yr + p.off_nbr) + 4 * p.NPAD;
+      slot = reinterpret_cast<uint16_t*>(yr + p.off_slot);
+      best = reinterpret_cast<Key*>(yr + p.off_best);
+      credits = reinterpret_cast<int32_t*>(yr + p.off_credits);
+    }
   }
 };
 
 // Second half of the counting sort: bucket counts -> start offsets -> entries in bucket
 // order.  `act` marks teams that take part; every thread of the workgroup must call
 // (barriers inside).  Requires pl[] written and counts[] filled, and a barrier after that.
-template <bool WIDE>
-__device__ __forceinline__ void scan_and_scatter(const Params& p, const TeamLds<WIDE>& L, bool act, int lt, int ts,
+template <bool WIDE, typename Tables>
+__device__ __forceinline__ void scan_and_scatter(const Params& p, const Tables& L, bool act, int lt, int ts,
                                                  const Buckets bk, const Bits& bits) {
   int part = 0;
   const int j0 = lt * p.scan_chunk;
@@ -453,8 +463,8 @@ constexpr uint32_t kCompactNone = 1023u;  // "no neighbour" in the compact 10-bi
 // One observation row (own features + K neighbour slots) written to `row` (registers, LDS
 // or global).  KC > 0 fixes K at compile time so that the row can live in registers.  CN:
 // the neighbour ids of agent i come from the compact form (K = 4).
-template <int KC, bool CN, bool WIDE, typename Ptr>
-__device__ __forceinline__ void write_row(Ptr row, const Params& p, const TeamLds<WIDE>& L, int i, int k_runtime,
+template <int KC, bool CN, typename Tables, typename Ptr>
+__device__ __forceinline__ void write_row(Ptr row, const Params& p, const Tables& L, int i, int k_runtime,
                                           float t_frac) {
   const int K = KC > 0 ? KC : k_runtime;
   const uint32_t me = L.pl[i];
@@ -508,8 +518,9 @@ __device__ __forceinline__ void wave_sync_lds() {
 // neighbour list in registers and send rows through the LDS transpose.  KX < 0: any K,
 // by repeated selection, rows written directly (slow path).
 // ----------------------------------------------------------------------------------
-template <bool WIDE, int KX, bool CN>
-__global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_per_eu(WIDE ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
+template <bool WIDE, int KX, bool CN, bool BIG>
+__global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
+    __attribute__((amdgpu_waves_per_eu((WIDE || BIG || KX == 0) ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
                                                              const float* __restrict__ probs, uint32_t g_lo,
                                                              uint32_t g_hi) {
   using R = Rep<WIDE>;
@@ -527,7 +538,7 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_p
   const bool vec = p.vec4 != 0;
   const bool valid = e < p.E;
   const int64_t abase = int64_t(valid ? e : 0) * N;
-  const TeamLds<WIDE> L(smem, team, p);
+  const TeamLds<WIDE, BIG> L(smem, team, p, e);
   Bits bits;
   bits.ib = p.idx_bits;
   bits.xb = p.xy_bits;
@@ -793,7 +804,7 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_p
           tm = int(fastdiv(uint32_t(Rr), p.div_N));
           i = Rr - tm * N;
         }
-        const TeamLds<WIDE> Lr(smem, have ? tm : 0, p);
+        const TeamLds<WIDE, BIG> Lr(smem, have ? tm : 0, p, e0 + (have ? tm : 0));
         const float t_frac = static_cast<float>(Lr.misc[1]) * p.inv_T;
         float row[5 + 4 * (KX > 0 ? KX : 1)];
         if constexpr (KX > 0) {
@@ -836,7 +847,7 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_p
       for (int Rr = tid; Rr < rows_total; Rr += p.wg_size) {
         const int tm = int(fastdiv(uint32_t(Rr), p.div_N));
         const int i = Rr - tm * N;
-        const TeamLds<WIDE> Lr(smem, tm, p);
+        const TeamLds<WIDE, BIG> Lr(smem, tm, p, e0 + tm);
         if (Lr.misc[2])
           write_row<(KX > 0 ? KX : 0), CN>(obs_wg + int64_t(Rr) * D, p, Lr, i, K, static_cast<float>(Lr.misc[1]) * p.inv_T);
       }
@@ -895,17 +906,17 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize) __attribute__((amdgpu_waves_p
   }
 }
 
-template <bool WIDE, int KX, bool CN>
+template <bool WIDE, int KX, bool CN, bool BIG>
 hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream) {
   const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
-  hipLaunchKernelGGL((env_kernel<WIDE, KX, CN>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, p,
+  hipLaunchKernelGGL((env_kernel<WIDE, KX, CN, BIG>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, p,
                      mode, probs, uint32_t(g), uint32_t(g >> 32));
   return hipGetLastError();
 }
 
-template <bool WIDE, int KX, bool CN>
+template <bool WIDE, int KX, bool CN, bool BIG>
 hipError_t prepare_env_variant(const Params& p) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&env_kernel<WIDE, KX, CN>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&env_kernel<WIDE, KX, CN, BIG>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
 }
 
@@ -918,18 +929,26 @@ int variant_of(const Params& p) {
 
 }  // namespace
 
-#define WD_DISPATCH(fn, ...)                                             \
-  do {                                                                   \
-    const int kx = variant_of(p);                                        \
-    if (!p.wide) {                                                       \
-      if (kx == 4 && p.compact_nbr) return fn<false, 4, true>(p, ##__VA_ARGS__); \
-      if (kx == 4) return fn<false, 4, false>(p, ##__VA_ARGS__);         \
-      if (kx == 0) return fn<false, 0, false>(p, ##__VA_ARGS__);         \
-      return fn<false, -1, false>(p, ##__VA_ARGS__);                     \
-    }                                                                    \
-    if (kx == 4) return fn<true, 4, false>(p, ##__VA_ARGS__);            \
-    if (kx == 0) return fn<true, 0, false>(p, ##__VA_ARGS__);            \
-    return fn<true, -1, false>(p, ##__VA_ARGS__);                        \
+#define WD_DISPATCH(fn, ...)                                                               \
+  do {                                                                                     \
+    const int kx = variant_of(p);                                                          \
+    if (p.big) {                                                                           \
+      if (!p.wide) {                                                                       \
+        if (kx == 4) return fn<false, 4, false, true>(p, ##__VA_ARGS__);                   \
+        return fn<false, 0, false, true>(p, ##__VA_ARGS__);                                \
+      }                                                                                    \
+      if (kx == 4) return fn<true, 4, false, true>(p, ##__VA_ARGS__);                      \
+      return fn<true, 0, false, true>(p, ##__VA_ARGS__);                                   \
+    }                                                                                      \
+    if (!p.wide) {                                                                         \
+      if (kx == 4 && p.compact_nbr) return fn<false, 4, true, false>(p, ##__VA_ARGS__);    \
+      if (kx == 4) return fn<false, 4, false, false>(p, ##__VA_ARGS__);                    \
+      if (kx == 0) return fn<false, 0, false, false>(p, ##__VA_ARGS__);                    \
+      return fn<false, -1, false, false>(p, ##__VA_ARGS__);                                \
+    }                                                                                      \
+    if (kx == 4) return fn<true, 4, false, false>(p, ##__VA_ARGS__);                       \
+    if (kx == 0) return fn<true, 0, false, false>(p, ##__VA_ARGS__);                       \
+    return fn<true, -1, false, false>(p, ##__VA_ARGS__);                                   \
   } while (0)
 
 hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream) {
@@ -938,7 +957,7 @@ hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint
 
 hipError_t prepare_env_kernels(const Params& p) { WD_DISPATCH(prepare_env_variant); }
 
-bool env_kernel_available(const Params& p) { return p.obs_mode == 0; }
+bool env_kernel_available(const Params& p) { return p.obs_mode == 0 && !(p.big && p.K > kMaxRegisterK); }
 
 hipError_t launch_sample(const Params& p, const float* probs, uint64_t g, hipStream_t stream) {
   const int64_t total = int64_t(p.E) * p.NG;

@@ -135,6 +135,19 @@ def test_rollout_20000x100_env_slice():
              full_envs=cfg.num_envs, check_every=5, sharded=8)
 
 
+def test_rollout_10x8192_all_envs():
+    """The agent-parallel stress workload (one env exceeds a workgroup's LDS: large-env layout),
+    all 10 envs, separate calls, oracle sharded over threads."""
+    cfg = CONFIGS["tag_10x8192"]
+    lockstep(cfg.kwargs(), 12, cfg.seed, fused=False, sharded=10)
+
+
+def test_rollout_10x8192_fused_across_episode_ends():
+    cfg = CONFIGS["tag_10x8192"]
+    kw = dict(cfg.kwargs(), num_envs=3, episode_length=7)
+    lockstep(kw, 17, cfg.seed, fused=True, full_envs=3, sharded=3)
+
+
 # ---- the headline workload at full size, in the launch configuration the benchmark times ----------
 def test_headline_workload_full_size_sampled_envs_and_invariants():
     import paper_2108_13976_amd as wd
@@ -226,6 +239,8 @@ EDGE = {
     "thousand_agents_dense": dict(num_envs=3, num_agents=1000, num_taggers=100, grid_size=12, episode_length=20, obs_k=4, tag_r2=0),
     "thousand_twenty_four": dict(num_envs=2, num_agents=1024, num_taggers=1, grid_size=64, episode_length=8, obs_k=2),
     "many_agents_one_team": dict(num_envs=2, num_agents=1500, num_taggers=50, grid_size=90, episode_length=8, obs_k=4),
+    "large_env_narrow_keys": dict(num_envs=2, num_agents=8192, num_taggers=700, grid_size=100, episode_length=4, obs_k=4),
+    "large_env_k_two": dict(num_envs=2, num_agents=6001, num_taggers=3, grid_size=300, episode_length=3, obs_k=2),
     "odd_rewards": dict(num_envs=12, num_agents=25, num_taggers=5, grid_size=8, episode_length=20, obs_k=2,
                         tag_reward=0.3, tag_penalty=-2.5),
 }
@@ -236,4 +251,4 @@ EDGE = {
 def test_edge_case(name, fused):
     kw = dict(seed=77, **EDGE[name])
     steps = min(3 * kw["episode_length"], 60)
-    lockstep(kw, steps, 77, fused=fused)
+    lockstep(kw, steps, 77, fused=fused, sharded=2 if kw["num_agents"] > 4000 else 0)
