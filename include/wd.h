@@ -14,8 +14,9 @@
  *     aborts.  On failure nothing has been enqueued unless stated otherwise.
  *   - All pointers inside wd_buffers and the `probs` arguments are DEVICE
  *     pointers (hipMalloc'd or PyTorch-allocated), owned by the caller and only
- *     borrowed until wd_destroy.  Each must be 256-byte aligned and hold at least
- *     the element count that wd_query_layout reports.  All other pointers
+ *     borrowed until wd_destroy.  Each buffer must be 256-byte aligned (probs:
+ *     16-byte aligned) and hold at least the element count that wd_query_layout
+ *     reports.  All other pointers
  *     (config, layout, handle, out parameters) are HOST pointers.
  *   - Kernels are enqueued on wd_config.stream (a hipStream_t, borrowed; NULL =
  *     the default stream) and are NOT synchronised: the caller synchronises
@@ -46,7 +47,7 @@ typedef enum wd_status {
   WD_OK = 0,
   WD_E_NULL = -1,   /* a required pointer is NULL                                   */
   WD_E_CONFIG = -2, /* a config field is out of range or struct_size mismatches     */
-  WD_E_ALIGN = -3,  /* a device buffer is not 256-byte aligned                      */
+  WD_E_ALIGN = -3,  /* a device buffer is not aligned as required                   */
   WD_E_STATE = -4,  /* call order: sample/step/reset(DONE) before the first reset(ALL) */
   WD_E_HIP = -5,    /* a HIP call failed; wd_last_error(handle) has the text        */
   WD_E_UNSUPPORTED = -6 /* valid config that this build has no kernel for           */

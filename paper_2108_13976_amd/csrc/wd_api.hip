@@ -72,6 +72,11 @@ int32_t obs_dim(const wd_config* c) {
 
 bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
+// probs is read with 16-byte loads when N % 4 == 0, with 4-byte loads otherwise
+bool probs_aligned(const wd::Params& p, const void* probs) {
+  return (reinterpret_cast<uintptr_t>(probs) & (p.vec4 ? 15u : 3u)) == 0;
+}
+
 // Launch geometry and LDS map of the env-per-team kernels.  Returns false if an env does
 // not fit one workgroup's LDS.
 bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
@@ -308,7 +313,7 @@ int wd_reset(wd_handle* h, int mode) {
 
 int wd_sample(wd_handle* h, const float* probs) {
   if (!h || !probs) return WD_E_NULL;
-  if (!aligned256(probs)) return WD_E_ALIGN;
+  if (!probs_aligned(h->params, probs)) return WD_E_ALIGN;
   if (!h->started) return WD_E_STATE;
   const hipError_t err = wd::launch_sample(h->params, probs, h->g, h->stream);
   if (err != hipSuccess) return hip_failed(h, err, "sample kernel");
@@ -326,7 +331,7 @@ int wd_step(wd_handle* h) {
 
 int wd_iterate(wd_handle* h, const float* probs) {
   if (!h || !probs) return WD_E_NULL;
-  if (!aligned256(probs)) return WD_E_ALIGN;
+  if (!probs_aligned(h->params, probs)) return WD_E_ALIGN;
   if (!h->started) return WD_E_STATE;
   const hipError_t err = wd::launch_env_kernel(h->params, wd::kModeIterate, probs, h->g, h->stream);
   if (err != hipSuccess) return hip_failed(h, err, "iterate kernel");
@@ -358,7 +363,7 @@ const char* wd_strerror(int status) {
     case WD_OK: return "ok";
     case WD_E_NULL: return "a required pointer is NULL";
     case WD_E_CONFIG: return "configuration field out of range";
-    case WD_E_ALIGN: return "device buffer not 256-byte aligned";
+    case WD_E_ALIGN: return "device buffer not aligned as required";
     case WD_E_STATE: return "call before the first wd_reset(WD_RESET_ALL)";
     case WD_E_HIP: return "HIP call failed";
     case WD_E_UNSUPPORTED: return "configuration not covered by this build's kernels";
