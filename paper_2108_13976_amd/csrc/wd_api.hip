@@ -109,7 +109,7 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   uint32_t mul_max = 65536u;
   if (G > 1) mul_max = uint32_t(std::min<uint64_t>(65536u, ((uint64_t(side) << 16) - 1) / uint64_t(G - 1)));
   p->bucket_mul_max = mul_max;
-  const double lambda = 3.0;  // target live agents per bucket
+  const double lambda = 5.0;  // target live agents per bucket
   p->bucket_scale = float(65536.0 / (double(G) * std::sqrt(lambda)));
   p->div_N = wd::make_fastdiv(uint32_t(N));
   p->div_NG = wd::make_fastdiv(uint32_t(p->NG));
@@ -118,7 +118,21 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   p->idx_bits = bits_for(uint32_t(N - 1));
   p->xy_bits = bits_for(uint32_t(G - 1));
   const uint64_t d2max = 2ull * uint64_t(G - 1) * uint64_t(G - 1);
-  const bool narrow = (1 + 2 * p->xy_bits + p->idx_bits <= 32) && (((d2max + 1) << p->idx_bits) <= (1ull << 31));
+  // 32-bit form: live keys stay below 2^31, and a dead mark (x + dead_dx) exists that puts the
+  // squared distance of a marked entry from any grid cell into [2^(31-ib), 2^(32-ib))
+  bool narrow = false;
+  p->dead_dx = 0;
+  if (p->idx_bits <= 16) {
+    const uint64_t band = 1ull << (31 - p->idx_bits);
+    uint64_t lo = uint64_t(std::sqrt(double(band)));
+    while (lo * lo < band) ++lo;
+    const uint64_t shift = lo + uint64_t(G - 1);
+    const uint64_t far = shift + uint64_t(G - 1);
+    if (d2max + 1 <= band && far <= 32767 && far * far + uint64_t(G - 1) * uint64_t(G - 1) < 2 * band) {
+      narrow = true;
+      p->dead_dx = int32_t(shift);
+    }
+  }
   p->wide = narrow ? 0 : 1;
   const int key_bytes = narrow ? 4 : 8;
   const bool register_path = p->K <= wd::kMaxRegisterK;
@@ -133,10 +147,12 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   const int tpw = p->teams_per_wg;
   p->off_pl = take(4 * NPAD);
   p->off_misc = take(128);
+  p->off_edges = take(2 * (side + 2));
   p->keep_stride = int32_t(off);
   off = 0;
-  p->off_sorted = take(key_bytes * (NPAD + 4));  // padded: the search reads one entry ahead
-  p->off_starts = take(4ll * (nb_cap + 4));
+  p->off_sorted = take((narrow ? 4 : 8) * (NPAD + 4));
+  p->off_sorted_id = take(narrow ? 2 * (NPAD + 4) : 0);
+  p->off_starts = take(2ll * (nb_cap + 4));
   p->x_stride = int32_t(off);
   off = 0;
   if (!big) {

@@ -56,13 +56,14 @@ struct Params {
   uint32_t bucket_mul_max;  // largest multiplier whose bucket table fits nb_cap
   // (distance, index) keys and bucket entries: 32-bit when wide == 0
   int32_t wide, idx_bits, xy_bits;
+  int32_t dead_dx;       // 32-bit form: x offset that marks a runner tagged in this step
   FastDiv div_N, div_NG;
   // LDS map.  Per team: a kept part (positions, scalars); an X part (bucket-sorted entries
   // and bucket starts) that the row staging area overlays once the neighbour search is done;
   // a Y part (slots, tag keys, credits, bucket counters) that the neighbour lists overlay
   // once the rewards are out.
-  int32_t keep_stride, off_pl, off_misc;
-  int32_t x_base, x_stride, off_sorted, off_starts;
+  int32_t keep_stride, off_pl, off_misc, off_edges;
+  int32_t x_base, x_stride, off_sorted, off_sorted_id, off_starts;
   int32_t y_base, y_stride, off_slot, off_best, off_credits, off_counts, off_nbr;
   int32_t compact_nbr;   // K = 4 neighbour ids of an agent packed into 40 bits (N < 1024)
   int32_t lds_bytes;

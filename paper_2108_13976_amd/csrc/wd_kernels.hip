@@ -153,45 +153,58 @@ __global__ __launch_bounds__(kWorkgroupSize) void init_start_positions_kernel(co
 }
 
 // ----------------------------------------------------------------------------------
-// Keys and bucket entries.  A key is (squared distance << idx_bits) | agent index, so
-// unsigned comparison orders by distance first and index second.  A bucket entry holds
-// a live agent's position and index.  Both are 32-bit when the grid and agent count
-// allow (NARROW), else 64-bit (WIDE).
+// Keys and the bucket-sorted list.  A key is (squared distance << idx_bits) | agent index,
+// so unsigned comparison orders by distance first and index second.  The sorted list holds
+// position and index of the live agents, grouped by bucket.
+//   NARROW (32-bit keys): positions x | y << 16 in one array, 16-bit indices in another; the
+//     squared distance of a candidate is one packed 16-bit subtract and one two-element dot
+//     product.  A runner tagged in this step is marked by adding `dead_dx` to its x: that
+//     puts its squared distance from any agent on the grid into the band whose key has bit
+//     31 set, above every live key, so it sorts last and reads as "no neighbour".
+//   WIDE (64-bit keys): entries (x | y << 16 | dead bit, index).
 // ----------------------------------------------------------------------------------
-struct Bits {
-  int ib, xb;             // bits of an agent index, bits of a coordinate
-  uint32_t imask, xmask;
+typedef short short2v __attribute__((ext_vector_type(2)));
+
+struct Ent {
+  uint32_t pos;  // x | y << 16 (plus the dead mark of the representation)
+  uint32_t id;   // agent index
 };
 
 template <bool WIDE>
-struct Rep;
+struct SortedList;
 
 template <>
-struct Rep<false> {
+struct SortedList<false> {
   using Key = uint32_t;
-  using Entry = uint32_t;
-  static __device__ __forceinline__ Entry make(int x, int y, int i, const Bits& b) {
-    return uint32_t(i) | (uint32_t(x) << b.ib) | (uint32_t(y) << (b.ib + b.xb));
+  uint32_t* pos;
+  uint16_t* id;
+  int dead_dx;
+  __device__ __forceinline__ Ent get(uint32_t q) const { return Ent{pos[q], uint32_t(id[q])}; }
+  __device__ __forceinline__ void put(uint32_t q, int x, int y, int i) const {
+    pos[q] = uint32_t(x) | (uint32_t(y) << 16);
+    id[q] = uint16_t(i);
   }
-  static __device__ __forceinline__ int x(Entry e, const Bits& b) { return int((e >> b.ib) & b.xmask); }
-  static __device__ __forceinline__ int y(Entry e, const Bits& b) { return int((e >> (b.ib + b.xb)) & b.xmask); }
-  static __device__ __forceinline__ uint32_t idx(Entry e, const Bits& b) { return e & b.imask; }
-  static __device__ __forceinline__ bool dead(Entry e) { return (e & kDeadBit) != 0; }
-  static __device__ __forceinline__ void mark_dead(Entry* e) { *e |= kDeadBit; }
+  __device__ __forceinline__ void mark_dead(uint32_t q) const { pos[q] += uint32_t(dead_dx); }
+  __device__ __forceinline__ bool dead(const Ent& e) const { return int(e.pos & 0xFFFFu) >= dead_dx; }
+  static __device__ __forceinline__ int x(const Ent& e) { return int(e.pos & 0xFFFFu); }
+  static __device__ __forceinline__ int y(const Ent& e) { return int(e.pos >> 16); }
 };
 
 template <>
-struct Rep<true> {
+struct SortedList<true> {
   using Key = unsigned long long;
-  using Entry = uint2;
-  static __device__ __forceinline__ Entry make(int x, int y, int i, const Bits&) {
-    return make_uint2(uint32_t(x) | (uint32_t(y) << 16), uint32_t(i));
+  uint2* ent;
+  __device__ __forceinline__ Ent get(uint32_t q) const {
+    const uint2 v = ent[q];
+    return Ent{v.x, v.y};
   }
-  static __device__ __forceinline__ int x(Entry e, const Bits&) { return int(e.x & 0x7FFFu); }
-  static __device__ __forceinline__ int y(Entry e, const Bits&) { return int((e.x >> 16) & 0x7FFFu); }
-  static __device__ __forceinline__ uint32_t idx(Entry e, const Bits&) { return e.y; }
-  static __device__ __forceinline__ bool dead(Entry e) { return (e.x & kDeadBit) != 0; }
-  static __device__ __forceinline__ void mark_dead(Entry* e) { e->x |= kDeadBit; }
+  __device__ __forceinline__ void put(uint32_t q, int x, int y, int i) const {
+    ent[q] = make_uint2(uint32_t(x) | (uint32_t(y) << 16), uint32_t(i));
+  }
+  __device__ __forceinline__ void mark_dead(uint32_t q) const { ent[q].x |= kDeadBit; }
+  __device__ __forceinline__ bool dead(const Ent& e) const { return (e.pos & kDeadBit) != 0; }
+  static __device__ __forceinline__ int x(const Ent& e) { return int(e.pos & 0x7FFFu); }
+  static __device__ __forceinline__ int y(const Ent& e) { return int((e.pos >> 16) & 0x7FFFu); }
 };
 
 template <typename Key>
@@ -269,6 +282,11 @@ __device__ __forceinline__ Buckets choose_buckets(const Params& p, int n_live) {
 
 __device__ __forceinline__ int bucket_coord(int x, const Buckets bk) { return int(__umul24(uint32_t(x), bk.mul) >> 16); }
 
+// First cell of bucket coordinate b: the smallest x with (x * mul) >> 16 == b.
+__device__ __forceinline__ int bucket_first_cell(int b, const Buckets bk) {
+  return int((uint32_t(b) * 65536u + bk.mul - 1u) / bk.mul);
+}
+
 __device__ __forceinline__ int bucket_of(int x, int y, const Buckets bk) {
   return bucket_coord(y, bk) * bk.nbx + bucket_coord(x, bk);
 }
@@ -277,27 +295,34 @@ __device__ __forceinline__ int bucket_of(int x, int y, const Buckets bk) {
 // credits and neighbour lists in device memory.
 template <bool WIDE, bool BIG>
 struct TeamLds {
-  using Key = typename Rep<WIDE>::Key;
-  using Entry = typename Rep<WIDE>::Entry;
+  using Key = typename SortedList<WIDE>::Key;
   uint32_t* pl;      // [NPAD] packed position + dead bit, by agent index
   uint16_t* nbr;     // [NPAD][K] neighbour indices; overlays the tail of slot/best/credits/counts
   uint32_t* nbr_lo;  // compact form for K = 4, N < 1024: ids 0..2 and two bits of id 3 per agent,
   uint8_t* nbr_hi;   // and the other eight bits of id 3 (same memory as nbr)
-  int32_t* misc;     // [0] tags this step, [1] t after the call, [2] rows to be written, [4..11] scan scratch
-  Entry* sorted;     // [NPAD] entries of the live agents, grouped by bucket
+  int32_t* misc;     // [0] tags this step, [1] t after the call, [2] rows to be written, [4..19] scan scratch
+  uint16_t* edges;   // [nbx + 1] first cell of each bucket coordinate; edges[nbx] = G
+  SortedList<WIDE> sorted;  // [NPAD + pad] the live agents, grouped by bucket
   uint16_t* slot;    // [NPAD] where agent i sits in `sorted`
   Key* best;         // [NPAD] per runner: smallest (distance, tagger) key in range
   int32_t* credits;  // [N_tag]
   uint32_t* counts;  // [nb_cap] bucket counts, then scatter cursors
-  uint32_t* starts;  // [nb_cap + 1] bucket start offsets in `sorted`
+  uint16_t* starts;  // [nb_cap + 1] bucket start offsets in `sorted`
   __device__ __forceinline__ TeamLds(unsigned char* smem, int team, const Params& p, int env) {
     unsigned char* keep = smem + team * p.keep_stride;
     unsigned char* xr = smem + p.x_base + team * p.x_stride;
     unsigned char* yr = smem + p.y_base + team * p.y_stride;
     pl = reinterpret_cast<uint32_t*>(keep + p.off_pl);
     misc = reinterpret_cast<int32_t*>(keep + p.off_misc);
-    sorted = reinterpret_cast<Entry*>(xr + p.off_sorted);
-    starts = reinterpret_cast<uint32_t*>(xr + p.off_starts);
+    edges = reinterpret_cast<uint16_t*>(keep + p.off_edges);
+    if constexpr (WIDE) {
+      sorted.ent = reinterpret_cast<uint2*>(xr + p.off_sorted);
+    } else {
+      sorted.pos = reinterpret_cast<uint32_t*>(xr + p.off_sorted);
+      sorted.id = reinterpret_cast<uint16_t*>(xr + p.off_sorted_id);
+      sorted.dead_dx = p.dead_dx;
+    }
+    starts = reinterpret_cast<uint16_t*>(xr + p.off_starts);
     counts = reinterpret_cast<uint32_t*>(yr + p.off_counts);
     if constexpr (BIG) {
       nbr = p.g_nbr + env * p.g_stride_nbr;
@@ -322,7 +347,7 @@ struct TeamLds {
 // (barriers inside).  Requires pl[] written and counts[] filled, and a barrier after that.
 template <bool WIDE, typename Tables>
 __device__ __forceinline__ void scan_and_scatter(const Params& p, const Tables& L, bool act, int lt, int ts,
-                                                 const Buckets bk, const Bits& bits) {
+                                                 const Buckets bk) {
   int part = 0;
   const int j0 = lt * p.scan_chunk;
   if (act)
@@ -332,11 +357,11 @@ __device__ __forceinline__ void scan_and_scatter(const Params& p, const Tables& 
   if (act) {
     for (int c = 0; c < p.scan_chunk; ++c) {
       const int v = int(L.counts[j0 + c]);
-      L.starts[j0 + c] = uint32_t(run);
+      L.starts[j0 + c] = uint16_t(run);
       L.counts[j0 + c] = uint32_t(run);
       run += v;
     }
-    if (lt == ts - 1) L.starts[p.nb_cap] = uint32_t(total);
+    if (lt == ts - 1) L.starts[p.nb_cap] = uint16_t(total);
   }
   __syncthreads();
   if (act) {
@@ -350,7 +375,7 @@ __device__ __forceinline__ void scan_and_scatter(const Params& p, const Tables& 
           if (!(v[j] & kDeadBit)) {
             const int x = pos_x_of(v[j]), y = pos_y_of(v[j]);
             const uint32_t at = atomicAdd(&L.counts[bucket_of(x, y, bk)], 1u);
-            L.sorted[at] = Rep<WIDE>::make(x, y, i0 + j, bits);
+            L.sorted.put(at, x, y, i0 + j);
             L.slot[i0 + j] = uint16_t(at);
           }
         }
@@ -386,71 +411,82 @@ __device__ __forceinline__ void insert_key(unsigned long long (&keys)[KT], unsig
 
 // The K smallest (squared distance, index) keys among the other live agents, exactly.
 // Scans the (2r+1)^2 buckets around the agent's own; every agent outside that block is
-// farther than r bucket widths in x or in y, so once the K-th key is below (r*bmin+1)^2 (or
-// the block covers the grid) no unseen agent can enter the list; otherwise r doubles and
-// only the buckets that the wider block adds are scanned.  The agent's own entry is left
+// beyond a side of the block, so once the K-th key is nearer than the nearest cell beyond any
+// side (or the block covers the grid) no unseen agent can enter the list; otherwise r doubles
+// and only the buckets that the wider block adds, and that are near enough to matter, are scanned.  The agent's own entry is left
 // out by splitting its bucket row at its slot.
 template <int KT>
 __device__ __forceinline__ void scan_range(unsigned long long (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y,
-                                           const Bits& bits, const uint2* sorted) {
+                                           int ib, const SortedList<true>& sorted) {
   for (uint32_t q = qb; q < qe; ++q) {
-    const uint2 ent = sorted[q];
-    const int dx = Rep<true>::x(ent, bits) - x, dy = Rep<true>::y(ent, bits) - y;
+    const Ent ent = sorted.get(q);
+    const int dx = SortedList<true>::x(ent) - x, dy = SortedList<true>::y(ent) - y;
     const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
-    unsigned long long key = ((unsigned long long)(d2) << bits.ib) | (unsigned long long)(ent.y);
-    if (Rep<true>::dead(ent)) key = key_none<unsigned long long>();
+    unsigned long long key = ((unsigned long long)(d2) << ib) | (unsigned long long)(ent.id);
+    if (sorted.dead(ent)) key = key_none<unsigned long long>();
     insert_key<KT>(keys, key);
   }
 }
 
-// 32-bit entries carry the dead bit in bit 31, above every live key: a dead candidate's key
-// (distance part | index | dead bit) sorts behind all live ones and reads as "none".
 template <int KT>
-__device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y,
-                                           const Bits& bits, const uint32_t* sorted) {
-  if (qb >= qe) return;
-  const uint32_t keep = bits.imask | kDeadBit;
-  uint32_t cur = sorted[qb];
+__device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y, int ib,
+                                           const SortedList<false>& sorted) {
+  const short2v me = __builtin_bit_cast(short2v, uint32_t(x) | (uint32_t(y) << 16));
   for (uint32_t q = qb; q < qe; ++q) {
-    const uint32_t nxt = sorted[q + 1];  // one entry ahead; the table is padded by one
-    const int dx = int(__builtin_amdgcn_ubfe(cur, uint32_t(bits.ib), uint32_t(bits.xb))) - x;
-    const int dy = int(__builtin_amdgcn_ubfe(cur, uint32_t(bits.ib + bits.xb), uint32_t(bits.xb))) - y;
-    const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
-    insert_key<KT>(keys, (d2 << bits.ib) | (cur & keep));
-    cur = nxt;
+    const short2v d = __builtin_bit_cast(short2v, sorted.pos[q]) - me;       // (dx, dy), one packed subtract
+    const uint32_t d2 = uint32_t(__builtin_amdgcn_sdot2(d, d, 0, false));    // dx*dx + dy*dy
+    insert_key<KT>(keys, (d2 << ib) | uint32_t(sorted.id[q]));
   }
 }
 
 template <bool WIDE, int KT>
-__device__ __forceinline__ void nearest_keys(typename Rep<WIDE>::Key (&keys)[KT], int K, int x, int y,
-                                             uint32_t self_slot, const Buckets bk, const Bits& bits,
-                                             const typename Rep<WIDE>::Entry* sorted, const uint32_t* starts) {
-  using Key = typename Rep<WIDE>::Key;
+__device__ __forceinline__ void nearest_keys(typename SortedList<WIDE>::Key (&keys)[KT], int K, int x, int y,
+                                             uint32_t self_slot, const Buckets bk, int ib,
+                                             const SortedList<WIDE>& sorted, const uint16_t* starts,
+                                             const uint16_t* edges) {
+  using Key = typename SortedList<WIDE>::Key;
   const int bx = bucket_coord(x, bk), by = bucket_coord(y, bk), last = bk.nbx - 1;
 #pragma unroll
   for (int k = 0; k < KT; ++k) keys[k] = key_none<Key>();
   int px0 = 1, px1 = 0, py0 = 1, py1 = 0;  // block already scanned (empty)
+  uint32_t kth_d2 = ~0u;                   // squared distance of the K-th key so far
   for (int r = 1;; r *= 2) {
     const int x0 = max(bx - r, 0), x1 = min(bx + r, last);
     const int y0 = max(by - r, 0), y1 = min(by + r, last);
     for (int row = y0; row <= y1; ++row) {
-      const uint32_t* rs = starts + row * bk.nbx;
+      const uint16_t* rs = starts + row * bk.nbx;
       if (row < py0 || row > py1) {
-        // a row the earlier block did not touch; the agent's own row (first ring only) is
-        // split at its slot so that it does not meet itself
+        // A row the earlier block did not touch.  It cannot improve the list if even its
+        // nearest cell is farther than the K-th key (equal distance could still win on index).
+        const int gap = row > by ? int(edges[row]) - y : y - (int(edges[row + 1]) - 1);
+        if (r > 1 && uint32_t(gap * gap) > kth_d2) continue;
+        // the agent's own row (first ring only) is split at its slot so that it does not meet itself
         const uint32_t qb = rs[x0], qe = rs[x1 + 1];
         const uint32_t split = row == by ? self_slot : qe;
-        scan_range<KT>(keys, qb, split, x, y, bits, sorted);
-        scan_range<KT>(keys, split + 1, qe, x, y, bits, sorted);
+        scan_range<KT>(keys, qb, split, x, y, ib, sorted);
+        scan_range<KT>(keys, split + 1, qe, x, y, ib, sorted);
       } else {
         // only the buckets left and right of the earlier block are new
-        if (x0 < px0) scan_range<KT>(keys, rs[x0], rs[px0], x, y, bits, sorted);
-        if (x1 > px1) scan_range<KT>(keys, rs[px1 + 1], rs[x1 + 1], x, y, bits, sorted);
+        if (x0 < px0) {
+          const int gap = x - (int(edges[px0]) - 1);
+          if (uint32_t(gap * gap) <= kth_d2) scan_range<KT>(keys, rs[x0], rs[px0], x, y, ib, sorted);
+        }
+        if (x1 > px1) {
+          const int gap = int(edges[px1 + 1]) - x;
+          if (uint32_t(gap * gap) <= kth_d2) scan_range<KT>(keys, rs[px1 + 1], rs[x1 + 1], x, y, ib, sorted);
+        }
       }
+      if (!key_is_none(keys[K - 1])) kth_d2 = uint32_t(keys[K - 1] >> ib);
     }
-    if (bx - r <= 0 && bx + r >= last && by - r <= 0 && by + r >= last) break;
-    const uint64_t reach = uint64_t(r) * uint64_t(bk.bmin) + 1;
-    if (uint64_t(keys[K - 1]) < ((reach * reach) << bits.ib)) break;
+    // Every agent not scanned yet lies beyond a side of the block that is not the grid's
+    // edge; `reach` is the distance to the nearest cell beyond such a side.
+    int reach = 65535;
+    if (x0 > 0) reach = min(reach, x - int(edges[x0]) + 1);
+    if (x1 < last) reach = min(reach, int(edges[x1 + 1]) - x);
+    if (y0 > 0) reach = min(reach, y - int(edges[y0]) + 1);
+    if (y1 < last) reach = min(reach, int(edges[y1 + 1]) - y);
+    if (reach == 65535) break;  // the block covers the grid
+    if (kth_d2 < uint32_t(reach * reach)) break;
     px0 = x0;
     px1 = x1;
     py0 = y0;
@@ -491,18 +527,14 @@ __device__ __forceinline__ void write_row(Ptr row, const Params& p, const Tables
       j = lv ? uint32_t(L.nbr[i * K + kk]) : kNoNeighbour;
       none = j == kNoNeighbour;
     }
-    float f0 = 0.0f, f1 = 0.0f, f2 = 0.0f, f3 = 0.0f;
-    if (!none) {
-      const uint32_t other = L.pl[j];
-      f0 = static_cast<float>(pos_x_of(other) - x) * p.inv_G;
-      f1 = static_cast<float>(pos_y_of(other) - y) * p.inv_G;
-      f2 = int(j) < p.N_tag ? 1.0f : 0.0f;
-      f3 = 1.0f;
-    }
-    row[5 + 4 * kk + 0] = f0;
-    row[5 + 4 * kk + 1] = f1;
-    row[5 + 4 * kk + 2] = f2;
-    row[5 + 4 * kk + 3] = f3;
+    // no branch: an empty slot looks up the agent itself, whose offsets are zero, so only
+    // the two flags need the mask
+    const uint32_t jj = none ? uint32_t(i) : j;
+    const uint32_t other = L.pl[jj];
+    row[5 + 4 * kk + 0] = static_cast<float>(pos_x_of(other) - x) * p.inv_G;
+    row[5 + 4 * kk + 1] = static_cast<float>(pos_y_of(other) - y) * p.inv_G;
+    row[5 + 4 * kk + 2] = (!none && int(jj) < p.N_tag) ? 1.0f : 0.0f;
+    row[5 + 4 * kk + 3] = none ? 0.0f : 1.0f;
   }
 }
 
@@ -523,9 +555,8 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
     __attribute__((amdgpu_waves_per_eu((WIDE || BIG || KX == 0) ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
                                                              const float* __restrict__ probs, uint32_t g_lo,
                                                              uint32_t g_hi) {
-  using R = Rep<WIDE>;
-  using Key = typename R::Key;
-  using Entry = typename R::Entry;
+  using SL = SortedList<WIDE>;
+  using Key = typename SL::Key;
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x;
   const int ts = 1 << p.ts_log2;
@@ -539,11 +570,6 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
   const bool valid = e < p.E;
   const int64_t abase = int64_t(valid ? e : 0) * N;
   const TeamLds<WIDE, BIG> L(smem, team, p, e);
-  Bits bits;
-  bits.ib = p.idx_bits;
-  bits.xb = p.xy_bits;
-  bits.imask = (1u << p.idx_bits) - 1u;
-  bits.xmask = (1u << p.xy_bits) - 1u;
   const Key idx_mask = (Key(1) << p.idx_bits) - 1;
 
   int done_in = 0, t_in = 0, nlr_in = 0;
@@ -562,6 +588,7 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
   if (stepping) {
     if (step_act) {
       for (int j = lt; j < p.nb_cap; j += ts) L.counts[j] = 0u;
+      for (int j = lt; j <= bk.nbx; j += ts) L.edges[j] = uint16_t(min(bucket_first_cell(j, bk), G));
       for (int j = lt; j < N_tag; j += ts) L.credits[j] = 0;
       if (lt == 0) L.misc[0] = 0;
     }
@@ -612,7 +639,7 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
       }
     }
     __syncthreads();
-    scan_and_scatter<WIDE>(p, L, step_act, lt, ts, bk, bits);
+    scan_and_scatter<WIDE>(p, L, step_act, lt, ts, bk);
 
     // ---- tag check, from the tagger's side: runners in range get the smallest
     //      (distance, tagger) key; min is order-independent, so the result is unique ----
@@ -625,10 +652,10 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
         for (int row = by0; row <= by1; ++row) {
           const uint32_t q_end = L.starts[row * bk.nbx + bx1 + 1];
           for (uint32_t q = L.starts[row * bk.nbx + bx0]; q < q_end; ++q) {
-            const Entry ent = L.sorted[q];
-            const int j = int(R::idx(ent, bits));
+            const Ent ent = L.sorted.get(q);
+            const int j = int(ent.id);
             if (j < N_tag) continue;
-            const int dx = R::x(ent, bits) - x, dy = R::y(ent, bits) - y;
+            const int dx = SL::x(ent) - x, dy = SL::y(ent) - y;
             const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
             if (d2 <= uint32_t(p.tag_r2)) atomicMin(&L.best[j], (Key(d2) << p.idx_bits) | Key(i));
           }
@@ -653,7 +680,7 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
               if (b != key_none<Key>()) {
                 me |= kDeadBit;
                 L.pl[i] = me;
-                R::mark_dead(&L.sorted[L.slot[i]]);
+                L.sorted.mark_dead(L.slot[i]);
                 atomicAdd(&L.credits[int(b & idx_mask)], 1);
                 ++my_tags;
                 any = true;
@@ -708,6 +735,7 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
       if (reset_act) {
         bk = choose_buckets(p, N);
         for (int j = lt; j < p.nb_cap; j += ts) L.counts[j] = 0u;
+        for (int j = lt; j <= bk.nbx; j += ts) L.edges[j] = uint16_t(min(bucket_first_cell(j, bk), G));
       }
       __syncthreads();
       if (reset_act) {
@@ -745,7 +773,7 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
         out_act = true;
       }
       __syncthreads();
-      scan_and_scatter<WIDE>(p, L, reset_act, lt, ts, bk, bits);
+      scan_and_scatter<WIDE>(p, L, reset_act, lt, ts, bk);
     }
   }
 
@@ -760,12 +788,12 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
     if (out_act && K > 0) {
       const int n_sorted = int(L.starts[p.nb_cap]);
       for (int q = lt; q < n_sorted; q += ts) {
-        const Entry ent = L.sorted[q];
-        if (!R::dead(ent)) {
+        const Ent ent = L.sorted.get(q);
+        if (!L.sorted.dead(ent)) {
           Key keys[KT];
-          nearest_keys<WIDE, KT>(keys, K, R::x(ent, bits), R::y(ent, bits), uint32_t(q), bk, bits, L.sorted,
-                                 L.starts);
-          const uint32_t me = R::idx(ent, bits);
+          nearest_keys<WIDE, KT>(keys, K, SL::x(ent), SL::y(ent), uint32_t(q), bk, p.idx_bits, L.sorted, L.starts,
+                                 L.edges);
+          const uint32_t me = ent.id;
           if constexpr (CN) {
             uint32_t id[4];
 #pragma unroll
@@ -809,6 +837,32 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
         float row[5 + 4 * (KX > 0 ? KX : 1)];
         if constexpr (KX > 0) {
           if (have) write_row<KX, CN>(row, p, Lr, i, KX, t_frac);
+        }
+        if constexpr (KX > 0 && KX <= 4) {
+          if (vec_ok && srl == 5 && R0 + kWaveSize <= rows_total) {
+            // a full chunk: two flushes of 32 rows = 168 16-byte pieces each, no bounds to test
+            constexpr int DD = 5 + 4 * KX;
+            constexpr int kPieces = 32 * DD / 4;
+            float4* out4 = reinterpret_cast<float4*>(obs_wg + int64_t(R0) * DD) + lane;
+            const float4* st4 = reinterpret_cast<const float4*>(stage) + lane;
+            float* dst = stage + (lane & 31) * DD;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              if ((lane >> 5) == h) {
+#pragma unroll
+                for (int d = 0; d < DD; ++d) dst[d] = row[d];
+              }
+              wave_sync_lds();
+              const float4 a = st4[0], b = st4[kWaveSize];
+              float4 c = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+              if (lane + 2 * kWaveSize < kPieces) c = st4[2 * kWaveSize];
+              out4[h * kPieces] = a;
+              out4[h * kPieces + kWaveSize] = b;
+              if (lane + 2 * kWaveSize < kPieces) out4[h * kPieces + 2 * kWaveSize] = c;
+              wave_sync_lds();
+            }
+            continue;
+          }
         }
         for (int h = 0; h < flushes; ++h) {
           if (have && (lane >> srl) == h) {
@@ -875,11 +929,11 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
           Key bestk = key_none<Key>();
           if (!exhausted) {
             for (int q = 0; q < n_sorted; ++q) {
-              const Entry ent = L.sorted[q];
-              if (int(R::idx(ent, bits)) == i || R::dead(ent)) continue;
-              const int dx = R::x(ent, bits) - x, dy = R::y(ent, bits) - y;
+              const Ent ent = L.sorted.get(q);
+              if (int(ent.id) == i || L.sorted.dead(ent)) continue;
+              const int dx = SL::x(ent) - x, dy = SL::y(ent) - y;
               const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
-              const Key key = (Key(d2) << p.idx_bits) | Key(R::idx(ent, bits));
+              const Key key = (Key(d2) << p.idx_bits) | Key(ent.id);
               if ((!have_prev || key > prev) && key < bestk) bestk = key;
             }
           }
