@@ -109,7 +109,7 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   uint32_t mul_max = 65536u;
   if (G > 1) mul_max = uint32_t(std::min<uint64_t>(65536u, ((uint64_t(side) << 16) - 1) / uint64_t(G - 1)));
   p->bucket_mul_max = mul_max;
-  const double lambda = 5.0;  // target live agents per bucket
+  const double lambda = 4.0;  // target live agents per bucket
   p->bucket_scale = float(65536.0 / (double(G) * std::sqrt(lambda)));
   p->div_N = wd::make_fastdiv(uint32_t(N));
   p->div_NG = wd::make_fastdiv(uint32_t(p->NG));
