@@ -79,6 +79,35 @@ def time_gpu(cfg, ring, steps, warmup, mode, **over):
     return wall, event_s, stats, bytes_per_iteration
 
 
+def time_sampler(cfg, ring, reps=200):
+    """wd_sample and torch.multinomial on the same [E*N, 5] probabilities: actions per second."""
+    import torch
+    import paper_2108_13976_amd as wd
+
+    env = wd.TagEnvs(device="cuda:0", **cfg.kwargs())
+    env.reset(wd.WD_RESET_ALL)
+    flat = [r.view(-1, 5) for r in ring]
+
+    def timed(fn):
+        for k in range(10):
+            fn(k)
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        s.record(env.torch_stream)
+        for k in range(reps):
+            fn(k)
+        e.record(env.torch_stream)
+        torch.cuda.synchronize()
+        return s.elapsed_time(e) / 1e3 / reps
+
+    t_wd = timed(lambda k: env.sample(ring[k % RING]))
+    t_torch = timed(lambda k: torch.multinomial(flat[k % RING], 1))
+    agents = cfg.num_envs * cfg.num_agents
+    env.close()
+    return {"sampler_actions_per_s": agents / t_wd, "torch_multinomial_actions_per_s": agents / t_torch,
+            "sampler_over_torch": t_torch / t_wd, "sampler_us": t_wd * 1e6}
+
+
 def time_oracle(cfg, ring, envs_per_thread, iterations, threads):
     """The oracle as it stands on a bounded slice of the same workload: the first envs, from the
     reset state, the same probabilities.  Returns env-steps/s."""
@@ -188,6 +217,9 @@ def main():
         w2, e2, _, _ = time_gpu(cfg, ring, min(args.steps, 300), 20, args.mode, tag_r2=-1)
         extras["all_live_env_steps_per_s"] = min(args.steps, 300) / w2 * cfg.num_envs
         extras["all_live_hbm_frac"] = bytes_per_iteration / (e2 / min(args.steps, 300)) / 1e9 / HBM_PEAK_GBS
+        # the sampler alone against the framework's operator on the same probabilities
+        # (paper Sec. 5.4 compares its sampler with the PyTorch one)
+        extras.update(time_sampler(cfg, ring))
         other = "separate" if args.mode == "fused" else "fused"
         w3, _, _, _ = time_gpu(cfg, ring, min(args.steps, 300), 20, other)
         extras[f"{other}_env_steps_per_s"] = min(args.steps, 300) / w3 * cfg.num_envs
