@@ -139,6 +139,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="tag_2000x1000")
     ap.add_argument("--mode", choices=("fused", "separate"), default="fused")
+    ap.add_argument("--obs", choices=("partial", "full"), default="partial",
+                    help="observation mode; full = one slot per agent (D = 5 + 4N), HBM-write bound")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -169,6 +171,9 @@ def main():
                           "writes_kib": args.copy_probe_mib * 1024}))
         return
     cfg = CONFIGS[args.workload]
+    if args.obs == "full":
+        import dataclasses
+        cfg = dataclasses.replace(cfg, obs_mode=1)
     ring = device_probs_ring(cfg.seed, RING, cfg.num_envs, cfg.num_agents, "cuda:0")
     torch.cuda.synchronize()
 
@@ -196,7 +201,7 @@ def main():
         "config": {
             "workload": args.workload, "num_envs": cfg.num_envs, "num_agents": cfg.num_agents,
             "num_taggers": cfg.num_taggers, "grid_size": cfg.grid_size, "episode_length": cfg.episode_length,
-            "obs": f"partial K={cfg.obs_k}", "tag_r2": cfg.tag_r2, "seed": cfg.seed, "mode": args.mode,
+            "obs": f"partial K={cfg.obs_k}" if cfg.obs_mode == 0 else f"full D={cfg.obs_dim}", "tag_r2": cfg.tag_r2, "seed": cfg.seed, "mode": args.mode,
             "probs": f"softmax(N(0,1)) float32, ring of {RING} steps resident in HBM",
         },
         "agent_steps_per_s": agent_steps,

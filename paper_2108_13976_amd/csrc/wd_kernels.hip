@@ -538,6 +538,11 @@ __device__ __forceinline__ void write_row(Ptr row, const Params& p, const Tables
   }
 }
 
+// Four floats of one neighbour slot; rows of 5 + 4N floats put slots on 4-byte boundaries only.
+struct __attribute__((packed, aligned(4))) Slot4 {
+  float a, b, c, d;
+};
+
 __device__ __forceinline__ void wave_sync_lds() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
@@ -907,9 +912,40 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
       }
     }
   } else {
-    // any K: the k-th neighbour is the smallest key above the (k-1)-th; rows written in place
     __syncthreads();
-    if (out_act) {
+    if (p.obs_mode == 1) {
+      // Full observations (Sec. 5.1, "partial or full observations"): row i holds the own
+      // features and one slot per agent j in index order, zeros unless both are in play.  The
+      // team walks the N * N slots of its env; consecutive lanes write consecutive 16-byte
+      // slots, so the stream to HBM is contiguous except for the five own features per row.
+      if (out_act) {
+        const int64_t D = p.D;
+        float* env_obs = p.obs + abase * D;
+        const float tf = static_cast<float>(t_out) * p.inv_T;
+        const uint32_t slots = uint32_t(N) * uint32_t(N);
+        for (uint32_t u = uint32_t(lt); u < slots; u += uint32_t(ts)) {
+          const uint32_t i = fastdiv(u, p.div_N);
+          const uint32_t j = u - i * uint32_t(N);
+          const uint32_t me = L.pl[i], other = L.pl[j];
+          const bool both = !((me | other) & kDeadBit);
+          float* row = env_obs + int64_t(i) * D;
+          Slot4 v;
+          v.a = both ? static_cast<float>(pos_x_of(other) - pos_x_of(me)) * p.inv_G : 0.0f;
+          v.b = both ? static_cast<float>(pos_y_of(other) - pos_y_of(me)) * p.inv_G : 0.0f;
+          v.c = (both && int(j) < N_tag) ? 1.0f : 0.0f;
+          v.d = both ? 1.0f : 0.0f;
+          *reinterpret_cast<Slot4*>(row + 5 + 4 * j) = v;
+          if (j == 0) {
+            row[0] = static_cast<float>(pos_x_of(me)) * p.inv_G;
+            row[1] = static_cast<float>(pos_y_of(me)) * p.inv_G;
+            row[2] = int(i) < N_tag ? 1.0f : 0.0f;
+            row[3] = (me & kDeadBit) ? 0.0f : 1.0f;
+            row[4] = tf;
+          }
+        }
+      }
+    } else if (out_act) {
+      // any K: the k-th neighbour is the smallest key above the (k-1)-th; rows written in place
       const int D = p.D;
       const int n_sorted = int(L.starts[p.nb_cap]);
       const float tf = static_cast<float>(t_out) * p.inv_T;
@@ -976,6 +1012,7 @@ hipError_t prepare_env_variant(const Params& p) {
 
 // Which compiled variant serves K: 4 (the benchmark shape), 0 (K <= 8 at run time), -1 (any K).
 int variant_of(const Params& p) {
+  if (p.obs_mode == 1) return -1;
   if (p.K == 4) return 4;
   if (p.K <= kMaxRegisterK) return 0;
   return -1;
@@ -1011,7 +1048,7 @@ hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint
 
 hipError_t prepare_env_kernels(const Params& p) { WD_DISPATCH(prepare_env_variant); }
 
-bool env_kernel_available(const Params& p) { return p.obs_mode == 0 && !(p.big && p.K > kMaxRegisterK); }
+bool env_kernel_available(const Params& p) { return !(p.big && (p.obs_mode == 1 || p.K > kMaxRegisterK)); }
 
 hipError_t launch_sample(const Params& p, const float* probs, uint64_t g, hipStream_t stream) {
   const int64_t total = int64_t(p.E) * p.NG;

@@ -241,6 +241,10 @@ EDGE = {
     "many_agents_one_team": dict(num_envs=2, num_agents=1500, num_taggers=50, grid_size=90, episode_length=8, obs_k=4),
     "large_env_narrow_keys": dict(num_envs=2, num_agents=8192, num_taggers=700, grid_size=100, episode_length=4, obs_k=4),
     "large_env_k_two": dict(num_envs=2, num_agents=6001, num_taggers=3, grid_size=300, episode_length=3, obs_k=2),
+    "full_obs_tiny": dict(num_envs=40, num_agents=5, num_taggers=1, grid_size=6, episode_length=12, obs_mode=1),
+    "full_obs_fifty": dict(num_envs=9, num_agents=50, num_taggers=10, grid_size=20, episode_length=30, obs_mode=1),
+    "full_obs_odd_count": dict(num_envs=5, num_agents=131, num_taggers=7, grid_size=15, episode_length=10, obs_mode=1),
+    "full_obs_thousand": dict(num_envs=2, num_agents=1000, num_taggers=100, grid_size=30, episode_length=5, obs_mode=1),
     "odd_rewards": dict(num_envs=12, num_agents=25, num_taggers=5, grid_size=8, episode_length=20, obs_k=2,
                         tag_reward=0.3, tag_penalty=-2.5),
 }
