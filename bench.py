@@ -183,7 +183,7 @@ def main():
     agent_steps = env_steps * cfg.num_agents
     launch_s = event_s / args.steps  # average duration of one iteration on the launch stream
     achieved_gbs = bytes_per_iteration / launch_s / 1e9
-    traffic = read_traffic(args.workload)
+    traffic = read_traffic(args.workload) if args.obs == "partial" else None
 
     out = {
         "metric": "env_steps_per_s",
