@@ -108,6 +108,36 @@ def time_sampler(cfg, ring, reps=200):
             "sampler_over_torch": t_torch / t_wd, "sampler_us": t_wd * 1e6}
 
 
+def time_rollout(cfg, ring, k=16, launches=12):
+    """wd_rollout: k iterations per launch with every iteration's action, reward, done and
+    observations recorded (paper Sec. 4.5 item 7: roll-out data gathered into a training batch)."""
+    import torch
+    import paper_2108_13976_amd as wd
+
+    if cfg.obs_mode != 0 or cfg.num_agents > 4096:
+        return {}
+    env = wd.TagEnvs(device="cuda:0", **cfg.kwargs())
+    env.reset(wd.WD_RESET_ALL)
+    E, N, D = env.E, env.N, env.D
+    out = {"action": torch.empty((k, E, N), dtype=torch.int32, device=env.device),
+           "reward": torch.empty((k, E, N), dtype=torch.float32, device=env.device),
+           "done": torch.empty((k, E), dtype=torch.int32, device=env.device),
+           "obs": torch.empty((k, E, N, D), dtype=torch.float32, device=env.device)}
+    from paper_2108_13976_amd.binding import wd_rollout_buffers
+    bufs = wd_rollout_buffers(*[out[n].data_ptr() for n in ("action", "reward", "done", "obs")])
+    for _ in range(3):
+        wd.wd_rollout(env.handle, ring.data_ptr(), RING, k, bufs)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(launches):
+        wd.wd_rollout(env.handle, ring.data_ptr(), RING, k, bufs)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    env.close()
+    return {"rollout_k": k, "rollout_env_steps_per_s": launches * k * cfg.num_envs / dt,
+            "rollout_us_per_iteration": dt / (launches * k) * 1e6}
+
+
 def time_oracle(cfg, ring, envs_per_thread, iterations, threads):
     """The oracle as it stands on a bounded slice of the same workload: the first envs, from the
     reset state, the same probabilities.  Returns env-steps/s."""
@@ -225,6 +255,7 @@ def main():
         # the sampler alone against the framework's operator on the same probabilities
         # (paper Sec. 5.4 compares its sampler with the PyTorch one)
         extras.update(time_sampler(cfg, ring))
+        extras.update(time_rollout(cfg, ring))
         other = "separate" if args.mode == "fused" else "fused"
         w3, _, _, _ = time_gpu(cfg, ring, min(args.steps, 300), 20, other)
         extras[f"{other}_env_steps_per_s"] = min(args.steps, 300) / w3 * cfg.num_envs

@@ -137,6 +137,24 @@ int wd_step(wd_handle* h);
  * wd_reset(WD_RESET_DONE), with identical results. */
 int wd_iterate(wd_handle* h, const float* probs);
 
+/* Per-iteration outputs of a multi-step roll-out (the experience a trainer batches,
+ * Sec. 4.5 item 7): DEVICE pointers, caller-owned, 16-byte aligned, each may be NULL.
+ * Slice s (0 <= s < k) holds what iteration s produced. */
+typedef struct wd_rollout_buffers {
+  int32_t* action; /* [k][E][N]    actions sampled in iteration s                          */
+  float* reward;   /* [k][E][N]    rewards of the step of iteration s                      */
+  int32_t* done;   /* [k][E]       done flags after the step, before the reset clears them  */
+  float* obs;      /* [k][E][N][D] observations after iteration s (after the reset of done envs) */
+} wd_rollout_buffers;
+
+/* k whole roll-out iterations in ONE launch (launch latency paid once; Sec. 4.5 items
+ * 3-6 repeated).  probs_ring: device [ring_len][E][N][5]; iteration s samples from entry
+ * (g + s) mod ring_len.  Results equal k calls of wd_iterate with those probabilities:
+ * the in-place buffers end in the state after the last iteration, `out` (may be NULL)
+ * receives every iteration's outputs, g advances by k.  WD_E_UNSUPPORTED for
+ * configurations that use the large-env layout, full observations or K > 8. */
+int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const wd_rollout_buffers* out);
+
 /* The global step counter g used as the RNG step index (checkpoint / resume). */
 int wd_get_step(wd_handle* h, uint64_t* g);
 int wd_set_step(wd_handle* h, uint64_t g);

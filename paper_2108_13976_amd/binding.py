@@ -46,6 +46,10 @@ class wd_buffers(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in BUFFER_NAMES]
 
 
+class wd_rollout_buffers(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("action", "reward", "done", "obs")]
+
+
 class wd_layout(ctypes.Structure):
     _fields_ = [
         ("obs_dim", ctypes.c_int32),
@@ -81,6 +85,7 @@ def load_library(path=LIBRARY):
         lib.wd_sample.argtypes = [H, ctypes.c_void_p]
         lib.wd_step.argtypes = [H]
         lib.wd_iterate.argtypes = [H, ctypes.c_void_p]
+        lib.wd_rollout.argtypes = [H, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.POINTER(wd_rollout_buffers)]
         lib.wd_get_step.argtypes = [H, ctypes.POINTER(ctypes.c_uint64)]
         lib.wd_set_step.argtypes = [H, ctypes.c_uint64]
         lib.wd_destroy.argtypes = [H]
@@ -88,7 +93,7 @@ def load_library(path=LIBRARY):
         lib.wd_strerror.restype = ctypes.c_char_p
         lib.wd_last_error.argtypes = [H]
         lib.wd_last_error.restype = ctypes.c_char_p
-        for name in ("wd_query_layout", "wd_create", "wd_reset", "wd_sample", "wd_step", "wd_iterate",
+        for name in ("wd_query_layout", "wd_create", "wd_reset", "wd_sample", "wd_step", "wd_iterate", "wd_rollout",
                      "wd_get_step", "wd_set_step", "wd_destroy"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
@@ -140,6 +145,11 @@ def wd_step(handle):
 
 def wd_iterate(handle, probs_ptr):
     _call(handle, "wd_iterate", ctypes.c_void_p(probs_ptr))
+
+
+def wd_rollout(handle, probs_ring_ptr, ring_len, k, out=None):
+    _call(handle, "wd_rollout", ctypes.c_void_p(probs_ring_ptr), int(ring_len), int(k),
+          ctypes.byref(out) if out is not None else None)
 
 
 def wd_get_step(handle):
@@ -211,6 +221,22 @@ class TagEnvs:
     def iterate(self, probs):
         self._check_probs(probs)
         wd_iterate(self.handle, probs.data_ptr())
+
+    def rollout(self, probs_ring, k, record=("action", "reward", "done", "obs")):
+        """k iterations in one launch; returns a dict of [k, ...] device tensors for the recorded outputs."""
+        import torch
+
+        ring_len = probs_ring.shape[0]
+        if (probs_ring.dtype != torch.float32 or not probs_ring.is_contiguous() or probs_ring.device != self.device
+                or probs_ring.numel() != ring_len * self.layout.probs_elems):
+            raise ValueError("probs_ring must be a contiguous float32 device tensor of shape [R, E, N, 5]")
+        E, N, D = self.E, self.N, self.D
+        shapes = {"action": ((k, E, N), torch.int32), "reward": ((k, E, N), torch.float32),
+                  "done": ((k, E), torch.int32), "obs": ((k, E, N, D), torch.float32)}
+        out = {n: torch.empty(shapes[n][0], dtype=shapes[n][1], device=self.device) for n in record}
+        bufs = wd_rollout_buffers(*[out[n].data_ptr() if n in out else None for n in ("action", "reward", "done", "obs")])
+        wd_rollout(self.handle, probs_ring.data_ptr(), ring_len, k, bufs)
+        return out
 
     def _check_probs(self, probs):
         import torch

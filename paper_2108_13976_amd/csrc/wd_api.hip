@@ -355,6 +355,34 @@ int wd_iterate(wd_handle* h, const float* probs) {
   return WD_OK;
 }
 
+int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const wd_rollout_buffers* out) {
+  if (!h || !probs_ring) return WD_E_NULL;
+  if (ring_len < 1 || k < 1) return WD_E_CONFIG;
+  if (!probs_aligned(h->params, probs_ring)) return WD_E_ALIGN;
+  if (out) {
+    const void* ptrs[] = {out->action, out->reward, out->done, out->obs};
+    for (const void* ptr : ptrs)
+      if (reinterpret_cast<uintptr_t>(ptr) & 15u) return WD_E_ALIGN;
+  }
+  if (!h->started) return WD_E_STATE;
+  if (!wd::rollout_available(h->params)) return WD_E_UNSUPPORTED;
+  wd::Roll roll;
+  std::memset(&roll, 0, sizeof(roll));
+  roll.steps = k;
+  roll.ring_len = ring_len;
+  roll.ring_pos = int32_t(h->g % uint64_t(ring_len));
+  if (out) {
+    roll.action = out->action;
+    roll.reward = out->reward;
+    roll.done = out->done;
+    roll.obs = out->obs;
+  }
+  const hipError_t err = wd::launch_rollout(h->params, roll, probs_ring, h->g, h->stream);
+  if (err != hipSuccess) return hip_failed(h, err, "rollout kernel");
+  h->g += uint64_t(k);
+  return WD_OK;
+}
+
 int wd_get_step(wd_handle* h, uint64_t* g) {
   if (!h || !g) return WD_E_NULL;
   *g = h->g;

@@ -81,6 +81,18 @@ struct Params {
   float* reward;
   float* obs;
   int32_t *t, *done, *n_live_runners, *tags_step;
+  int32_t* done_log;     // optional [E]: done flags of an iteration before its reset (roll-outs)
+};
+
+// A multi-step roll-out: iteration s reads ring entry (ring_pos + s) mod ring_len and writes
+// slice s of the buffers that are not NULL (action, reward [steps][E][N]; done [steps][E];
+// obs [steps][E][N][D]).
+struct Roll {
+  int32_t steps, ring_len, ring_pos, pad;
+  int32_t* action;
+  float* reward;
+  int32_t* done;
+  float* obs;
 };
 
 enum EnvKernelMode { kModeStep = 0, kModeResetAll = 1, kModeResetDone = 2, kModeIterate = 3 };
@@ -89,6 +101,8 @@ enum EnvKernelMode { kModeStep = 0, kModeResetAll = 1, kModeResetDone = 2, kMode
 hipError_t launch_sample(const Params& p, const float* probs, uint64_t g, hipStream_t stream);
 hipError_t launch_init_start_positions(const Params& p, hipStream_t stream);
 hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream);
+hipError_t launch_rollout(const Params& p, const Roll& roll, const float* ring, uint64_t g, hipStream_t stream);
+bool rollout_available(const Params& p);
 // One-time per-process setup of kernel attributes (dynamic LDS limit) for a plan.
 hipError_t prepare_env_kernels(const Params& p);
 // True if the env-per-team kernels cover this configuration.

@@ -556,13 +556,10 @@ __device__ __forceinline__ void wave_sync_lds() {
 // by repeated selection, rows written directly (slow path).
 // ----------------------------------------------------------------------------------
 template <bool WIDE, int KX, bool CN, bool BIG>
-__global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
-    __attribute__((amdgpu_waves_per_eu((WIDE || BIG || KX == 0) ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
-                                                             const float* __restrict__ probs, uint32_t g_lo,
-                                                             uint32_t g_hi) {
+__device__ __forceinline__ void env_body(const Params& p, const int mode, const float* __restrict__ probs,
+                                         uint32_t g_lo, uint32_t g_hi, unsigned char* smem) {
   using SL = SortedList<WIDE>;
   using Key = typename SL::Key;
-  extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x;
   const int ts = 1 << p.ts_log2;
   const int team = tid >> p.ts_log2;
@@ -734,6 +731,7 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
 
   if (mode != kModeStep) {
     // ---- reset: restore the start state of envs that are done (or of all) ------------------
+    if (p.done_log && valid && lt == 0) p.done_log[e] = done_now ? 1 : 0;  // the flag before the reset clears it
     const bool reset_act = valid && (mode == kModeResetAll || done_now);
     const bool any_reset = (mode == kModeIterate) ? (__syncthreads_or(reset_act ? 1 : 0) != 0) : true;
     if (any_reset) {
@@ -997,6 +995,57 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
 }
 
 template <bool WIDE, int KX, bool CN, bool BIG>
+__global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
+    __attribute__((amdgpu_waves_per_eu((WIDE || BIG || KX == 0) ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
+                                                             const float* __restrict__ probs, uint32_t g_lo,
+                                                             uint32_t g_hi) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  env_body<WIDE, KX, CN, BIG>(p, mode, probs, g_lo, g_hi, smem);
+}
+
+// Several roll-out iterations in one launch.  Envs never interact, so a workgroup can run its
+// envs through `steps` iterations on its own: step s samples from ring entry (ring_pos + s) mod
+// ring_len, writes action / reward / observations of that iteration to the s-th slice of the
+// roll-out buffers (the data a trainer batches, Sec. 4.5 item 7) and the done flags as they
+// were before the reset; the last iteration writes the caller's in-place buffers, from which
+// the last slice is then copied.
+template <bool WIDE, int KX, bool CN>
+__global__ __launch_bounds__(kMaxEnvWorkgroupSize)
+    __attribute__((amdgpu_waves_per_eu((WIDE || KX == 0) ? 4 : 8, 8))) void rollout_kernel(const Params p, const Roll roll,
+                                                                                 const float* __restrict__ ring,
+                                                                                 uint32_t g_lo, uint32_t g_hi) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int64_t EN = int64_t(p.E) * p.N;
+  const uint64_t g0 = (uint64_t(g_hi) << 32) | g_lo;
+  int ring_at = roll.ring_pos;
+  for (int s = 0; s < roll.steps; ++s) {
+    Params q = p;
+    if (s + 1 < roll.steps) {
+      if (roll.action) q.action = roll.action + s * EN;
+      if (roll.reward) q.reward = roll.reward + s * EN;
+      if (roll.obs) q.obs = roll.obs + s * EN * p.D;
+    }
+    q.done_log = roll.done ? roll.done + int64_t(s) * p.E : nullptr;
+    const uint64_t g = g0 + uint64_t(s);
+    env_body<WIDE, KX, CN, false>(q, kModeIterate, ring + int64_t(ring_at) * EN * kNumActions, uint32_t(g),
+                                  uint32_t(g >> 32), smem);
+    ring_at = ring_at + 1 == roll.ring_len ? 0 : ring_at + 1;
+    __syncthreads();  // this step's state and LDS use are complete before the next step starts
+  }
+  const int e0 = blockIdx.x * p.teams_per_wg;
+  const int64_t first = int64_t(e0) * p.N;
+  const int64_t count = int64_t(min(p.teams_per_wg, p.E - e0)) * p.N;
+  const int64_t last = int64_t(roll.steps - 1) * EN;
+  if (roll.action)
+    for (int64_t i = threadIdx.x; i < count; i += blockDim.x) roll.action[last + first + i] = p.action[first + i];
+  if (roll.reward)
+    for (int64_t i = threadIdx.x; i < count; i += blockDim.x) roll.reward[last + first + i] = p.reward[first + i];
+  if (roll.obs)
+    for (int64_t i = threadIdx.x; i < count * p.D; i += blockDim.x)
+      roll.obs[(last + first) * p.D + i] = p.obs[first * p.D + i];
+}
+
+template <bool WIDE, int KX, bool CN, bool BIG>
 hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream) {
   const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
   hipLaunchKernelGGL((env_kernel<WIDE, KX, CN, BIG>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, p,
@@ -1008,6 +1057,17 @@ template <bool WIDE, int KX, bool CN, bool BIG>
 hipError_t prepare_env_variant(const Params& p) {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(&env_kernel<WIDE, KX, CN, BIG>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
+}
+
+template <bool WIDE, int KX, bool CN>
+hipError_t launch_rollout_variant(const Params& p, const Roll& roll, const float* ring, uint64_t g, hipStream_t stream) {
+  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&rollout_kernel<WIDE, KX, CN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
+  if (err != hipSuccess) return err;
+  const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
+  hipLaunchKernelGGL((rollout_kernel<WIDE, KX, CN>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, p,
+                     roll, ring, uint32_t(g), uint32_t(g >> 32));
+  return hipGetLastError();
 }
 
 // Which compiled variant serves K: 4 (the benchmark shape), 0 (K <= 8 at run time), -1 (any K).
@@ -1047,6 +1107,19 @@ hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint
 }
 
 hipError_t prepare_env_kernels(const Params& p) { WD_DISPATCH(prepare_env_variant); }
+
+bool rollout_available(const Params& p) { return !p.big && p.obs_mode == 0 && p.K <= kMaxRegisterK; }
+
+hipError_t launch_rollout(const Params& p, const Roll& roll, const float* ring, uint64_t g, hipStream_t stream) {
+  const int kx = variant_of(p);
+  if (!p.wide) {
+    if (kx == 4 && p.compact_nbr) return launch_rollout_variant<false, 4, true>(p, roll, ring, g, stream);
+    if (kx == 4) return launch_rollout_variant<false, 4, false>(p, roll, ring, g, stream);
+    return launch_rollout_variant<false, 0, false>(p, roll, ring, g, stream);
+  }
+  if (kx == 4) return launch_rollout_variant<true, 4, false>(p, roll, ring, g, stream);
+  return launch_rollout_variant<true, 0, false>(p, roll, ring, g, stream);
+}
 
 bool env_kernel_available(const Params& p) { return !(p.big && (p.obs_mode == 1 || p.K > kMaxRegisterK)); }
 

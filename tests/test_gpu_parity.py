@@ -182,6 +182,48 @@ def test_headline_workload_full_size_sampled_envs_and_invariants():
     gpu.close()
 
 
+@pytest.mark.parametrize("name,k,rounds", [("tag_10x5", 37, 8), ("tag_100x50", 16, 5), ("tag_20000x100", 6, 2)])
+def test_multi_step_rollout_equals_single_iterations(name, k, rounds):
+    """wd_rollout (k iterations in one launch, per-iteration outputs) against k calls of the
+    separate entry points, and both against the oracle at the end."""
+    import torch
+    import paper_2108_13976_amd as wd
+    from oracle import tag_oracle
+
+    cfg = CONFIGS[name]
+    kw = cfg.kwargs()
+    if cfg.num_envs > 500:
+        kw.update(num_envs=203, env_offset=900)
+    E, N = kw["num_envs"], cfg.num_agents
+    lo = kw.get("env_offset", 0)
+    ring_len = 5
+    host_ring = np.stack([probs_for_step(cfg.seed, r, cfg.num_envs, N, lo, lo + E) for r in range(ring_len)])
+    a, b = make_gpu(kw), make_gpu(kw)
+    orc = make_oracle(kw)
+    ring = upload(host_ring, a.device)
+    a.reset(wd.WD_RESET_ALL), b.reset(wd.WD_RESET_ALL), orc.reset()
+    g = 0
+    for _ in range(rounds):
+        rec = a.rollout(ring, k)
+        for s in range(k):
+            pr = ring[(g + s) % ring_len]
+            b.sample(pr), b.step()
+            sb = b.to_host()
+            assert np.array_equal(rec["action"][s].cpu().numpy(), sb["action"])
+            assert np.array_equal(rec["done"][s].cpu().numpy(), sb["done"])
+            assert rec["reward"][s].cpu().numpy().tobytes() == sb["reward"].tobytes()
+            b.reset(wd.WD_RESET_DONE)
+            assert rec["obs"][s].cpu().numpy().tobytes() == b.to_host()["obs"].tobytes()
+            orc.iterate(host_ring[(g + s) % ring_len], g + s)
+        g += k
+        assert a.global_step == g
+        sa, sb = a.to_host(), b.to_host()
+        for n in sa:
+            assert sa[n].tobytes() == sb[n].tobytes(), n
+        assert_equal_state(sa, orc, f"after {g} iterations")
+    a.close(), b.close()
+
+
 def test_two_runs_are_byte_identical():
     import paper_2108_13976_amd as wd
 
