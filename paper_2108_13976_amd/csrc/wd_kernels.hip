@@ -1011,7 +1011,7 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
 // the last slice is then copied.
 template <bool WIDE, int KX, bool CN>
 __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
-    __attribute__((amdgpu_waves_per_eu((WIDE || KX == 0) ? 4 : 8, 8))) void rollout_kernel(const Params p, const Roll roll,
+    __attribute__((amdgpu_waves_per_eu(2, 8))) void rollout_kernel(const Params p, const Roll roll,
                                                                                  const float* __restrict__ ring,
                                                                                  uint32_t g_lo, uint32_t g_hi) {
   extern __shared__ __align__(16) unsigned char smem[];
