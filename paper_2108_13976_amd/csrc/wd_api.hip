@@ -109,8 +109,11 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   uint32_t mul_max = 65536u;
   if (G > 1) mul_max = uint32_t(std::min<uint64_t>(65536u, ((uint64_t(side) << 16) - 1) / uint64_t(G - 1)));
   p->bucket_mul_max = mul_max;
-  const double lambda = 4.0;  // target live agents per bucket
-  p->bucket_scale = float(65536.0 / (double(G) * std::sqrt(lambda)));
+  p->bucket_scale = float(65536.0 / double(G));
+  // target live agents per bucket: about 5 in an env of a hundred agents, 1.5 at a thousand
+  p->lambda_c = 47.0f;
+  p->lambda_min = 1.5f;
+  p->lambda_max = 5.0f;
   p->div_N = wd::make_fastdiv(uint32_t(N));
   p->div_NG = wd::make_fastdiv(uint32_t(p->NG));
 
@@ -161,6 +164,10 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
     p->off_credits = take(4ll * c.num_taggers);
   }
   p->off_counts = take(4ll * nb_cap);
+  // slots of the second search pass: over slot[] (not needed any more by then), which the
+  // neighbour lists therefore must not overlay; a large env has no slot[] in LDS
+  p->off_retry = (big && register_path) ? take(2 * NPAD) : 0;
+  const int64_t retry_bytes = (big || !register_path) ? 0 : align16(2 * NPAD);
   const int64_t y_tables = off;
   // neighbour lists: K 16-bit ids per agent, or 40 bits per agent when K = 4 and ids fit 10 bits
   p->compact_nbr = (!big && narrow && p->K == 4 && N < 1024) ? 1 : 0;
@@ -178,10 +185,10 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   auto plan_with = [&](int64_t stage, int64_t* x_span, int64_t* y_stride) {
     if (tpw == 1) {
       *x_span = x_area;
-      *y_stride = align16(std::max<int64_t>(std::max<int64_t>(y_tables, nbr_bytes), stage + nbr_bytes - x_area));
+      *y_stride = align16(std::max<int64_t>(std::max<int64_t>(y_tables, retry_bytes + nbr_bytes), stage + nbr_bytes - x_area));
     } else {
       *x_span = std::max<int64_t>(x_area, stage);
-      *y_stride = align16(std::max<int64_t>(y_tables, nbr_bytes));
+      *y_stride = align16(std::max<int64_t>(y_tables, retry_bytes + nbr_bytes));
     }
     return p->keep_stride * int64_t(tpw) + *x_span + *y_stride * tpw;
   };

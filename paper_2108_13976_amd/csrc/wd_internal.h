@@ -52,7 +52,8 @@ struct Params {
   int32_t vec4;          // N % 4 == 0: a group's global slices are 16-byte aligned
   int32_t nb_cap;        // bucket slots per team (power of two, >= team size)
   int32_t scan_chunk;    // nb_cap / team size
-  float bucket_scale;    // 65536 / (G * sqrt(lambda)): bucket multiplier = scale * sqrt(n_live)
+  float bucket_scale;    // 65536 / G: bucket multiplier = scale * sqrt(n_live / lambda)
+  float lambda_c, lambda_min, lambda_max;  // live agents per bucket aimed at: lambda_c / sqrt(n_live), clamped
   uint32_t bucket_mul_max;  // largest multiplier whose bucket table fits nb_cap
   // (distance, index) keys and bucket entries: 32-bit when wide == 0
   int32_t wide, idx_bits, xy_bits;
@@ -64,7 +65,7 @@ struct Params {
   // once the rewards are out.
   int32_t keep_stride, off_pl, off_misc, off_edges;
   int32_t x_base, x_stride, off_sorted, off_sorted_id, off_starts;
-  int32_t y_base, y_stride, off_slot, off_best, off_credits, off_counts, off_nbr;
+  int32_t y_base, y_stride, off_slot, off_best, off_credits, off_counts, off_nbr, off_retry;
   int32_t compact_nbr;   // K = 4 neighbour ids of an agent packed into 40 bits (N < 1024)
   int32_t lds_bytes;
   // Large envs (big != 0): one 1024-thread workgroup per env; slots, tag keys, credits and

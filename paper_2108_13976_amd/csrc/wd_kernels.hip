@@ -264,10 +264,14 @@ struct Buckets {
 };
 
 // Bucket width for n_live agents on the grid: about sqrt(lambda / density) cells, so that a
-// bucket holds about lambda live agents, limited by the size of the bucket table.  Any choice
-// gives the same results; it only trades search rings against candidates per ring.
+// bucket holds about lambda live agents, limited by the size of the bucket table.  lambda
+// falls with the number of agents (lambda_c / sqrt(n), clamped): a crowded env is bound by the
+// candidates each search visits, a sparse one by the per-ring overhead.  Any choice gives
+// the same results; it only trades search rings against candidates per ring.
 __device__ __forceinline__ Buckets choose_buckets(const Params& p, int n_live) {
-  const float want = p.bucket_scale * sqrtf(static_cast<float>(max(n_live, 1)));
+  const float n = static_cast<float>(max(n_live, 1));
+  const float lambda = fminf(fmaxf(p.lambda_c * rsqrtf(n), p.lambda_min), p.lambda_max);
+  const float want = p.bucket_scale * sqrtf(n / lambda);
   uint32_t mul = static_cast<uint32_t>(fminf(want, 65536.0f) + 0.5f);
   mul = min(max(mul, 2u), p.bucket_mul_max);
   Buckets b;
@@ -300,10 +304,11 @@ struct TeamLds {
   uint16_t* nbr;     // [NPAD][K] neighbour indices; overlays the tail of slot/best/credits/counts
   uint32_t* nbr_lo;  // compact form for K = 4, N < 1024: ids 0..2 and two bits of id 3 per agent,
   uint8_t* nbr_hi;   // and the other eight bits of id 3 (same memory as nbr)
-  int32_t* misc;     // [0] tags this step, [1] t after the call, [2] rows to be written, [4..19] scan scratch
+  int32_t* misc;     // [0] tags this step, [1] t after the call, [2] rows to be written, [3] length of retry[], [4..19] scan scratch
   uint16_t* edges;   // [nbx + 1] first cell of each bucket coordinate; edges[nbx] = G
   SortedList<WIDE> sorted;  // [NPAD + pad] the live agents, grouped by bucket
   uint16_t* slot;    // [NPAD] where agent i sits in `sorted`
+  uint16_t* retry;   // [NPAD] slots whose neighbour search needs wider rings (reuses slot[] when that is in LDS)
   Key* best;         // [NPAD] per runner: smallest (distance, tagger) key in range
   int32_t* credits;  // [N_tag]
   uint32_t* counts;  // [nb_cap] bucket counts, then scatter cursors
@@ -324,6 +329,7 @@ struct TeamLds {
     }
     starts = reinterpret_cast<uint16_t*>(xr + p.off_starts);
     counts = reinterpret_cast<uint32_t*>(yr + p.off_counts);
+    retry = reinterpret_cast<uint16_t*>(yr + p.off_retry);
     if constexpr (BIG) {
       nbr = p.g_nbr + env * p.g_stride_nbr;
       nbr_lo = nullptr;
@@ -439,8 +445,8 @@ __device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, ui
   }
 }
 
-template <bool WIDE, int KT>
-__device__ __forceinline__ void nearest_keys(typename SortedList<WIDE>::Key (&keys)[KT], int K, int x, int y,
+template <bool WIDE, int KT, bool FIRST>
+__device__ __forceinline__ bool nearest_keys(typename SortedList<WIDE>::Key (&keys)[KT], int K, int x, int y,
                                              uint32_t self_slot, const Buckets bk, int ib,
                                              const SortedList<WIDE>& sorted, const uint16_t* starts,
                                              const uint16_t* edges) {
@@ -487,11 +493,13 @@ __device__ __forceinline__ void nearest_keys(typename SortedList<WIDE>::Key (&ke
     if (y1 < last) reach = min(reach, int(edges[y1 + 1]) - y);
     if (reach == 65535) break;  // the block covers the grid
     if (kth_d2 < uint32_t(reach * reach)) break;
+    if constexpr (FIRST) return false;  // the first ring did not settle it
     px0 = x0;
     px1 = x1;
     py0 = y0;
     py1 = y1;
   }
+  return true;
 }
 
 constexpr uint32_t kCompactNone = 1023u;  // "no neighbour" in the compact 10-bit form
@@ -586,6 +594,7 @@ __device__ __forceinline__ void env_body(const Params& p, const int mode, const 
   int t_out = t_in;
   bool done_now = done_in != 0;
   Buckets bk = choose_buckets(p, nlr_in + N_tag);
+  if (lt == 0) L.misc[3] = 0;  // every mode passes a barrier before the neighbour search appends
 
   if (stepping) {
     if (step_act) {
@@ -787,29 +796,48 @@ __device__ __forceinline__ void env_body(const Params& p, const int mode, const 
   }
   if constexpr (KX >= 0) {
     constexpr int KT = KX > 0 ? KX : kMaxRegisterK;
-    // K nearest, in bucket order (neighbouring lanes search neighbouring cells)
-    if (out_act && K > 0) {
+    // K nearest, in bucket order (neighbouring lanes search neighbouring cells).  Two passes:
+    // every live agent tries the 3x3 buckets around it; the few that this does not settle
+    // (sparse spots, grid borders) queue up and are searched with widening rings afterwards,
+    // packed into full waves, so that a wave of the first pass never waits for one such lane.
+    const auto put_neighbours = [&](uint32_t me, const Key(&keys)[KT]) {
+      if constexpr (CN) {
+        uint32_t id[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) id[kk] = key_is_none(keys[kk]) ? kCompactNone : uint32_t(keys[kk] & idx_mask);
+        L.nbr_lo[me] = id[0] | (id[1] << 10) | (id[2] << 20) | (id[3] << 30);
+        L.nbr_hi[me] = uint8_t(id[3] >> 2);
+      } else {
+#pragma unroll
+        for (int kk = 0; kk < KT; ++kk)
+          if (kk < K)
+            L.nbr[me * K + kk] = key_is_none(keys[kk]) ? uint16_t(kNoNeighbour) : uint16_t(keys[kk] & idx_mask);
+      }
+    };
+    const bool search = out_act && K > 0;
+    if (search) {
       const int n_sorted = int(L.starts[p.nb_cap]);
       for (int q = lt; q < n_sorted; q += ts) {
         const Ent ent = L.sorted.get(q);
         if (!L.sorted.dead(ent)) {
           Key keys[KT];
-          nearest_keys<WIDE, KT>(keys, K, SL::x(ent), SL::y(ent), uint32_t(q), bk, p.idx_bits, L.sorted, L.starts,
-                                 L.edges);
-          const uint32_t me = ent.id;
-          if constexpr (CN) {
-            uint32_t id[4];
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) id[kk] = key_is_none(keys[kk]) ? kCompactNone : uint32_t(keys[kk] & idx_mask);
-            L.nbr_lo[me] = id[0] | (id[1] << 10) | (id[2] << 20) | (id[3] << 30);
-            L.nbr_hi[me] = uint8_t(id[3] >> 2);
-          } else {
-#pragma unroll
-            for (int kk = 0; kk < KT; ++kk)
-              if (kk < K)
-                L.nbr[me * K + kk] = key_is_none(keys[kk]) ? uint16_t(kNoNeighbour) : uint16_t(keys[kk] & idx_mask);
-          }
+          if (nearest_keys<WIDE, KT, true>(keys, K, SL::x(ent), SL::y(ent), uint32_t(q), bk, p.idx_bits, L.sorted,
+                                           L.starts, L.edges))
+            put_neighbours(ent.id, keys);
+          else
+            L.retry[atomicAdd(&L.misc[3], 1)] = uint16_t(q);
         }
+      }
+    }
+    __syncthreads();
+    if (search) {
+      const int n_retry = L.misc[3];
+      for (int j = lt; j < n_retry; j += ts) {
+        const uint32_t q = L.retry[j];
+        const Ent ent = L.sorted.get(q);
+        Key keys[KT];
+        nearest_keys<WIDE, KT, false>(keys, K, SL::x(ent), SL::y(ent), q, bk, p.idx_bits, L.sorted, L.starts, L.edges);
+        put_neighbours(ent.id, keys);
       }
     }
     const bool all_out = __syncthreads_and((out_act || !valid) ? 1 : 0) != 0;  // also the barrier before the rows
