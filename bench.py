@@ -108,9 +108,10 @@ def time_sampler(cfg, ring, reps=200):
             "sampler_over_torch": t_torch / t_wd, "sampler_us": t_wd * 1e6}
 
 
-def time_rollout(cfg, ring, k=16, launches=12):
+def time_rollout(cfg, ring, k=25, launches=40, warm=2):
     """wd_rollout: k iterations per launch with every iteration's action, reward, done and
-    observations recorded (paper Sec. 4.5 item 7: roll-out data gathered into a training batch)."""
+    observations recorded (paper Sec. 4.5 item 7: roll-out data gathered into a training batch).
+    The defaults cover the same iterations as the main timing: 50 warm-up, then 1000."""
     import torch
     import paper_2108_13976_amd as wd
 
@@ -125,17 +126,22 @@ def time_rollout(cfg, ring, k=16, launches=12):
            "obs": torch.empty((k, E, N, D), dtype=torch.float32, device=env.device)}
     from paper_2108_13976_amd.binding import wd_rollout_buffers
     bufs = wd_rollout_buffers(*[out[n].data_ptr() for n in ("action", "reward", "done", "obs")])
-    for _ in range(3):
-        wd.wd_rollout(env.handle, ring.data_ptr(), RING, k, bufs)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(launches):
-        wd.wd_rollout(env.handle, ring.data_ptr(), RING, k, bufs)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    res = {"rollout_k": k}
+    # with every iteration's outputs recorded, then state only (outputs in place, as wd_iterate)
+    for label, b in (("rollout", bufs), ("rollout_in_place", None)):
+        env.reset(wd.WD_RESET_ALL)
+        for _ in range(warm):
+            wd.wd_rollout(env.handle, ring.data_ptr(), RING, k, b)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(launches):
+            wd.wd_rollout(env.handle, ring.data_ptr(), RING, k, b)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        res[label + "_env_steps_per_s"] = launches * k * cfg.num_envs / dt
+        res[label + "_us_per_iteration"] = dt / (launches * k) * 1e6
     env.close()
-    return {"rollout_k": k, "rollout_env_steps_per_s": launches * k * cfg.num_envs / dt,
-            "rollout_us_per_iteration": dt / (launches * k) * 1e6}
+    return res
 
 
 def time_oracle(cfg, ring, envs_per_thread, iterations, threads):

@@ -563,12 +563,20 @@ __device__ __forceinline__ void wave_sync_lds() {
 // neighbour list in registers and send rows through the LDS transpose.  KX < 0: any K,
 // by repeated selection, rows written directly (slow path).
 // ----------------------------------------------------------------------------------
+// Where one iteration's outputs go: the in-place buffers, or a slice of a roll-out's arrays.
+struct StepOut {
+  int32_t* action;   // written by the sampler of an iterate-mode call (the step reads p.action otherwise)
+  float* reward;
+  float* obs;
+  int32_t* done_log; // optional: done flags before the reset clears them
+};
+
 template <bool WIDE, int KX, bool CN, bool BIG>
-__device__ __forceinline__ void env_body(const Params& p, const int mode, const float* __restrict__ probs,
-                                         uint32_t g_lo, uint32_t g_hi, unsigned char* smem) {
+__device__ __forceinline__ void env_body(const Params& p, const StepOut out, const int mode,
+                                         const float* __restrict__ probs, uint32_t g_lo, uint32_t g_hi,
+                                         unsigned char* smem, const int tid) {
   using SL = SortedList<WIDE>;
   using Key = typename SL::Key;
-  const int tid = threadIdx.x;
   const int ts = 1 << p.ts_log2;
   const int team = tid >> p.ts_log2;
   const int lt = tid & (ts - 1);
@@ -614,7 +622,7 @@ __device__ __forceinline__ void env_body(const Params& p, const int mode, const 
         if (mode == kModeIterate) {
           const Block4 r = random_block(p, uint32_t(e), uint32_t(grp), g_lo, g_hi, kStreamAction);
           sample_group(probs, a0, n, vec, r, act);
-          store4(p.action, a0, n, vec, act);
+          store4(out.action, a0, n, vec, act);
         } else if (step_act) {
           load4(p.action, a0, n, vec, act);
         }
@@ -720,7 +728,7 @@ __device__ __forceinline__ void env_body(const Params& p, const int mode, const 
             else if (i < N && L.best[i] != key_none<Key>())
               rew[j] = p.tag_penalty;
           }
-          store4(p.reward, abase + i0, min(4, N - i0), vec, rew);
+          store4(out.reward, abase + i0, min(4, N - i0), vec, rew);
         }
       }
       const int tags = L.misc[0];
@@ -740,7 +748,7 @@ __device__ __forceinline__ void env_body(const Params& p, const int mode, const 
 
   if (mode != kModeStep) {
     // ---- reset: restore the start state of envs that are done (or of all) ------------------
-    if (p.done_log && valid && lt == 0) p.done_log[e] = done_now ? 1 : 0;  // the flag before the reset clears it
+    if (out.done_log && valid && lt == 0) out.done_log[e] = done_now ? 1 : 0;  // the flag before the reset clears it
     const bool reset_act = valid && (mode == kModeResetAll || done_now);
     const bool any_reset = (mode == kModeIterate) ? (__syncthreads_or(reset_act ? 1 : 0) != 0) : true;
     if (any_reset) {
@@ -848,7 +856,7 @@ __device__ __forceinline__ void env_body(const Params& p, const int mode, const 
     const int wave = tid >> 6, lane = tid & (kWaveSize - 1);
     const int D = KX > 0 ? 5 + 4 * KX : p.D;
     const int rows_total = min(p.teams_per_wg, p.E - e0) * N;
-    float* const obs_wg = p.obs + int64_t(e0) * N * D;
+    float* const obs_wg = out.obs + int64_t(e0) * N * D;
     if (all_out) {
       const int srl = p.stage_rows_log2, stage_rows = 1 << srl, flushes = kWaveSize >> srl;
       float* stage = reinterpret_cast<float*>(smem + p.x_base) + wave * stage_rows * D;
@@ -946,7 +954,7 @@ __device__ __forceinline__ void env_body(const Params& p, const int mode, const 
       // slots, so the stream to HBM is contiguous except for the five own features per row.
       if (out_act) {
         const int64_t D = p.D;
-        float* env_obs = p.obs + abase * D;
+        float* env_obs = out.obs + abase * D;
         const float tf = static_cast<float>(t_out) * p.inv_T;
         const uint32_t slots = uint32_t(N) * uint32_t(N);
         for (uint32_t u = uint32_t(lt); u < slots; u += uint32_t(ts)) {
@@ -976,7 +984,7 @@ __device__ __forceinline__ void env_body(const Params& p, const int mode, const 
       const int n_sorted = int(L.starts[p.nb_cap]);
       const float tf = static_cast<float>(t_out) * p.inv_T;
       for (int i = lt; i < N; i += ts) {
-        float* row = p.obs + (abase + i) * D;
+        float* row = out.obs + (abase + i) * D;
         const uint32_t me = L.pl[i];
         const int x = pos_x_of(me), y = pos_y_of(me);
         const bool lv = !(me & kDeadBit);
@@ -1028,7 +1036,18 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
                                                              const float* __restrict__ probs, uint32_t g_lo,
                                                              uint32_t g_hi) {
   extern __shared__ __align__(16) unsigned char smem[];
-  env_body<WIDE, KX, CN, BIG>(p, mode, probs, g_lo, g_hi, smem);
+  env_body<WIDE, KX, CN, BIG>(p, StepOut{p.action, p.reward, p.obs, p.done_log}, mode, probs, g_lo, g_hi, smem, int(threadIdx.x));
+}
+
+// Workgroup-wide copy of `count` 4-byte words: 16-byte pieces when both ends are aligned.
+template <typename T>
+__device__ __forceinline__ void copy_words(T* __restrict__ dst, const T* __restrict__ src, int64_t count) {
+  static_assert(sizeof(T) == 4, "4-byte elements");
+  const bool aligned = ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15) == 0;
+  const int64_t quads = aligned ? count >> 2 : 0;
+  for (int64_t i = threadIdx.x; i < quads; i += blockDim.x)
+    reinterpret_cast<uint4*>(dst)[i] = reinterpret_cast<const uint4*>(src)[i];
+  for (int64_t i = 4 * quads + threadIdx.x; i < count; i += blockDim.x) dst[i] = src[i];
 }
 
 // Several roll-out iterations in one launch.  Envs never interact, so a workgroup can run its
@@ -1037,40 +1056,55 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
 // roll-out buffers (the data a trainer batches, Sec. 4.5 item 7) and the done flags as they
 // were before the reset; the last iteration writes the caller's in-place buffers, from which
 // the last slice is then copied.
+struct RollArgs {  // the one kernel argument of rollout_kernel
+  Params p;
+  Roll roll;
+  const float* ring;
+  uint64_t g0;
+};
+
 template <bool WIDE, int KX, bool CN>
 __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
-    __attribute__((amdgpu_waves_per_eu(2, 8))) void rollout_kernel(const Params p, const Roll roll,
-                                                                                 const float* __restrict__ ring,
-                                                                                 uint32_t g_lo, uint32_t g_hi) {
+    __attribute__((amdgpu_waves_per_eu((WIDE || KX == 0) ? 4 : 8, 8))) void rollout_kernel(const RollArgs args) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const int64_t EN = int64_t(p.E) * p.N;
-  const uint64_t g0 = (uint64_t(g_hi) << 32) | g_lo;
-  int ring_at = roll.ring_pos;
-  for (int s = 0; s < roll.steps; ++s) {
-    Params q = p;
-    if (s + 1 < roll.steps) {
-      if (roll.action) q.action = roll.action + s * EN;
-      if (roll.reward) q.reward = roll.reward + s * EN;
-      if (roll.obs) q.obs = roll.obs + s * EN * p.D;
+  // The loop reads its parameters from the kernel-argument segment (args is the only argument,
+  // at offset 0) through a pointer that is opaque to the optimiser in every iteration: loads of
+  // the many fields then stay next to their uses, as in the one-step kernel, instead of being
+  // hoisted out of the loop into more scalar registers than there are.
+  typedef const __attribute__((address_space(4))) RollArgs* KernargPtr;
+  KernargPtr ak = (KernargPtr)__builtin_amdgcn_kernarg_segment_ptr();
+  const int steps = args.roll.steps;
+  int ring_at = args.roll.ring_pos;
+  for (int s = 0; s < steps; ++s) {
+    asm volatile("" : "+s"(ak));
+    int tid = threadIdx.x;  // likewise: what a thread derives from its id is recomputed per step, not kept
+    asm volatile("" : "+v"(tid));
+    const RollArgs& a = *(const RollArgs*)ak;
+    const Params& p = a.p;
+    const Roll& roll = a.roll;
+    const int64_t EN = int64_t(p.E) * p.N;
+    StepOut out = {p.action, p.reward, p.obs, roll.done ? roll.done + int64_t(s) * p.E : nullptr};
+    if (s + 1 < steps) {
+      if (roll.action) out.action = roll.action + s * EN;
+      if (roll.reward) out.reward = roll.reward + s * EN;
+      if (roll.obs) out.obs = roll.obs + s * EN * p.D;
     }
-    q.done_log = roll.done ? roll.done + int64_t(s) * p.E : nullptr;
-    const uint64_t g = g0 + uint64_t(s);
-    env_body<WIDE, KX, CN, false>(q, kModeIterate, ring + int64_t(ring_at) * EN * kNumActions, uint32_t(g),
-                                  uint32_t(g >> 32), smem);
+    const uint64_t g = a.g0 + uint64_t(s);
+    env_body<WIDE, KX, CN, false>(p, out, kModeIterate, a.ring + int64_t(ring_at) * EN * kNumActions, uint32_t(g),
+                                  uint32_t(g >> 32), smem, tid);
     ring_at = ring_at + 1 == roll.ring_len ? 0 : ring_at + 1;
     __syncthreads();  // this step's state and LDS use are complete before the next step starts
   }
+  const Params& p = args.p;
+  const Roll& roll = args.roll;
+  const int64_t EN = int64_t(p.E) * p.N;
   const int e0 = blockIdx.x * p.teams_per_wg;
   const int64_t first = int64_t(e0) * p.N;
   const int64_t count = int64_t(min(p.teams_per_wg, p.E - e0)) * p.N;
-  const int64_t last = int64_t(roll.steps - 1) * EN;
-  if (roll.action)
-    for (int64_t i = threadIdx.x; i < count; i += blockDim.x) roll.action[last + first + i] = p.action[first + i];
-  if (roll.reward)
-    for (int64_t i = threadIdx.x; i < count; i += blockDim.x) roll.reward[last + first + i] = p.reward[first + i];
-  if (roll.obs)
-    for (int64_t i = threadIdx.x; i < count * p.D; i += blockDim.x)
-      roll.obs[(last + first) * p.D + i] = p.obs[first * p.D + i];
+  const int64_t last = int64_t(steps - 1) * EN;
+  if (roll.action) copy_words(roll.action + last + first, p.action + first, count);
+  if (roll.reward) copy_words(roll.reward + last + first, p.reward + first, count);
+  if (roll.obs) copy_words(roll.obs + (last + first) * p.D, p.obs + first * p.D, count * p.D);
 }
 
 template <bool WIDE, int KX, bool CN, bool BIG>
@@ -1093,8 +1127,12 @@ hipError_t launch_rollout_variant(const Params& p, const Roll& roll, const float
                                        hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
   if (err != hipSuccess) return err;
   const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
-  hipLaunchKernelGGL((rollout_kernel<WIDE, KX, CN>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, p,
-                     roll, ring, uint32_t(g), uint32_t(g >> 32));
+  RollArgs args;
+  args.p = p;
+  args.roll = roll;
+  args.ring = ring;
+  args.g0 = g;
+  hipLaunchKernelGGL((rollout_kernel<WIDE, KX, CN>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, args);
   return hipGetLastError();
 }
 
