@@ -546,6 +546,21 @@ __device__ __forceinline__ void write_row(Ptr row, const Params& p, const Tables
   }
 }
 
+// Slot j of agent i's full observation row: zeros unless both are in play.
+struct FullSlot {
+  float a, b, c, d;
+};
+
+__device__ __forceinline__ FullSlot full_slot(uint32_t me, uint32_t other, bool other_is_tagger, float inv_G) {
+  const bool both = !((me | other) & kDeadBit);
+  FullSlot s;
+  s.a = both ? static_cast<float>(pos_x_of(other) - pos_x_of(me)) * inv_G : 0.0f;
+  s.b = both ? static_cast<float>(pos_y_of(other) - pos_y_of(me)) * inv_G : 0.0f;
+  s.c = (both && other_is_tagger) ? 1.0f : 0.0f;
+  s.d = both ? 1.0f : 0.0f;
+  return s;
+}
+
 // Four floats of one neighbour slot; rows of 5 + 4N floats put slots on 4-byte boundaries only.
 struct __attribute__((packed, aligned(4))) Slot4 {
   float a, b, c, d;
@@ -956,25 +971,82 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
         const int64_t D = p.D;
         float* env_obs = out.obs + abase * D;
         const float tf = static_cast<float>(t_out) * p.inv_T;
-        const uint32_t slots = uint32_t(N) * uint32_t(N);
-        for (uint32_t u = uint32_t(lt); u < slots; u += uint32_t(ts)) {
-          const uint32_t i = fastdiv(u, p.div_N);
-          const uint32_t j = u - i * uint32_t(N);
-          const uint32_t me = L.pl[i], other = L.pl[j];
-          const bool both = !((me | other) & kDeadBit);
-          float* row = env_obs + int64_t(i) * D;
-          Slot4 v;
-          v.a = both ? static_cast<float>(pos_x_of(other) - pos_x_of(me)) * p.inv_G : 0.0f;
-          v.b = both ? static_cast<float>(pos_y_of(other) - pos_y_of(me)) * p.inv_G : 0.0f;
-          v.c = (both && int(j) < N_tag) ? 1.0f : 0.0f;
-          v.d = both ? 1.0f : 0.0f;
-          *reinterpret_cast<Slot4*>(row + 5 + 4 * j) = v;
-          if (j == 0) {
-            row[0] = static_cast<float>(pos_x_of(me)) * p.inv_G;
-            row[1] = static_cast<float>(pos_y_of(me)) * p.inv_G;
-            row[2] = int(i) < N_tag ? 1.0f : 0.0f;
-            row[3] = (me & kDeadBit) ? 0.0f : 1.0f;
-            row[4] = tf;
+        if (vec && ts >= kWaveSize) {
+          // N % 4 == 0: the env's block starts on a 16-byte boundary, and so does every fourth
+          // float of it.  A wave takes whole rows and writes them as ALIGNED 16-byte pieces; a
+          // row starts 0..3 floats past such a boundary, so a piece holds the tail of one slot
+          // and the head of the next, at an offset that is the same for the whole row.
+          const int wv = lt >> 6, lane = lt & (kWaveSize - 1), n_waves = ts >> 6;
+          const uint32_t Du = uint32_t(D);
+          float4* const env_q = reinterpret_cast<float4*>(env_obs);
+          for (int i = wv; i < N; i += n_waves) {
+            const uint32_t row_f = uint32_t(i) * Du;                       // first float of row i in the block
+            const uint32_t g_lo = (row_f + 3u) >> 2, g_hi = (row_f + Du + 3u) >> 2;  // pieces that start in row i
+            const uint32_t shift = (4u * g_lo - row_f - 5u) & 3u;          // slot component a piece starts with
+            const uint32_t me = L.pl[i];
+            for (uint32_t g = g_lo + uint32_t(lane); g < g_hi; g += kWaveSize) {
+              const int c0 = int(4u * g - row_f);  // column of the piece's first float
+              float4 v;
+              if (c0 >= 5 && c0 + 3 < int(Du)) {
+                const int ja = (c0 - 5) >> 2, jb = min(ja + 1, N - 1);
+                const FullSlot A = full_slot(me, L.pl[ja], ja < N_tag, p.inv_G);
+                const FullSlot B = full_slot(me, L.pl[jb], jb < N_tag, p.inv_G);
+                switch (shift) {  // uniform over the wave
+                  case 0: v = make_float4(A.a, A.b, A.c, A.d); break;
+                  case 1: v = make_float4(A.b, A.c, A.d, B.a); break;
+                  case 2: v = make_float4(A.c, A.d, B.a, B.b); break;
+                  default: v = make_float4(A.d, B.a, B.b, B.c); break;
+                }
+              } else {
+                // the piece holds own features, or runs into the next row (never past the
+                // block: its length is a multiple of four floats)
+                float f[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                  int col = c0 + k, r = i;
+                  if (col >= int(Du)) {
+                    col -= int(Du);
+                    r = i + 1;
+                  }
+                  const uint32_t mr = L.pl[r];
+                  if (col < 5) {
+                    f[k] = col == 0   ? static_cast<float>(pos_x_of(mr)) * p.inv_G
+                           : col == 1 ? static_cast<float>(pos_y_of(mr)) * p.inv_G
+                           : col == 2 ? (r < N_tag ? 1.0f : 0.0f)
+                           : col == 3 ? ((mr & kDeadBit) ? 0.0f : 1.0f)
+                                      : tf;
+                  } else {
+                    const int j = (col - 5) >> 2, comp = (col - 5) & 3;
+                    const FullSlot S = full_slot(mr, L.pl[j], j < N_tag, p.inv_G);
+                    f[k] = comp == 0 ? S.a : comp == 1 ? S.b : comp == 2 ? S.c : S.d;
+                  }
+                }
+                v = make_float4(f[0], f[1], f[2], f[3]);
+              }
+              env_q[g] = v;
+            }
+          }
+        } else {
+          const uint32_t slots = uint32_t(N) * uint32_t(N);
+          for (uint32_t u = uint32_t(lt); u < slots; u += uint32_t(ts)) {
+            const uint32_t i = fastdiv(u, p.div_N);
+            const uint32_t j = u - i * uint32_t(N);
+            const uint32_t me = L.pl[i];
+            const FullSlot S = full_slot(me, L.pl[j], int(j) < N_tag, p.inv_G);
+            float* row = env_obs + int64_t(i) * D;
+            Slot4 v;
+            v.a = S.a;
+            v.b = S.b;
+            v.c = S.c;
+            v.d = S.d;
+            *reinterpret_cast<Slot4*>(row + 5 + 4 * j) = v;
+            if (j == 0) {
+              row[0] = static_cast<float>(pos_x_of(me)) * p.inv_G;
+              row[1] = static_cast<float>(pos_y_of(me)) * p.inv_G;
+              row[2] = int(i) < N_tag ? 1.0f : 0.0f;
+              row[3] = (me & kDeadBit) ? 0.0f : 1.0f;
+              row[4] = tf;
+            }
           }
         }
       }
@@ -1032,7 +1104,7 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
 
 template <bool WIDE, int KX, bool CN, bool BIG>
 __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
-    __attribute__((amdgpu_waves_per_eu((WIDE || BIG || KX == 0) ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
+    __attribute__((amdgpu_waves_per_eu((WIDE || BIG || KX <= 0) ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
                                                              const float* __restrict__ probs, uint32_t g_lo,
                                                              uint32_t g_hi) {
   extern __shared__ __align__(16) unsigned char smem[];

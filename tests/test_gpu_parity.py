@@ -286,6 +286,9 @@ EDGE = {
     "full_obs_tiny": dict(num_envs=40, num_agents=5, num_taggers=1, grid_size=6, episode_length=12, obs_mode=1),
     "full_obs_fifty": dict(num_envs=9, num_agents=50, num_taggers=10, grid_size=20, episode_length=30, obs_mode=1),
     "full_obs_odd_count": dict(num_envs=5, num_agents=131, num_taggers=7, grid_size=15, episode_length=10, obs_mode=1),
+    # N % 4 == 0 and at least one wave per env: rows leave as aligned 16-byte pieces
+    "full_obs_one_wave": dict(num_envs=3, num_agents=132, num_taggers=9, grid_size=12, episode_length=8, obs_mode=1),
+    "full_obs_two_waves": dict(num_envs=3, num_agents=260, num_taggers=20, grid_size=16, episode_length=6, obs_mode=1),
     "full_obs_thousand": dict(num_envs=2, num_agents=1000, num_taggers=100, grid_size=30, episode_length=5, obs_mode=1),
     "odd_rewards": dict(num_envs=12, num_agents=25, num_taggers=5, grid_size=8, episode_length=20, obs_k=2,
                         tag_reward=0.3, tag_penalty=-2.5),
