@@ -973,13 +973,14 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
         const float tf = static_cast<float>(t_out) * p.inv_T;
         if (vec && ts >= kWaveSize) {
           // N % 4 == 0: the env's block starts on a 16-byte boundary, and so does every fourth
-          // float of it.  A wave takes whole rows and writes them as ALIGNED 16-byte pieces; a
+          // float of it.  A wave takes a run of whole rows and writes them as ALIGNED 16-byte pieces; a
           // row starts 0..3 floats past such a boundary, so a piece holds the tail of one slot
           // and the head of the next, at an offset that is the same for the whole row.
           const int wv = lt >> 6, lane = lt & (kWaveSize - 1), n_waves = ts >> 6;
           const uint32_t Du = uint32_t(D);
           float4* const env_q = reinterpret_cast<float4*>(env_obs);
-          for (int i = wv; i < N; i += n_waves) {
+          const int rows_per_wave = (N + n_waves - 1) / n_waves;  // contiguous rows: one sequential stream per wave
+          for (int i = wv * rows_per_wave; i < min(N, (wv + 1) * rows_per_wave); ++i) {
             const uint32_t row_f = uint32_t(i) * Du;                       // first float of row i in the block
             const uint32_t g_lo = (row_f + 3u) >> 2, g_hi = (row_f + Du + 3u) >> 2;  // pieces that start in row i
             const uint32_t shift = (4u * g_lo - row_f - 5u) & 3u;          // slot component a piece starts with
