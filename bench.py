@@ -3,12 +3,14 @@
 
 A "step" is one roll-out iteration of the whole batch: sample an action for every agent from
 its policy probabilities, advance every environment by one Tag step, reset the environments
-that finished (paper Sec. 4.5 items 3-6), all through libwd's C ABI.  The metric is the paper's
+that finished (paper Sec. 4.5 items 3-6), all through libwd's C ABI.  By default 25 such
+iterations go into one launch (wd_rollout, every output written in place in every iteration,
+exactly as one wd_iterate call per iteration would; --mode fused times that).  The metric is the paper's
 (Sec. 5.3): environment steps per second at 2000 environments x 1000 agents; agent-steps/s and
 the fraction of the HBM roofline are reported next to it, and the CPU oracle is timed on the
 host cores as a baseline.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--mode fused|separate]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--mode auto|rollout|fused|separate]
 
 Prints ONE JSON line.
 """
@@ -27,20 +29,34 @@ RING = 8               # steps of policy outputs resident before the timed regio
 PAPER_ENV_STEPS_PER_S = 2.9e6  # Sec. 5.3, one A100: context only
 
 
-def read_traffic(workload):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary."""
+def read_traffic(workload, iterations_per_launch):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary
+    (None unless that summary was taken with the same number of iterations per launch)."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
     if not os.path.exists(path):
         return None
+    found = {}
     for line in open(path):
-        if line.startswith("traffic_bytes_per_launch"):
-            return float(line.split()[1])
-    return None
+        parts = line.split()
+        if len(parts) == 2 and parts[0] in ("traffic_bytes_per_launch", "iterations_per_launch"):
+            found[parts[0]] = float(parts[1])
+    if found.get("iterations_per_launch", 1) != iterations_per_launch:
+        return None
+    return found.get("traffic_bytes_per_launch")
 
 
-def run_iterations(env, ring, first_g, count, mode):
+def run_iterations(env, ring, first_g, count, mode, per_launch=1):
+    """Enqueues `count` roll-out iterations; returns the number of launches of the dominant kernel."""
     import paper_2108_13976_amd as wd
 
+    if mode == "rollout":  # several iterations per launch, every output in place as with wd_iterate
+        launches = 0
+        while count > 0:
+            k = min(per_launch, count)
+            wd.wd_rollout(env.handle, ring.data_ptr(), RING, k, None)
+            count -= k
+            launches += 1
+        return launches
     for k in range(count):
         probs = ring[(first_g + k) % RING]
         if mode == "fused":
@@ -49,10 +65,12 @@ def run_iterations(env, ring, first_g, count, mode):
             env.sample(probs)
             env.step()
             env.reset(wd.WD_RESET_DONE)
+    return count
 
 
-def time_gpu(cfg, ring, steps, warmup, mode, **over):
-    """Returns (seconds for `steps` iterations by the host clock, same by HIP events, final state stats)."""
+def time_gpu(cfg, ring, steps, warmup, mode, per_launch=1, **over):
+    """Returns (seconds for `steps` iterations by the host clock, same by HIP events, final state
+    stats, algorithmic bytes per iteration, launches of the dominant kernel in the timed region)."""
     import torch
     import paper_2108_13976_amd as wd
 
@@ -60,12 +78,12 @@ def time_gpu(cfg, ring, steps, warmup, mode, **over):
     kw.update(over)
     env = wd.TagEnvs(device="cuda:0", **kw)
     env.reset(wd.WD_RESET_ALL)
-    run_iterations(env, ring, 0, warmup, mode)
+    run_iterations(env, ring, 0, warmup, mode, per_launch)
     start_ev, end_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     start_ev.record(env.torch_stream)
-    run_iterations(env, ring, warmup, steps, mode)
+    launches = run_iterations(env, ring, warmup, steps, mode, per_launch)
     end_ev.record(env.torch_stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -76,7 +94,7 @@ def time_gpu(cfg, ring, steps, warmup, mode, **over):
     }
     bytes_per_iteration = env.layout.bytes_per_iteration
     env.close()
-    return wall, event_s, stats, bytes_per_iteration
+    return wall, event_s, stats, bytes_per_iteration, launches
 
 
 def time_sampler(cfg, ring, reps=200):
@@ -108,15 +126,39 @@ def time_sampler(cfg, ring, reps=200):
             "sampler_over_torch": t_torch / t_wd, "sampler_us": t_wd * 1e6}
 
 
-def time_rollout(cfg, ring, k=25, launches=40, warm=2):
-    """wd_rollout: k iterations per launch with every iteration's action, reward, done and
-    observations recorded (paper Sec. 4.5 item 7: roll-out data gathered into a training batch).
-    The defaults cover the same iterations as the main timing: 50 warm-up, then 1000."""
+def rollout_offered(cfg):
+    """wd_rollout covers partial observations with K <= 8 in the small (LDS) layout; whether it
+    takes this configuration is asked of the library itself, on a one-env copy."""
+    import paper_2108_13976_amd as wd
+    import torch
+
+    if cfg.obs_mode != 0:
+        return False
+    kw = cfg.kwargs()
+    kw["num_envs"] = 1
+    env = wd.TagEnvs(device="cuda:0", **kw)
+    env.reset(wd.WD_RESET_ALL)
+    probs = torch.full((1, 1, cfg.num_agents, 5), 0.2, dtype=torch.float32, device="cuda:0")
+    try:
+        wd.wd_rollout(env.handle, probs.data_ptr(), 1, 1, None)
+        ok = True
+    except wd.WdError as err:
+        if err.status != wd.binding.WD_E_UNSUPPORTED:
+            raise
+        ok = False
+    torch.cuda.synchronize()
+    env.close()
+    return ok
+
+
+def time_rollout(cfg, ring, k=25, steps=1000, warmup=50):
+    """wd_rollout with every iteration's action, reward, done and observations recorded in
+    [k, ...] arrays (paper Sec. 4.5 item 7: roll-out data gathered into a training batch), over
+    the same iterations as the main timing."""
     import torch
     import paper_2108_13976_amd as wd
+    from paper_2108_13976_amd.binding import wd_rollout_buffers
 
-    if cfg.obs_mode != 0 or cfg.num_agents > 4096:
-        return {}
     env = wd.TagEnvs(device="cuda:0", **cfg.kwargs())
     env.reset(wd.WD_RESET_ALL)
     E, N, D = env.E, env.N, env.D
@@ -124,24 +166,19 @@ def time_rollout(cfg, ring, k=25, launches=40, warm=2):
            "reward": torch.empty((k, E, N), dtype=torch.float32, device=env.device),
            "done": torch.empty((k, E), dtype=torch.int32, device=env.device),
            "obs": torch.empty((k, E, N, D), dtype=torch.float32, device=env.device)}
-    from paper_2108_13976_amd.binding import wd_rollout_buffers
     bufs = wd_rollout_buffers(*[out[n].data_ptr() for n in ("action", "reward", "done", "obs")])
-    res = {"rollout_k": k}
-    # with every iteration's outputs recorded, then state only (outputs in place, as wd_iterate)
-    for label, b in (("rollout", bufs), ("rollout_in_place", None)):
-        env.reset(wd.WD_RESET_ALL)
-        for _ in range(warm):
-            wd.wd_rollout(env.handle, ring.data_ptr(), RING, k, b)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(launches):
-            wd.wd_rollout(env.handle, ring.data_ptr(), RING, k, b)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        res[label + "_env_steps_per_s"] = launches * k * cfg.num_envs / dt
-        res[label + "_us_per_iteration"] = dt / (launches * k) * 1e6
+    launches = max(1, steps // k)
+    for _ in range(max(1, warmup // k)):
+        wd.wd_rollout(env.handle, ring.data_ptr(), RING, k, bufs)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(launches):
+        wd.wd_rollout(env.handle, ring.data_ptr(), RING, k, bufs)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
     env.close()
-    return res
+    return {"rollout_recorded_k": k, "rollout_recorded_env_steps_per_s": launches * k * cfg.num_envs / dt,
+            "rollout_recorded_us_per_iteration": dt / (launches * k) * 1e6}
 
 
 def time_oracle(cfg, ring, envs_per_thread, iterations, threads):
@@ -174,7 +211,11 @@ def main():
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="tag_2000x1000")
-    ap.add_argument("--mode", choices=("fused", "separate"), default="fused")
+    ap.add_argument("--mode", choices=("auto", "rollout", "fused", "separate"), default="auto",
+                    help="rollout: wd_rollout, several iterations per launch, outputs in place; fused: one "
+                         "wd_iterate launch per iteration; separate: wd_sample, wd_step, wd_reset per iteration; "
+                         "auto: rollout where the library offers it for the configuration, else fused")
+    ap.add_argument("--iterations-per-launch", type=int, default=25, help="rollout mode only")
     ap.add_argument("--obs", choices=("partial", "full"), default="partial",
                     help="observation mode; full = one slot per agent (D = 5 + 4N), HBM-write bound")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -213,13 +254,21 @@ def main():
     ring = device_probs_ring(cfg.seed, RING, cfg.num_envs, cfg.num_agents, "cuda:0")
     torch.cuda.synchronize()
 
-    wall, event_s, stats, bytes_per_iteration = time_gpu(cfg, ring, args.steps, args.warmup, args.mode)
+    mode = args.mode
+    if mode == "auto":
+        mode = "rollout" if rollout_offered(cfg) else "fused"
+    per_launch = args.iterations_per_launch if mode == "rollout" else 1
+    wall, event_s, stats, bytes_per_iteration, launches = time_gpu(cfg, ring, args.steps, args.warmup, mode, per_launch)
     iters_per_s = args.steps / wall
     env_steps = iters_per_s * cfg.num_envs
     agent_steps = env_steps * cfg.num_agents
-    launch_s = event_s / args.steps  # average duration of one iteration on the launch stream
-    achieved_gbs = bytes_per_iteration / launch_s / 1e9
-    traffic = read_traffic(args.workload) if args.obs == "partial" else None
+    launch_s = event_s / launches  # average duration of one launch on its stream (gaps included)
+    bytes_per_launch = bytes_per_iteration * args.steps / launches
+    achieved_gbs = bytes_per_launch / launch_s / 1e9
+    traffic = read_traffic(args.workload, per_launch) if (args.obs == "partial" and mode != "separate") else None
+    kernel_name = {"rollout": f"rollout_kernel ({per_launch} iterations of sample + step + reset per launch)",
+                   "fused": "env_kernel (sample + step + reset fused)",
+                   "separate": "sample + step + reset kernels"}[mode]
 
     out = {
         "metric": "env_steps_per_s",
@@ -237,16 +286,17 @@ def main():
         "config": {
             "workload": args.workload, "num_envs": cfg.num_envs, "num_agents": cfg.num_agents,
             "num_taggers": cfg.num_taggers, "grid_size": cfg.grid_size, "episode_length": cfg.episode_length,
-            "obs": f"partial K={cfg.obs_k}" if cfg.obs_mode == 0 else f"full D={cfg.obs_dim}", "tag_r2": cfg.tag_r2, "seed": cfg.seed, "mode": args.mode,
+            "obs": f"partial K={cfg.obs_k}" if cfg.obs_mode == 0 else f"full D={cfg.obs_dim}", "tag_r2": cfg.tag_r2, "seed": cfg.seed, "mode": mode,
+            "iterations_per_launch": per_launch,
             "probs": f"softmax(N(0,1)) float32, ring of {RING} steps resident in HBM",
         },
         "agent_steps_per_s": agent_steps,
         "paper_env_steps_per_s_a100": PAPER_ENV_STEPS_PER_S,
         "roofline": {
             "bound": "hbm",
-            "kernel": "env_kernel (sample + step + reset fused)" if args.mode == "fused" else "sample + step + reset kernels",
+            "kernel": kernel_name,
             "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
-            "algorithmic_bytes_per_launch": bytes_per_iteration, "avg_launch_us": launch_s * 1e6,
+            "algorithmic_bytes_per_launch": bytes_per_launch, "avg_launch_us": launch_s * 1e6,
             "traffic": traffic,
         },
         "state_at_end": stats,
@@ -255,16 +305,22 @@ def main():
     if not args.no_extras:
         extras = {}
         # worst case for the neighbour search: tagging disabled, every agent live in every step
-        w2, e2, _, _ = time_gpu(cfg, ring, min(args.steps, 300), 20, args.mode, tag_r2=-1)
-        extras["all_live_env_steps_per_s"] = min(args.steps, 300) / w2 * cfg.num_envs
-        extras["all_live_hbm_frac"] = bytes_per_iteration / (e2 / min(args.steps, 300)) / 1e9 / HBM_PEAK_GBS
+        short = min(args.steps, 300)
+        w2, e2, _, _, _ = time_gpu(cfg, ring, short, 25, mode, per_launch, tag_r2=-1)
+        extras["all_live_env_steps_per_s"] = short / w2 * cfg.num_envs
+        extras["all_live_hbm_frac"] = bytes_per_iteration / (e2 / short) / 1e9 / HBM_PEAK_GBS
         # the sampler alone against the framework's operator on the same probabilities
         # (paper Sec. 5.4 compares its sampler with the PyTorch one)
         extras.update(time_sampler(cfg, ring))
-        extras.update(time_rollout(cfg, ring))
-        other = "separate" if args.mode == "fused" else "fused"
-        w3, _, _, _ = time_gpu(cfg, ring, min(args.steps, 300), 20, other)
-        extras[f"{other}_env_steps_per_s"] = min(args.steps, 300) / w3 * cfg.num_envs
+        if rollout_offered(cfg):
+            extras.update(time_rollout(cfg, ring, k=per_launch if mode == "rollout" else 25))
+        # the other launch shapes over the same iterations as the main timing
+        for other in ("rollout", "fused", "separate"):
+            if other == mode or (other == "rollout" and not rollout_offered(cfg)):
+                continue
+            k_other = args.iterations_per_launch if other == "rollout" else 1
+            w3, _, _, _, _ = time_gpu(cfg, ring, args.steps, args.warmup, other, k_other)
+            extras[f"{other}_env_steps_per_s"] = args.steps / w3 * cfg.num_envs
         out["extras"] = extras
 
     if not args.no_cpu_baseline:

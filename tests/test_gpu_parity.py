@@ -182,6 +182,53 @@ def test_headline_workload_full_size_sampled_envs_and_invariants():
     gpu.close()
 
 
+def test_headline_workload_full_size_multi_step_launches():
+    """The launch shape the benchmark times: wd_rollout, 25 iterations per launch, outputs in
+    place, at 2000 x 1000.  Sampled envs against the oracle after every launch; then one launch
+    that records every iteration, each slice of the sampled envs against the oracle."""
+    import paper_2108_13976_amd as wd
+
+    cfg = CONFIGS["tag_2000x1000"]
+    kw = cfg.kwargs()
+    E, N = cfg.num_envs, cfg.num_agents
+    k, ring_len = 25, 5
+    host_ring = np.stack([probs_for_step(cfg.seed, r, E, N) for r in range(ring_len)])
+    gpu = make_gpu(kw)
+    ring = upload(host_ring, gpu.device)
+    gpu.reset(wd.WD_RESET_ALL)
+    rng = np.random.default_rng(11)
+    sample_envs = sorted(int(e) for e in rng.choice(E, size=10, replace=False)) + [0, E - 1]
+    oracles = {e: make_oracle(kw, e, e + 1) for e in sample_envs}
+    for o in oracles.values():
+        o.reset()
+    g = 0
+    for launch in range(2):
+        gpu.rollout(ring, k, record=())
+        for s in range(k):
+            for e, o in oracles.items():
+                o.iterate(host_ring[(g + s) % ring_len][e:e + 1], g + s)
+        g += k
+        assert gpu.global_step == g
+        state = gpu.to_host()
+        for e, o in oracles.items():
+            assert_equal_state(state, o, f"after launch {launch} env {e}", env_lo=e)
+        check_obs_invariants(cfg, state, FLOAT_TOL)
+    k2 = 4
+    rec = gpu.rollout(ring, k2)
+    rec = {n: v.cpu().numpy() for n, v in rec.items()}
+    for s in range(k2):
+        for e, o in oracles.items():
+            pr = host_ring[(g + s) % ring_len][e:e + 1]
+            o.sample(pr, g + s)
+            o.step()
+            assert np.array_equal(rec["action"][s][e], o.action[0]), (s, e)
+            assert np.array_equal(rec["done"][s][e:e + 1], o.done), (s, e)
+            assert np.abs(rec["reward"][s][e] - o.reward[0]).max() <= FLOAT_TOL, (s, e)
+            o.reset(1)
+            assert np.abs(rec["obs"][s][e].astype(np.float64) - o.obs[0]).max() <= FLOAT_TOL, (s, e)
+    gpu.close()
+
+
 @pytest.mark.parametrize("name,k,rounds", [("tag_10x5", 37, 8), ("tag_100x50", 16, 5), ("tag_20000x100", 6, 2)])
 def test_multi_step_rollout_equals_single_iterations(name, k, rounds):
     """wd_rollout (k iterations in one launch, per-iteration outputs) against k calls of the
