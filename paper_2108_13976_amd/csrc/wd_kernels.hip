@@ -231,7 +231,7 @@ __device__ __forceinline__ int pos_y_of(uint32_t pl) { return int((pl >> 16) & 0
 // (wave_totals: one int per wave of the team).  Contains a workgroup barrier when the team
 // spans several waves, so every thread of the workgroup must call it.
 __device__ __forceinline__ int team_exclusive_scan(int v, int lt, int ts_log2, int* wave_totals, int* total) {
-  const int lane = threadIdx.x & (kWaveSize - 1);
+  const int lane = lt & (kWaveSize - 1);  // teams of a wave or more start on wave boundaries
   const int width = ts_log2 >= 6 ? kWaveSize : (1 << ts_log2);
   const int sub = lane & (width - 1);
   int incl = v;
@@ -304,7 +304,7 @@ struct TeamLds {
   uint16_t* nbr;     // [NPAD][K] neighbour indices; overlays the tail of slot/best/credits/counts
   uint32_t* nbr_lo;  // compact form for K = 4, N < 1024: ids 0..2 and two bits of id 3 per agent,
   uint8_t* nbr_hi;   // and the other eight bits of id 3 (same memory as nbr)
-  int32_t* misc;     // [0] tags this step, [1] t after the call, [2] rows to be written, [3] length of retry[], [4..19] scan scratch
+  int32_t* misc;     // [0] tags this step, [1] t after the call, [2] rows to be written, [3] length of retry[], [4..19] scan scratch, [20..21] of the first team: workgroup votes
   uint16_t* edges;   // [nbx + 1] first cell of each bucket coordinate; edges[nbx] = G
   SortedList<WIDE> sorted;  // [NPAD + pad] the live agents, grouped by bucket
   uint16_t* slot;    // [NPAD] where agent i sits in `sorted`
@@ -586,7 +586,7 @@ struct StepOut {
   int32_t* done_log; // optional: done flags before the reset clears them
 };
 
-template <bool WIDE, int KX, bool CN, bool BIG>
+template <bool WIDE, int KX, bool CN, bool BIG, bool LOOPED>
 __device__ __forceinline__ void env_body(const Params& p, const StepOut out, const int mode,
                                          const float* __restrict__ probs, uint32_t g_lo, uint32_t g_hi,
                                          unsigned char* smem, const int tid) {
@@ -618,6 +618,15 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
   bool done_now = done_in != 0;
   Buckets bk = choose_buckets(p, nlr_in + N_tag);
   if (lt == 0) L.misc[3] = 0;  // every mode passes a barrier before the neighbour search appends
+  // Two workgroup-wide votes: some env of the workgroup is being reset; some env gets no new
+  // rows.  Inside the roll-out loop (LOOPED) they are flags in the first team's scalars, cleared
+  // here, set before a barrier that the code needs anyway and read after it; the one-step
+  // kernel uses the voting barriers (each form measured faster where it is used).
+  int32_t* const wg_flags = reinterpret_cast<int32_t*>(smem + p.off_misc) + 20;
+  if (LOOPED && tid == 0) {
+    wg_flags[0] = 0;
+    wg_flags[1] = 0;
+  }
 
   if (stepping) {
     if (step_act) {
@@ -765,7 +774,16 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
     // ---- reset: restore the start state of envs that are done (or of all) ------------------
     if (out.done_log && valid && lt == 0) out.done_log[e] = done_now ? 1 : 0;  // the flag before the reset clears it
     const bool reset_act = valid && (mode == kModeResetAll || done_now);
-    const bool any_reset = (mode == kModeIterate) ? (__syncthreads_or(reset_act ? 1 : 0) != 0) : true;
+    bool any_reset = true;
+    if (mode == kModeIterate) {
+      if constexpr (LOOPED) {
+        if (reset_act && lt == 0) wg_flags[0] = 1;
+        __syncthreads();
+        any_reset = wg_flags[0] != 0;
+      } else {
+        any_reset = __syncthreads_or(reset_act ? 1 : 0) != 0;
+      }
+    }
     if (any_reset) {
       if (reset_act) {
         bk = choose_buckets(p, N);
@@ -838,6 +856,7 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
       }
     };
     const bool search = out_act && K > 0;
+    if (LOOPED && valid && !out_act && lt == 0) wg_flags[1] = 1;  // read after the two barriers below
     if (search) {
       const int n_sorted = int(L.starts[p.nb_cap]);
       for (int q = lt; q < n_sorted; q += ts) {
@@ -863,7 +882,13 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
         put_neighbours(ent.id, keys);
       }
     }
-    const bool all_out = __syncthreads_and((out_act || !valid) ? 1 : 0) != 0;  // also the barrier before the rows
+    bool all_out;  // also the barrier after which the rows may overlay the sort tables
+    if constexpr (LOOPED) {
+      __syncthreads();
+      all_out = wg_flags[1] == 0;
+    } else {
+      all_out = __syncthreads_and((out_act || !valid) ? 1 : 0) != 0;
+    }
 
     // Rows, in index order.  A wave builds 64 rows in registers and sends them, 32 at a
     // time, through an LDS transpose (which overlays the sort tables) so that each store
@@ -1109,7 +1134,7 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
                                                              const float* __restrict__ probs, uint32_t g_lo,
                                                              uint32_t g_hi) {
   extern __shared__ __align__(16) unsigned char smem[];
-  env_body<WIDE, KX, CN, BIG>(p, StepOut{p.action, p.reward, p.obs, p.done_log}, mode, probs, g_lo, g_hi, smem, int(threadIdx.x));
+  env_body<WIDE, KX, CN, BIG, false>(p, StepOut{p.action, p.reward, p.obs, p.done_log}, mode, probs, g_lo, g_hi, smem, int(threadIdx.x));
 }
 
 // Workgroup-wide copy of `count` 4-byte words: 16-byte pieces when both ends are aligned.
@@ -1148,10 +1173,10 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
   KernargPtr ak = (KernargPtr)__builtin_amdgcn_kernarg_segment_ptr();
   const int steps = args.roll.steps;
   int ring_at = args.roll.ring_pos;
+  int tid = threadIdx.x;
   for (int s = 0; s < steps; ++s) {
     asm volatile("" : "+s"(ak));
-    int tid = threadIdx.x;  // likewise: what a thread derives from its id is recomputed per step, not kept
-    asm volatile("" : "+v"(tid));
+    asm volatile("" : "+v"(tid));  // likewise: what a thread derives from its id is recomputed per step, not kept
     const RollArgs& a = *(const RollArgs*)ak;
     const Params& p = a.p;
     const Roll& roll = a.roll;
@@ -1163,7 +1188,7 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
       if (roll.obs) out.obs = roll.obs + s * EN * p.D;
     }
     const uint64_t g = a.g0 + uint64_t(s);
-    env_body<WIDE, KX, CN, false>(p, out, kModeIterate, a.ring + int64_t(ring_at) * EN * kNumActions, uint32_t(g),
+    env_body<WIDE, KX, CN, false, true>(p, out, kModeIterate, a.ring + int64_t(ring_at) * EN * kNumActions, uint32_t(g),
                                   uint32_t(g >> 32), smem, tid);
     ring_at = ring_at + 1 == roll.ring_len ? 0 : ring_at + 1;
     __syncthreads();  // this step's state and LDS use are complete before the next step starts
