@@ -3,14 +3,16 @@
 
 A "step" is one roll-out iteration of the whole batch: sample an action for every agent from
 its policy probabilities, advance every environment by one Tag step, reset the environments
-that finished (paper Sec. 4.5 items 3-6), all through libwd's C ABI.  By default 25 such
-iterations go into one launch (wd_rollout, every output written in place in every iteration,
-exactly as one wd_iterate call per iteration would; --mode fused times that).  The metric is the paper's
+that finished (paper Sec. 4.5 items 3-6), all through libwd's C ABI, one wd_iterate launch per
+iteration, so that every iteration's observations and rewards can be read before the next (as a
+policy would).  --mode rollout times wd_rollout instead: 25 iterations per launch with the
+same writes in every iteration, of which only the last iteration's survive; the default run
+reports it among the extras.  The metric is the paper's
 (Sec. 5.3): environment steps per second at 2000 environments x 1000 agents; agent-steps/s and
 the fraction of the HBM roofline are reported next to it, and the CPU oracle is timed on the
 host cores as a baseline.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--mode auto|rollout|fused|separate]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--mode fused|rollout|separate]
 
 Prints ONE JSON line.
 """
@@ -211,10 +213,11 @@ def main():
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="tag_2000x1000")
-    ap.add_argument("--mode", choices=("auto", "rollout", "fused", "separate"), default="auto",
-                    help="rollout: wd_rollout, several iterations per launch, outputs in place; fused: one "
-                         "wd_iterate launch per iteration; separate: wd_sample, wd_step, wd_reset per iteration; "
-                         "auto: rollout where the library offers it for the configuration, else fused")
+    ap.add_argument("--mode", choices=("fused", "rollout", "separate"), default="fused",
+                    help="fused: one wd_iterate launch per iteration (every iteration's outputs can be read "
+                         "before the next); rollout: wd_rollout, several iterations per launch, outputs in "
+                         "place (only the last iteration's survive); separate: wd_sample, wd_step, wd_reset "
+                         "per iteration")
     ap.add_argument("--iterations-per-launch", type=int, default=25, help="rollout mode only")
     ap.add_argument("--obs", choices=("partial", "full"), default="partial",
                     help="observation mode; full = one slot per agent (D = 5 + 4N), HBM-write bound")
@@ -255,8 +258,9 @@ def main():
     torch.cuda.synchronize()
 
     mode = args.mode
-    if mode == "auto":
-        mode = "rollout" if rollout_offered(cfg) else "fused"
+    if mode == "rollout" and not rollout_offered(cfg):
+        print("bench.py: the library does not offer wd_rollout for this configuration", file=sys.stderr)
+        sys.exit(2)
     per_launch = args.iterations_per_launch if mode == "rollout" else 1
     wall, event_s, stats, bytes_per_iteration, launches = time_gpu(cfg, ring, args.steps, args.warmup, mode, per_launch)
     iters_per_s = args.steps / wall
