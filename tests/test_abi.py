@@ -94,7 +94,7 @@ def test_null_and_misaligned_buffers():
 def test_call_order_is_enforced_before_any_launch():
     h = wd.wd_create(good_config(), fake_buffers())
     for call in (lambda: wd.wd_step(h), lambda: wd.wd_sample(h, 0x20000), lambda: wd.wd_iterate(h, 0x20000),
-                 lambda: wd.wd_reset(h, wd.WD_RESET_DONE)):
+                 lambda: wd.wd_rollout(h, 0x20000, 4, 3), lambda: wd.wd_reset(h, wd.WD_RESET_DONE)):
         with pytest.raises(wd.WdError) as ei:
             call()
         assert ei.value.status == binding.WD_E_STATE
@@ -104,6 +104,17 @@ def test_call_order_is_enforced_before_any_launch():
     with pytest.raises(wd.WdError) as ei:
         wd.wd_sample(h, 0)
     assert ei.value.status == binding.WD_E_NULL
+    # wd_rollout checks its own arguments before the call order
+    for ring_len, k in ((0, 1), (1, 0), (-3, 2)):
+        with pytest.raises(wd.WdError) as ei:
+            wd.wd_rollout(h, 0x20000, ring_len, k)
+        assert ei.value.status == binding.WD_E_CONFIG
+    with pytest.raises(wd.WdError) as ei:
+        wd.wd_rollout(h, 0, 1, 1)
+    assert ei.value.status == binding.WD_E_NULL
+    with pytest.raises(wd.WdError) as ei:
+        wd.wd_rollout(h, 0x20000, 1, 1, binding.wd_rollout_buffers(0x30000, 0x30004, None, None))
+    assert ei.value.status == binding.WD_E_ALIGN
     assert wd.wd_get_step(h) == 0
     wd.wd_set_step(h, 2**40 + 3)
     assert wd.wd_get_step(h) == 2**40 + 3
