@@ -136,7 +136,13 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
       p->dead_dx = int32_t(shift);
     }
   }
-  p->wide = narrow ? 0 : 1;
+  // Else, in the large-env layout: keys that need all 32 bits, the dead mark moved into bit 15
+  // of the index array.  Else 64-bit keys.
+  const bool flagged32 = !narrow && big && p->idx_bits <= 15 && G <= 32767 &&
+                         p->idx_bits + bits_for(uint32_t(d2max)) <= 32 &&
+                         ((d2max << p->idx_bits) | uint64_t(N - 1)) < 0xFFFFFFFFull;  // all ones = "none"
+  if (flagged32) narrow = true;  // the same table layout as the 31-bit form
+  p->wide = flagged32 ? 2 : (narrow ? 0 : 1);
   const int key_bytes = narrow ? 4 : 8;
   const bool register_path = c.obs_mode == WD_OBS_PARTIAL && p->K <= wd::kMaxRegisterK;
 
@@ -287,7 +293,7 @@ int wd_create(const wd_config* cfg, const wd_buffers* bufs, wd_handle** out) {
   h->scratch = nullptr;
   if (params.big) {
     // large envs: slots, tag keys, credits and neighbour lists of every env, in one allocation
-    const int64_t E = cfg->num_envs, key_bytes = params.wide ? 8 : 4;
+    const int64_t E = cfg->num_envs, key_bytes = params.wide == 1 ? 8 : 4;
     const int64_t slot_b = align16(2 * params.g_stride_agents * E), best_b = align16(key_bytes * params.g_stride_agents * E);
     const int64_t cred_b = align16(4 * params.g_stride_credits * E), nbr_b = align16(2 * params.g_stride_nbr * E);
     if (hipMalloc(&h->scratch, size_t(slot_b + best_b + cred_b + nbr_b)) != hipSuccess) {

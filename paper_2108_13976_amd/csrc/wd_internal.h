@@ -55,7 +55,8 @@ struct Params {
   float bucket_scale;    // 65536 / G: bucket multiplier = scale * sqrt(n_live / lambda)
   float lambda_c, lambda_min, lambda_max;  // live agents per bucket aimed at: lambda_c / sqrt(n_live), clamped
   uint32_t bucket_mul_max;  // largest multiplier whose bucket table fits nb_cap
-  // (distance, index) keys and bucket entries: 32-bit when wide == 0
+  // (distance, index) keys and bucket entries: 0 = 32-bit keys below 2^31, 1 = 64-bit, 2 = 32-bit
+  // keys using all bits (dead mark in the index array)
   int32_t wide, idx_bits, xy_bits;
   int32_t dead_dx;       // 32-bit form: x offset that marks a runner tagged in this step
   FastDiv div_N, div_NG;

@@ -161,8 +161,12 @@ __global__ __launch_bounds__(kWorkgroupSize) void init_start_positions_kernel(co
 //     product.  A runner tagged in this step is marked by adding `dead_dx` to its x: that
 //     puts its squared distance from any agent on the grid into the band whose key has bit
 //     31 set, above every live key, so it sorts last and reads as "no neighbour".
-//   WIDE (64-bit keys): entries (x | y << 16 | dead bit, index).
+//   WIDE = 1 (64-bit keys): entries (x | y << 16 | dead bit, index).
+//   WIDE = 2 (32-bit keys that need all 32 bits, so that no band is left for the dead mark):
+//     arrays as in the narrow form; a tagged runner is marked in bit 15 of its index, which
+//     costs two instructions per candidate.
 // ----------------------------------------------------------------------------------
+constexpr int kKeys31 = 0, kKeys64 = 1, kKeys32 = 2;
 typedef short short2v __attribute__((ext_vector_type(2)));
 
 struct Ent {
@@ -170,11 +174,11 @@ struct Ent {
   uint32_t id;   // agent index
 };
 
-template <bool WIDE>
+template <int WIDE>
 struct SortedList;
 
 template <>
-struct SortedList<false> {
+struct SortedList<kKeys31> {
   using Key = uint32_t;
   uint32_t* pos;
   uint16_t* id;
@@ -191,7 +195,7 @@ struct SortedList<false> {
 };
 
 template <>
-struct SortedList<true> {
+struct SortedList<kKeys64> {
   using Key = unsigned long long;
   uint2* ent;
   __device__ __forceinline__ Ent get(uint32_t q) const {
@@ -207,13 +211,34 @@ struct SortedList<true> {
   static __device__ __forceinline__ int y(const Ent& e) { return int((e.pos >> 16) & 0x7FFFu); }
 };
 
+constexpr uint32_t kDeadIdFlag = 0x8000u;
+
+template <>
+struct SortedList<kKeys32> {
+  using Key = uint32_t;
+  uint32_t* pos;
+  uint16_t* id;
+  __device__ __forceinline__ Ent get(uint32_t q) const { return Ent{pos[q], uint32_t(id[q])}; }
+  __device__ __forceinline__ void put(uint32_t q, int x, int y, int i) const {
+    pos[q] = uint32_t(x) | (uint32_t(y) << 16);
+    id[q] = uint16_t(i);
+  }
+  __device__ __forceinline__ void mark_dead(uint32_t q) const { id[q] = uint16_t(id[q] | kDeadIdFlag); }
+  __device__ __forceinline__ bool dead(const Ent& e) const { return (e.id & kDeadIdFlag) != 0; }
+  static __device__ __forceinline__ int x(const Ent& e) { return int(e.pos & 0xFFFFu); }
+  static __device__ __forceinline__ int y(const Ent& e) { return int(e.pos >> 16); }
+};
+
 template <typename Key>
 __device__ __forceinline__ Key key_none() {
   return ~Key(0);
 }
-// A 32-bit list slot is empty if it holds the initial value or a dead candidate's key.
-__device__ __forceinline__ bool key_is_none(uint32_t k) { return (k & kDeadBit) != 0; }
-__device__ __forceinline__ bool key_is_none(unsigned long long k) { return k == ~0ull; }
+// An empty list slot holds the initial value; in the narrow form also a dead candidate's key.
+template <int WIDE, typename Key>
+__device__ __forceinline__ bool key_is_none(Key k) {
+  if constexpr (WIDE == kKeys31) return (k & kDeadBit) != 0;
+  return k == ~Key(0);
+}
 
 // Positions by agent index: x | y << 16 | dead bit.
 __device__ __forceinline__ uint32_t pack_pos(int x, int y, bool is_live) {
@@ -297,7 +322,7 @@ __device__ __forceinline__ int bucket_of(int x, int y, const Buckets bk) {
 
 // Views of one team's tables: in LDS, except that a large env (BIG) keeps slots, tag keys,
 // credits and neighbour lists in device memory.
-template <bool WIDE, bool BIG>
+template <int WIDE, bool BIG>
 struct TeamLds {
   using Key = typename SortedList<WIDE>::Key;
   uint32_t* pl;      // [NPAD] packed position + dead bit, by agent index
@@ -320,12 +345,12 @@ struct TeamLds {
     pl = reinterpret_cast<uint32_t*>(keep + p.off_pl);
     misc = reinterpret_cast<int32_t*>(keep + p.off_misc);
     edges = reinterpret_cast<uint16_t*>(keep + p.off_edges);
-    if constexpr (WIDE) {
+    if constexpr (WIDE == kKeys64) {
       sorted.ent = reinterpret_cast<uint2*>(xr + p.off_sorted);
     } else {
       sorted.pos = reinterpret_cast<uint32_t*>(xr + p.off_sorted);
       sorted.id = reinterpret_cast<uint16_t*>(xr + p.off_sorted_id);
-      sorted.dead_dx = p.dead_dx;
+      if constexpr (WIDE == kKeys31) sorted.dead_dx = p.dead_dx;
     }
     starts = reinterpret_cast<uint16_t*>(xr + p.off_starts);
     counts = reinterpret_cast<uint32_t*>(yr + p.off_counts);
@@ -351,7 +376,7 @@ struct TeamLds {
 // Second half of the counting sort: bucket counts -> start offsets -> entries in bucket
 // order.  `act` marks teams that take part; every thread of the workgroup must call
 // (barriers inside).  Requires pl[] written and counts[] filled, and a barrier after that.
-template <bool WIDE, typename Tables>
+template <int WIDE, typename Tables>
 __device__ __forceinline__ void scan_and_scatter(const Params& p, const Tables& L, bool act, int lt, int ts,
                                                  const Buckets bk) {
   int part = 0;
@@ -423,10 +448,10 @@ __device__ __forceinline__ void insert_key(unsigned long long (&keys)[KT], unsig
 // out by splitting its bucket row at its slot.
 template <int KT>
 __device__ __forceinline__ void scan_range(unsigned long long (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y,
-                                           int ib, const SortedList<true>& sorted) {
+                                           int ib, const SortedList<kKeys64>& sorted) {
   for (uint32_t q = qb; q < qe; ++q) {
     const Ent ent = sorted.get(q);
-    const int dx = SortedList<true>::x(ent) - x, dy = SortedList<true>::y(ent) - y;
+    const int dx = SortedList<kKeys64>::x(ent) - x, dy = SortedList<kKeys64>::y(ent) - y;
     const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
     unsigned long long key = ((unsigned long long)(d2) << ib) | (unsigned long long)(ent.id);
     if (sorted.dead(ent)) key = key_none<unsigned long long>();
@@ -436,7 +461,7 @@ __device__ __forceinline__ void scan_range(unsigned long long (&keys)[KT], uint3
 
 template <int KT>
 __device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y, int ib,
-                                           const SortedList<false>& sorted) {
+                                           const SortedList<kKeys31>& sorted) {
   const short2v me = __builtin_bit_cast(short2v, uint32_t(x) | (uint32_t(y) << 16));
   for (uint32_t q = qb; q < qe; ++q) {
     const short2v d = __builtin_bit_cast(short2v, sorted.pos[q]) - me;       // (dx, dy), one packed subtract
@@ -445,7 +470,21 @@ __device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, ui
   }
 }
 
-template <bool WIDE, int KT, bool FIRST>
+template <int KT>
+__device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y, int ib,
+                                           const SortedList<kKeys32>& sorted) {
+  const short2v me = __builtin_bit_cast(short2v, uint32_t(x) | (uint32_t(y) << 16));
+  for (uint32_t q = qb; q < qe; ++q) {
+    const short2v d = __builtin_bit_cast(short2v, sorted.pos[q]) - me;
+    const uint32_t d2 = uint32_t(__builtin_amdgcn_sdot2(d, d, 0, false));
+    const uint32_t idv = sorted.id[q];
+    // a marked entry becomes the empty key (all ones): sign-extend the flag bit over the key
+    const uint32_t dead_mask = uint32_t(int32_t(idv << 16) >> 31);
+    insert_key<KT>(keys, ((d2 << ib) | idv) | dead_mask);
+  }
+}
+
+template <int WIDE, int KT, bool FIRST>
 __device__ __forceinline__ bool nearest_keys(typename SortedList<WIDE>::Key (&keys)[KT], int K, int x, int y,
                                              uint32_t self_slot, const Buckets bk, int ib,
                                              const SortedList<WIDE>& sorted, const uint16_t* starts,
@@ -482,7 +521,7 @@ __device__ __forceinline__ bool nearest_keys(typename SortedList<WIDE>::Key (&ke
           if (uint32_t(gap * gap) <= kth_d2) scan_range<KT>(keys, rs[px1 + 1], rs[x1 + 1], x, y, ib, sorted);
         }
       }
-      if (!key_is_none(keys[K - 1])) kth_d2 = uint32_t(keys[K - 1] >> ib);
+      if (!key_is_none<WIDE>(keys[K - 1])) kth_d2 = uint32_t(keys[K - 1] >> ib);
     }
     // Every agent not scanned yet lies beyond a side of the block that is not the grid's
     // edge; `reach` is the distance to the nearest cell beyond such a side.
@@ -586,7 +625,7 @@ struct StepOut {
   int32_t* done_log; // optional: done flags before the reset clears them
 };
 
-template <bool WIDE, int KX, bool CN, bool BIG, bool LOOPED>
+template <int WIDE, int KX, bool CN, bool BIG, bool LOOPED>
 __device__ __forceinline__ void env_body(const Params& p, const StepOut out, const int mode,
                                          const float* __restrict__ probs, uint32_t g_lo, uint32_t g_hi,
                                          unsigned char* smem, const int tid) {
@@ -845,14 +884,14 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
       if constexpr (CN) {
         uint32_t id[4];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) id[kk] = key_is_none(keys[kk]) ? kCompactNone : uint32_t(keys[kk] & idx_mask);
+        for (int kk = 0; kk < 4; ++kk) id[kk] = key_is_none<WIDE>(keys[kk]) ? kCompactNone : uint32_t(keys[kk] & idx_mask);
         L.nbr_lo[me] = id[0] | (id[1] << 10) | (id[2] << 20) | (id[3] << 30);
         L.nbr_hi[me] = uint8_t(id[3] >> 2);
       } else {
 #pragma unroll
         for (int kk = 0; kk < KT; ++kk)
           if (kk < K)
-            L.nbr[me * K + kk] = key_is_none(keys[kk]) ? uint16_t(kNoNeighbour) : uint16_t(keys[kk] & idx_mask);
+            L.nbr[me * K + kk] = key_is_none<WIDE>(keys[kk]) ? uint16_t(kNoNeighbour) : uint16_t(keys[kk] & idx_mask);
       }
     };
     const bool search = out_act && K > 0;
@@ -1128,7 +1167,7 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
   }
 }
 
-template <bool WIDE, int KX, bool CN, bool BIG>
+template <int WIDE, int KX, bool CN, bool BIG>
 __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
     __attribute__((amdgpu_waves_per_eu((WIDE || BIG || KX <= 0) ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
                                                              const float* __restrict__ probs, uint32_t g_lo,
@@ -1161,7 +1200,7 @@ struct RollArgs {  // the one kernel argument of rollout_kernel
   uint64_t g0;
 };
 
-template <bool WIDE, int KX, bool CN>
+template <int WIDE, int KX, bool CN>
 __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
     __attribute__((amdgpu_waves_per_eu((WIDE || KX == 0) ? 4 : 8, 8))) void rollout_kernel(const RollArgs args) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -1205,7 +1244,7 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
   if (roll.obs) copy_words(roll.obs + (last + first) * p.D, p.obs + first * p.D, count * p.D);
 }
 
-template <bool WIDE, int KX, bool CN, bool BIG>
+template <int WIDE, int KX, bool CN, bool BIG>
 hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream) {
   const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
   hipLaunchKernelGGL((env_kernel<WIDE, KX, CN, BIG>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, p,
@@ -1213,13 +1252,13 @@ hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uin
   return hipGetLastError();
 }
 
-template <bool WIDE, int KX, bool CN, bool BIG>
+template <int WIDE, int KX, bool CN, bool BIG>
 hipError_t prepare_env_variant(const Params& p) {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(&env_kernel<WIDE, KX, CN, BIG>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
 }
 
-template <bool WIDE, int KX, bool CN>
+template <int WIDE, int KX, bool CN>
 hipError_t launch_rollout_variant(const Params& p, const Roll& roll, const float* ring, uint64_t g, hipStream_t stream) {
   hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&rollout_kernel<WIDE, KX, CN>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
@@ -1248,6 +1287,10 @@ int variant_of(const Params& p) {
   do {                                                                                     \
     const int kx = variant_of(p);                                                          \
     if (p.big) {                                                                           \
+      if (p.wide == 2) {                                                                   \
+        if (kx == 4) return fn<2, 4, false, true>(p, ##__VA_ARGS__);                       \
+        return fn<2, 0, false, true>(p, ##__VA_ARGS__);                                    \
+      }                                                                                    \
       if (!p.wide) {                                                                       \
         if (kx == 4) return fn<false, 4, false, true>(p, ##__VA_ARGS__);                   \
         return fn<false, 0, false, true>(p, ##__VA_ARGS__);                                \

@@ -329,6 +329,12 @@ EDGE = {
     "thousand_twenty_four": dict(num_envs=2, num_agents=1024, num_taggers=1, grid_size=64, episode_length=8, obs_k=2),
     "many_agents_one_team": dict(num_envs=2, num_agents=1500, num_taggers=50, grid_size=90, episode_length=8, obs_k=4),
     "large_env_narrow_keys": dict(num_envs=2, num_agents=8192, num_taggers=700, grid_size=100, episode_length=4, obs_k=4),
+    # 8000 agents on a 500 grid: (distance, index) keys need exactly 32 bits (dead mark in the index array)
+    "large_env_full_32_bit_keys": dict(num_envs=2, num_agents=8000, num_taggers=900, grid_size=500, episode_length=3, obs_k=3,
+                                       tag_r2=8),
+    # 5000 agents on a 1000 grid: 64-bit keys
+    "large_env_wide_keys": dict(num_envs=2, num_agents=5000, num_taggers=600, grid_size=1000, episode_length=3, obs_k=4,
+                                tag_r2=18),
     "large_env_k_two": dict(num_envs=2, num_agents=6001, num_taggers=3, grid_size=300, episode_length=3, obs_k=2),
     "full_obs_tiny": dict(num_envs=40, num_agents=5, num_taggers=1, grid_size=6, episode_length=12, obs_mode=1),
     "full_obs_fifty": dict(num_envs=9, num_agents=50, num_taggers=10, grid_size=20, episode_length=30, obs_mode=1),
