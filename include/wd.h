@@ -25,7 +25,7 @@
  *   - All state lives in the caller's buffers.  The library allocates no device
  *     memory, with one exception: for envs too large for a workgroup's LDS
  *     (thousands of agents) wd_create allocates per-env work tables once on the
- *     current device (about 18 bytes per agent) and wd_destroy frees them.
+ *     current device (about 20 bytes per agent) and wd_destroy frees them.
  *   - Random numbers are Philox4x32-10 blocks keyed by (seed, global env id,
  *     agent, global step g, stream), so results do not depend on launch shape,
  *     and a run over envs [a, b) with env_offset = a reproduces those envs of the

@@ -172,7 +172,7 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   p->off_counts = take(4ll * nb_cap);
   // slots of the second search pass: over slot[] (not needed any more by then), which the
   // neighbour lists therefore must not overlay; a large env has no slot[] in LDS
-  p->off_retry = (big && register_path) ? take(2 * NPAD) : 0;
+  p->off_retry = 0;  // (a large env searches in its observation kernel, which needs no second pass)
   const int64_t retry_bytes = (big || !register_path) ? 0 : align16(2 * NPAD);
   const int64_t y_tables = off;
   // neighbour lists: K 16-bit ids per agent, or 40 bits per agent when K = 4 and ids fit 10 bits
@@ -181,7 +181,8 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   // per-env strides of the tables a large env keeps in device memory
   p->g_stride_agents = NPAD;
   p->g_stride_credits = (c.num_taggers + 3) / 4 * 4;
-  p->g_stride_nbr = NPAD * int64_t(std::max(p->K, 1));
+  // observation kernel of a large env: about one search per thread
+  p->big_slices = std::max(1, std::min(64, (N + wd::kBigObsWorkgroupSize - 1) / wd::kBigObsWorkgroupSize));
   // The staging area of the rows (32 or 16 rows per wave and flush) overlays the X parts and,
   // in a one-team workgroup, the head of the Y part in front of the neighbour lists.
   const int64_t x_area = int64_t(p->x_stride) * tpw;
@@ -211,6 +212,7 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   p->y_base = int32_t(p->x_base + x_span);
   const int64_t total = int64_t(p->y_base) + int64_t(p->y_stride) * tpw;
   p->lds_bytes = int32_t(std::min<int64_t>(total, INT32_MAX));
+  p->g_stride_image = p->y_base;  // kept part + sorted part, a multiple of 16 bytes
   return total <= kLdsLimitBytes;
 }
 
@@ -292,11 +294,11 @@ int wd_create(const wd_config* cfg, const wd_buffers* bufs, wd_handle** out) {
   if (!h) return WD_E_NULL;
   h->scratch = nullptr;
   if (params.big) {
-    // large envs: slots, tag keys, credits and neighbour lists of every env, in one allocation
+    // large envs: slots, tag keys, credits and the table image of every env, in one allocation
     const int64_t E = cfg->num_envs, key_bytes = params.wide == 1 ? 8 : 4;
     const int64_t slot_b = align16(2 * params.g_stride_agents * E), best_b = align16(key_bytes * params.g_stride_agents * E);
-    const int64_t cred_b = align16(4 * params.g_stride_credits * E), nbr_b = align16(2 * params.g_stride_nbr * E);
-    if (hipMalloc(&h->scratch, size_t(slot_b + best_b + cred_b + nbr_b)) != hipSuccess) {
+    const int64_t cred_b = align16(4 * params.g_stride_credits * E), image_b = params.g_stride_image * E;
+    if (hipMalloc(&h->scratch, size_t(slot_b + best_b + cred_b + image_b)) != hipSuccess) {
       (void)hipGetLastError();
       delete h;
       return WD_E_HIP;
@@ -305,7 +307,7 @@ int wd_create(const wd_config* cfg, const wd_buffers* bufs, wd_handle** out) {
     params.g_best = base;
     params.g_credits = reinterpret_cast<int32_t*>(base + best_b);
     params.g_slot = reinterpret_cast<uint16_t*>(base + best_b + cred_b);
-    params.g_nbr = reinterpret_cast<uint16_t*>(base + best_b + cred_b + slot_b);
+    params.g_image = base + best_b + cred_b + slot_b;
   }
   h->cfg = *cfg;
   h->bufs = *bufs;

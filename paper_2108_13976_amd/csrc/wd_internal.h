@@ -11,6 +11,7 @@ namespace wd {
 constexpr int kWorkgroupSize = 256;     // flat per-agent kernels: four wave64s
 constexpr int kMaxEnvWorkgroupSize = 512;  // env-per-team kernels run 256 or 512 threads,
 constexpr int kBigEnvWorkgroupSize = 1024; // or 1024 for an env too large for the small layout
+constexpr int kBigObsWorkgroupSize = 512;  // observation kernel of the large-env layout
 constexpr int kWaveSize = 64;
 constexpr int kNumActions = 5;
 constexpr int kMaxRegisterK = 8;        // K up to this keeps the candidate list in registers
@@ -76,8 +77,9 @@ struct Params {
   uint16_t* g_slot;
   void* g_best;
   int32_t* g_credits;
-  uint16_t* g_nbr;
-  int64_t g_stride_agents, g_stride_credits, g_stride_nbr;
+  unsigned char* g_image;  // per env: the kept and sorted parts of LDS as the env kernel left them
+  int64_t g_stride_agents, g_stride_credits, g_stride_image;
+  int32_t big_slices;      // workgroups per env in the observation kernel
   // device buffers (borrowed from the caller)
   int32_t *pos_x, *pos_y, *pos_x0, *pos_y0, *live, *action;
   float* reward;

@@ -329,7 +329,7 @@ struct TeamLds {
   uint16_t* nbr;     // [NPAD][K] neighbour indices; overlays the tail of slot/best/credits/counts
   uint32_t* nbr_lo;  // compact form for K = 4, N < 1024: ids 0..2 and two bits of id 3 per agent,
   uint8_t* nbr_hi;   // and the other eight bits of id 3 (same memory as nbr)
-  int32_t* misc;     // [0] tags this step, [1] t after the call, [2] rows to be written, [3] length of retry[], [4..19] scan scratch, [20..21] of the first team: workgroup votes
+  int32_t* misc;     // [0] tags this step, [1] t after the call, [2] rows to be written, [3] length of retry[], [4..19] scan scratch, [20..21] of the first team: workgroup votes, [22..23] bucket geometry for big_obs_kernel
   uint16_t* edges;   // [nbx + 1] first cell of each bucket coordinate; edges[nbx] = G
   SortedList<WIDE> sorted;  // [NPAD + pad] the live agents, grouped by bucket
   uint16_t* slot;    // [NPAD] where agent i sits in `sorted`
@@ -356,7 +356,7 @@ struct TeamLds {
     counts = reinterpret_cast<uint32_t*>(yr + p.off_counts);
     retry = reinterpret_cast<uint16_t*>(yr + p.off_retry);
     if constexpr (BIG) {
-      nbr = p.g_nbr + env * p.g_stride_nbr;
+      nbr = nullptr;  // no neighbour lists: big_obs_kernel writes rows straight from the search
       nbr_lo = nullptr;
       nbr_hi = nullptr;
       slot = p.g_slot + env * p.g_stride_agents;
@@ -541,6 +541,7 @@ __device__ __forceinline__ bool nearest_keys(typename SortedList<WIDE>::Key (&ke
   return true;
 }
 
+constexpr int kMiscBucketMul = 22, kMiscBucketSide = 23;  // misc[] slots that carry the bucket geometry to big_obs_kernel
 constexpr uint32_t kCompactNone = 1023u;  // "no neighbour" in the compact 10-bit form
 
 // One observation row (own features + K neighbour slots) written to `row` (registers, LDS
@@ -874,6 +875,22 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
     L.misc[1] = t_out;
     L.misc[2] = out_act ? 1 : 0;
   }
+  if constexpr (BIG) {
+    // A large env hands its tables (positions, bucket-sorted list, bucket starts and edges) to
+    // big_obs_kernel, which spreads the neighbour search and the rows of this env over many
+    // workgroups: the kept and the sorted part of LDS go to device memory as they are.
+    if (lt == 0) {
+      L.misc[kMiscBucketMul] = int32_t(bk.mul);
+      L.misc[kMiscBucketSide] = bk.nbx;
+    }
+    __syncthreads();
+    if (valid) {
+      uint4* image = reinterpret_cast<uint4*>(p.g_image + int64_t(e) * p.g_stride_image);
+      const uint4* src = reinterpret_cast<const uint4*>(smem);
+      for (int j = tid; j < p.y_base / 16; j += p.wg_size) image[j] = src[j];
+    }
+    return;
+  }
   if constexpr (KX >= 0) {
     constexpr int KT = KX > 0 ? KX : kMaxRegisterK;
     // K nearest, in bucket order (neighbouring lanes search neighbouring cells).  Two passes:
@@ -1176,6 +1193,93 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
   env_body<WIDE, KX, CN, BIG, false>(p, StepOut{p.action, p.reward, p.obs, p.done_log}, mode, probs, g_lo, g_hi, smem, int(threadIdx.x));
 }
 
+// ----------------------------------------------------------------------------------
+// Observations of large envs.  env_kernel<..., BIG> leaves each env's tables in device memory;
+// here workgroup (e, s) reloads them into LDS and serves slice s of env e: the live agents in
+// slots [s, s + 1) * chunk of the bucket-sorted list search their K nearest and write their
+// rows straight from registers, and the agents of index slice s that are out of the game get
+// their rows of zeros.  A row is 20 + 16 K contiguous bytes; the rows of a large-env batch are
+// a few megabytes, so scattered rows cost nothing that matters.
+// ----------------------------------------------------------------------------------
+template <int WIDE, int KT>
+__device__ __forceinline__ void store_row(float* __restrict__ row, const Params& p, const uint32_t* pl, int i, int K,
+                                          float t_frac, const typename SortedList<WIDE>::Key (&keys)[KT], bool lv) {
+  using Key = typename SortedList<WIDE>::Key;
+  const Key idx_mask = (Key(1) << p.idx_bits) - 1;
+  const uint32_t me = pl[i];
+  const int x = pos_x_of(me), y = pos_y_of(me);
+  row[0] = static_cast<float>(x) * p.inv_G;
+  row[1] = static_cast<float>(y) * p.inv_G;
+  row[2] = i < p.N_tag ? 1.0f : 0.0f;
+  row[3] = lv ? 1.0f : 0.0f;
+  row[4] = t_frac;
+#pragma unroll
+  for (int kk = 0; kk < KT; ++kk) {
+    if (kk < K) {
+      const bool none = !lv || key_is_none<WIDE>(keys[kk]);
+      const uint32_t j = none ? uint32_t(i) : uint32_t(keys[kk] & idx_mask);
+      const uint32_t other = pl[j];
+      row[5 + 4 * kk + 0] = static_cast<float>(pos_x_of(other) - x) * p.inv_G;
+      row[5 + 4 * kk + 1] = static_cast<float>(pos_y_of(other) - y) * p.inv_G;
+      row[5 + 4 * kk + 2] = (!none && int(j) < p.N_tag) ? 1.0f : 0.0f;
+      row[5 + 4 * kk + 3] = none ? 0.0f : 1.0f;
+    }
+  }
+}
+
+template <int WIDE, int KX>
+__global__ __launch_bounds__(kBigObsWorkgroupSize) void big_obs_kernel(const Params p) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  using SL = SortedList<WIDE>;
+  using Key = typename SL::Key;
+  constexpr int KT = KX > 0 ? KX : kMaxRegisterK;
+  const int tid = threadIdx.x;
+  const int e = blockIdx.x / p.big_slices, s = blockIdx.x - e * p.big_slices;
+  {
+    const uint4* image = reinterpret_cast<const uint4*>(p.g_image + int64_t(e) * p.g_stride_image);
+    uint4* dst = reinterpret_cast<uint4*>(smem);
+    for (int j = tid; j < p.y_base / 16; j += kBigObsWorkgroupSize) dst[j] = image[j];
+  }
+  __syncthreads();
+  const TeamLds<WIDE, true> L(smem, 0, p, e);
+  if (!L.misc[2]) return;  // this env keeps its rows (a step call on an env that was done)
+  Buckets bk;
+  bk.mul = uint32_t(L.misc[kMiscBucketMul]);
+  bk.nbx = L.misc[kMiscBucketSide];
+  bk.bmin = 0;
+  const int N = p.N, K = KX > 0 ? KX : p.K;
+  const int64_t D = KX > 0 ? 5 + 4 * KX : p.D;
+  float* const env_obs = p.obs + int64_t(e) * N * D;
+  const float t_frac = static_cast<float>(L.misc[1]) * p.inv_T;
+  // live agents, in bucket order
+  const int n_sorted = int(L.starts[p.nb_cap]);
+  const int q_chunk = (n_sorted + p.big_slices - 1) / p.big_slices;
+  const int q_end = min(n_sorted, (s + 1) * q_chunk);
+  for (int q = s * q_chunk + tid; q < q_end; q += kBigObsWorkgroupSize) {
+    const Ent ent = L.sorted.get(q);
+    if (L.sorted.dead(ent)) continue;  // tagged in this step: served below
+    Key keys[KT];
+    if (K > 0) {
+      nearest_keys<WIDE, KT, false>(keys, K, SL::x(ent), SL::y(ent), uint32_t(q), bk, p.idx_bits, L.sorted, L.starts,
+                                    L.edges);
+    } else {
+#pragma unroll
+      for (int kk = 0; kk < KT; ++kk) keys[kk] = key_none<Key>();
+    }
+    store_row<WIDE, KT>(env_obs + int64_t(ent.id) * D, p, L.pl, int(ent.id), K, t_frac, keys, true);
+  }
+  // agents out of the game, in index order
+  const int i_chunk = (N + p.big_slices - 1) / p.big_slices;
+  const int i_end = min(N, (s + 1) * i_chunk);
+  for (int i = s * i_chunk + tid; i < i_end; i += kBigObsWorkgroupSize) {
+    if (!(L.pl[i] & kDeadBit)) continue;
+    Key keys[KT];
+#pragma unroll
+    for (int kk = 0; kk < KT; ++kk) keys[kk] = key_none<Key>();
+    store_row<WIDE, KT>(env_obs + int64_t(i) * D, p, L.pl, i, K, t_frac, keys, false);
+  }
+}
+
 // Workgroup-wide copy of `count` 4-byte words: 16-byte pieces when both ends are aligned.
 template <typename T>
 __device__ __forceinline__ void copy_words(T* __restrict__ dst, const T* __restrict__ src, int64_t count) {
@@ -1249,13 +1353,27 @@ hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uin
   const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
   hipLaunchKernelGGL((env_kernel<WIDE, KX, CN, BIG>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, p,
                      mode, probs, uint32_t(g), uint32_t(g >> 32));
-  return hipGetLastError();
+  hipError_t err = hipGetLastError();
+  if constexpr (BIG) {
+    if (err != hipSuccess) return err;
+    // stream order puts the observation kernel behind the tables it reads
+    hipLaunchKernelGGL((big_obs_kernel<WIDE, KX>), dim3(p.E * p.big_slices), dim3(kBigObsWorkgroupSize),
+                       size_t(p.y_base), stream, p);
+    err = hipGetLastError();
+  }
+  return err;
 }
 
 template <int WIDE, int KX, bool CN, bool BIG>
 hipError_t prepare_env_variant(const Params& p) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&env_kernel<WIDE, KX, CN, BIG>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
+  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&env_kernel<WIDE, KX, CN, BIG>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
+  if constexpr (BIG) {
+    if (err != hipSuccess) return err;
+    err = hipFuncSetAttribute(reinterpret_cast<const void*>(&big_obs_kernel<WIDE, KX>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, p.y_base);
+  }
+  return err;
 }
 
 template <int WIDE, int KX, bool CN>
