@@ -182,6 +182,39 @@ def test_headline_workload_full_size_sampled_envs_and_invariants():
     gpu.close()
 
 
+def test_many_small_envs_workload_full_size_sampled_envs():
+    """tag_20000x100 at full size (2500 workgroups of eight envs, more than fit the chip at
+    once), one wd_iterate launch per iteration as the benchmark runs it, across an episode end
+    (T = 200): sampled envs against the oracle every few iterations."""
+    import paper_2108_13976_amd as wd
+
+    cfg = CONFIGS["tag_20000x100"]
+    kw = cfg.kwargs()
+    E, N = cfg.num_envs, cfg.num_agents
+    ring_len = 4
+    host_ring = np.stack([probs_for_step(cfg.seed, r, E, N) for r in range(ring_len)])
+    gpu = make_gpu(kw)
+    ring = upload(host_ring, gpu.device)
+    gpu.reset(wd.WD_RESET_ALL)
+    rng = np.random.default_rng(23)
+    sample_envs = sorted(int(e) for e in rng.choice(E, size=14, replace=False)) + [0, E - 1]
+    oracles = {e: make_oracle(kw, e, e + 1) for e in sample_envs}
+    for o in oracles.values():
+        o.reset()
+    steps = cfg.episode_length + 12
+    for g in range(steps):
+        gpu.iterate(ring[g % ring_len])
+        for e, o in oracles.items():
+            o.iterate(host_ring[g % ring_len][e:e + 1], g)
+        if g % 35 == 0 or g >= cfg.episode_length - 2:
+            state = gpu.to_host()
+            for e, o in oracles.items():
+                assert_equal_state(state, o, f"iteration {g} env {e}", env_lo=e)
+    check_obs_invariants(cfg, state, FLOAT_TOL)
+    assert (state["t"] <= cfg.episode_length).all()
+    gpu.close()
+
+
 def test_headline_workload_full_size_multi_step_launches():
     """The launch shape the benchmark times: wd_rollout, 25 iterations per launch, outputs in
     place, at 2000 x 1000.  Sampled envs against the oracle after every launch; then one launch
