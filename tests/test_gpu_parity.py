@@ -368,6 +368,10 @@ EDGE = {
     # 5000 agents on a 1000 grid: 64-bit keys
     "large_env_wide_keys": dict(num_envs=2, num_agents=5000, num_taggers=600, grid_size=1000, episode_length=3, obs_k=4,
                                 tag_r2=18),
+    "large_env_k_zero": dict(num_envs=2, num_agents=4100, num_taggers=40, grid_size=200, episode_length=3, obs_k=0),
+    # every runner is tagged in the first step: rows of zeros for all of them, then the reset
+    "large_env_all_tagged_at_once": dict(num_envs=2, num_agents=4500, num_taggers=30, grid_size=60, episode_length=5,
+                                         obs_k=4, tag_r2=10**7),
     "large_env_k_two": dict(num_envs=2, num_agents=6001, num_taggers=3, grid_size=300, episode_length=3, obs_k=2),
     "full_obs_tiny": dict(num_envs=40, num_agents=5, num_taggers=1, grid_size=6, episode_length=12, obs_mode=1),
     "full_obs_fifty": dict(num_envs=9, num_agents=50, num_taggers=10, grid_size=20, episode_length=30, obs_mode=1),
