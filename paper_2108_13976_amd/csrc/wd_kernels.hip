@@ -626,8 +626,20 @@ struct StepOut {
   int32_t* done_log; // optional: done flags before the reset clears them
 };
 
+// The parameters are read through a pointer into the kernel-argument segment that is made
+// opaque to the optimiser at every phase boundary (WD_NEW_PHASE): a phase then loads the
+// fields it uses with scalar loads of its own, instead of holding the ~100 fields of all
+// phases in scalar registers and spilling them into vector-register lanes.  The roll-out loop
+// does this once per iteration (measured: per phase is no gain there).
+typedef const __attribute__((address_space(4))) Params* KernargParams;
+#define WD_NEW_PHASE()                                   \
+  do {                                                   \
+    if constexpr (!LOOPED) asm volatile("" : "+s"(pk)); \
+  } while (0)
+#define p (*(const Params*)pk)
+
 template <int WIDE, int KX, bool CN, bool BIG, bool LOOPED>
-__device__ __forceinline__ void env_body(const Params& p, const StepOut out, const int mode,
+__device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, const int mode,
                                          const float* __restrict__ probs, uint32_t g_lo, uint32_t g_hi,
                                          unsigned char* smem, const int tid) {
   using SL = SortedList<WIDE>;
@@ -676,6 +688,7 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
       if (lt == 0) L.misc[0] = 0;
     }
     __syncthreads();
+    WD_NEW_PHASE();
     // ---- sample (iterate mode), move, stage positions in LDS, count buckets -------------
     for (int k = 0; k < p.gpt; ++k) {
       const int grp = lt + k * ts;
@@ -722,7 +735,9 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
       }
     }
     __syncthreads();
+    WD_NEW_PHASE();
     scan_and_scatter<WIDE>(p, L, step_act, lt, ts, bk);
+    WD_NEW_PHASE();
 
     // ---- tag check, from the tagger's side: runners in range get the smallest
     //      (distance, tagger) key; min is order-independent, so the result is unique ----
@@ -746,6 +761,7 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
       }
     }
     __syncthreads();
+    WD_NEW_PHASE();
     // ---- runners in range leave the game and credit their tagger ---------------------------
     if (step_act) {
       int my_tags = 0;
@@ -777,6 +793,7 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
       if (my_tags) atomicAdd(&L.misc[0], my_tags);
     }
     __syncthreads();
+    WD_NEW_PHASE();
     // ---- rewards, env clock and termination -----------------------------------------------
     if (step_act) {
       for (int k = 0; k < p.gpt; ++k) {
@@ -870,6 +887,7 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
     }
   }
 
+  WD_NEW_PHASE();
   // ---- observations ---------------------------------------------------------------------------
   if (lt == 0) {
     L.misc[1] = t_out;
@@ -946,6 +964,7 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
       all_out = __syncthreads_and((out_act || !valid) ? 1 : 0) != 0;
     }
 
+    WD_NEW_PHASE();
     // Rows, in index order.  A wave builds 64 rows in registers and sends them, 32 at a
     // time, through an LDS transpose (which overlays the sort tables) so that each store
     // instruction writes a contiguous run.
@@ -1184,13 +1203,19 @@ __device__ __forceinline__ void env_body(const Params& p, const StepOut out, con
   }
 }
 
+#undef p
+#undef WD_NEW_PHASE
+
 template <int WIDE, int KX, bool CN, bool BIG>
 __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
     __attribute__((amdgpu_waves_per_eu((WIDE || BIG || KX <= 0) ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
                                                              const float* __restrict__ probs, uint32_t g_lo,
                                                              uint32_t g_hi) {
   extern __shared__ __align__(16) unsigned char smem[];
-  env_body<WIDE, KX, CN, BIG, false>(p, StepOut{p.action, p.reward, p.obs, p.done_log}, mode, probs, g_lo, g_hi, smem, int(threadIdx.x));
+  // p is the first kernel argument: offset 0 of the kernel-argument segment
+  env_body<WIDE, KX, CN, BIG, false>((KernargParams)__builtin_amdgcn_kernarg_segment_ptr(),
+                                     StepOut{p.action, p.reward, p.obs, p.done_log}, mode, probs, g_lo, g_hi, smem,
+                                     int(threadIdx.x));
 }
 
 // ----------------------------------------------------------------------------------
@@ -1331,7 +1356,7 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
       if (roll.obs) out.obs = roll.obs + s * EN * p.D;
     }
     const uint64_t g = a.g0 + uint64_t(s);
-    env_body<WIDE, KX, CN, false, true>(p, out, kModeIterate, a.ring + int64_t(ring_at) * EN * kNumActions, uint32_t(g),
+    env_body<WIDE, KX, CN, false, true>((KernargParams)ak, out, kModeIterate, a.ring + int64_t(ring_at) * EN * kNumActions, uint32_t(g),
                                   uint32_t(g >> 32), smem, tid);
     ring_at = ring_at + 1 == roll.ring_len ? 0 : ring_at + 1;
     __syncthreads();  // this step's state and LDS use are complete before the next step starts
