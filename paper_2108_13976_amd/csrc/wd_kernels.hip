@@ -446,6 +446,14 @@ __device__ __forceinline__ void insert_key(unsigned long long (&keys)[KT], unsig
 // side (or the block covers the grid) no unseen agent can enter the list; otherwise r doubles
 // and only the buckets that the wider block adds, and that are near enough to matter, are scanned.  The agent's own entry is left
 // out by splitting its bucket row at its slot.
+// dx*dx + dy*dy of a packed pair of 16-bit differences, in one instruction (the form without
+// an accumulator register, which the compiler otherwise zeroes for every candidate)
+__device__ __forceinline__ uint32_t squared_length(short2v d) {
+  uint32_t r;
+  asm("v_dot2_i32_i16 %0, %1, %1, 0" : "=v"(r) : "v"(d));
+  return r;
+}
+
 template <int KT>
 __device__ __forceinline__ void scan_range(unsigned long long (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y,
                                            int ib, const SortedList<kKeys64>& sorted) {
@@ -463,10 +471,14 @@ template <int KT>
 __device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y, int ib,
                                            const SortedList<kKeys31>& sorted) {
   const short2v me = __builtin_bit_cast(short2v, uint32_t(x) | (uint32_t(y) << 16));
-  for (uint32_t q = qb; q < qe; ++q) {
-    const short2v d = __builtin_bit_cast(short2v, sorted.pos[q]) - me;       // (dx, dy), one packed subtract
-    const uint32_t d2 = uint32_t(__builtin_amdgcn_sdot2(d, d, 0, false));    // dx*dx + dy*dy
-    insert_key<KT>(keys, (d2 << ib) | uint32_t(sorted.id[q]));
+  // one running pointer per array, the loop ends on the first: three instructions of loop
+  // overhead per candidate
+  const uint32_t* pos = sorted.pos + qb;
+  const uint32_t* const pos_end = sorted.pos + qe;
+  const uint16_t* id = sorted.id + qb;
+  for (; pos < pos_end; ++pos, ++id) {
+    const short2v d = __builtin_bit_cast(short2v, *pos) - me;  // (dx, dy), one packed subtract
+    insert_key<KT>(keys, (squared_length(d) << ib) | uint32_t(*id));
   }
 }
 
@@ -476,7 +488,7 @@ __device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, ui
   const short2v me = __builtin_bit_cast(short2v, uint32_t(x) | (uint32_t(y) << 16));
   for (uint32_t q = qb; q < qe; ++q) {
     const short2v d = __builtin_bit_cast(short2v, sorted.pos[q]) - me;
-    const uint32_t d2 = uint32_t(__builtin_amdgcn_sdot2(d, d, 0, false));
+    const uint32_t d2 = squared_length(d);
     const uint32_t idv = sorted.id[q];
     // a marked entry becomes the empty key (all ones): sign-extend the flag bit over the key
     const uint32_t dead_mask = uint32_t(int32_t(idv << 16) >> 31);
