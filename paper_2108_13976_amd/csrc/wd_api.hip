@@ -85,6 +85,16 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   p->big = big ? 1 : 0;
   int ts_log2 = 3;
   while ((1 << ts_log2) < p->NG && ts_log2 < 8) ++ts_log2;
+  // A batch that cannot fill the chip is bound by the latency of one workgroup's chain of
+  // phases, not by throughput: give each env more lanes (fewer search rounds per lane) and each
+  // workgroup fewer envs (fewer row chunks per wave) while that still shortens the chain.
+  while (!big && ts_log2 < 8) {
+    const int ts_now = 1 << ts_log2, tpw_now = 256 / ts_now;
+    const int64_t wgs = (int64_t(c.num_envs) + tpw_now - 1) / tpw_now;
+    const int64_t rows_per_wg = int64_t(std::min(tpw_now, c.num_envs)) * N;
+    if (wgs >= 512 || (rows_per_wg <= 64 && N <= ts_now)) break;
+    ++ts_log2;
+  }
   p->wg_size = 256;
   if (big) {  // one env per 1024-thread workgroup
     ts_log2 = 10;
