@@ -151,8 +151,10 @@ typedef struct wd_rollout_buffers {
  * 3-6 repeated).  probs_ring: device [ring_len][E][N][5]; iteration s samples from entry
  * (g + s) mod ring_len.  Results equal k calls of wd_iterate with those probabilities:
  * the in-place buffers end in the state after the last iteration, `out` (may be NULL)
- * receives every iteration's outputs, g advances by k.  WD_E_UNSUPPORTED for
- * configurations that use the large-env layout, full observations or K > 8. */
+ * receives every iteration's outputs, g advances by k.  Configurations that use the
+ * large-env layout, full observations or K > 8 have no multi-step kernel: for them the
+ * call enqueues one launch per iteration (and device-to-device copies of the last slice),
+ * with the same results.  On WD_E_HIP part of the iterations may have been enqueued. */
 int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const wd_rollout_buffers* out);
 
 /* The global step counter g used as the RNG step index (checkpoint / resume). */

@@ -390,7 +390,37 @@ int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const
       if (reinterpret_cast<uintptr_t>(ptr) & 15u) return WD_E_ALIGN;
   }
   if (!h->started) return WD_E_STATE;
-  if (!wd::rollout_available(h->params)) return WD_E_UNSUPPORTED;
+  if (!wd::rollout_available(h->params)) {
+    // Configurations without a multi-step kernel (large-env layout, full observations,
+    // K > 8): the same results from one launch of the iteration kernels per iteration,
+    // outputs redirected to the slices, the last slice copied from the in-place buffers.
+    const int64_t EN = int64_t(h->cfg.num_envs) * h->cfg.num_agents, D = h->params.D;
+    for (int s = 0; s < k; ++s) {
+      wd::Params q = h->params;
+      if (out && s + 1 < k) {
+        if (out->action) q.action = out->action + int64_t(s) * EN;
+        if (out->reward) q.reward = out->reward + int64_t(s) * EN;
+        if (out->obs) q.obs = out->obs + int64_t(s) * EN * D;
+      }
+      q.done_log = (out && out->done) ? out->done + int64_t(s) * h->cfg.num_envs : nullptr;
+      const float* probs = probs_ring + int64_t((h->g + uint64_t(s)) % uint64_t(ring_len)) * EN * wd::kNumActions;
+      const hipError_t err = wd::launch_env_kernel(q, wd::kModeIterate, probs, h->g + uint64_t(s), h->stream);
+      if (err != hipSuccess) return hip_failed(h, err, "iteration kernel of a roll-out");
+    }
+    if (out) {
+      const int64_t last = int64_t(k - 1) * EN;
+      hipError_t err = hipSuccess;
+      if (out->action && err == hipSuccess)
+        err = hipMemcpyAsync(out->action + last, h->bufs.action, size_t(EN) * 4, hipMemcpyDeviceToDevice, h->stream);
+      if (out->reward && err == hipSuccess)
+        err = hipMemcpyAsync(out->reward + last, h->bufs.reward, size_t(EN) * 4, hipMemcpyDeviceToDevice, h->stream);
+      if (out->obs && err == hipSuccess)
+        err = hipMemcpyAsync(out->obs + last * D, h->bufs.obs, size_t(EN * D) * 4, hipMemcpyDeviceToDevice, h->stream);
+      if (err != hipSuccess) return hip_failed(h, err, "copy of the last roll-out slice");
+    }
+    h->g += uint64_t(k);
+    return WD_OK;
+  }
   wd::Roll roll;
   std::memset(&roll, 0, sizeof(roll));
   roll.steps = k;

@@ -320,8 +320,8 @@ __device__ __forceinline__ int bucket_of(int x, int y, const Buckets bk) {
   return bucket_coord(y, bk) * bk.nbx + bucket_coord(x, bk);
 }
 
-// Views of one team's tables: in LDS, except that a large env (BIG) keeps slots, tag keys,
-// credits and neighbour lists in device memory.
+// Views of one team's tables: in LDS, except that a large env (BIG) keeps slots, tag keys and
+// credits in device memory (and has no neighbour lists: its rows come from big_obs_kernel).
 template <int WIDE, bool BIG>
 struct TeamLds {
   using Key = typename SortedList<WIDE>::Key;

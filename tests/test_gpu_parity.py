@@ -304,6 +304,38 @@ def test_multi_step_rollout_equals_single_iterations(name, k, rounds):
     a.close(), b.close()
 
 
+@pytest.mark.parametrize("name,k", [("large_env_k_two", 3), ("full_obs_fifty", 4), ("k_all_others", 5)])
+def test_multi_step_rollout_without_a_multi_step_kernel(name, k):
+    """Large-env layout, full observations, K > 8: wd_rollout runs one launch per iteration;
+    its slices and final state against k calls of wd_iterate."""
+    import paper_2108_13976_amd as wd
+
+    kw = dict(EDGE[name], seed=77)
+    E, N = kw["num_envs"], kw["num_agents"]
+    ring_len = 3
+    host_ring = np.stack([probs_for_step(77, r, E, N) for r in range(ring_len)])
+    a, b = make_gpu(kw), make_gpu(kw)
+    ring = upload(host_ring, a.device)
+    a.reset(wd.WD_RESET_ALL), b.reset(wd.WD_RESET_ALL)
+    g = 0
+    for _ in range(2):
+        rec = a.rollout(ring, k)
+        for s in range(k):
+            b.sample(ring[(g + s) % ring_len]), b.step()
+            sb = b.to_host()
+            assert np.array_equal(rec["action"][s].cpu().numpy(), sb["action"])
+            assert np.array_equal(rec["done"][s].cpu().numpy(), sb["done"])
+            assert rec["reward"][s].cpu().numpy().tobytes() == sb["reward"].tobytes()
+            b.reset(wd.WD_RESET_DONE)
+            assert rec["obs"][s].cpu().numpy().tobytes() == b.to_host()["obs"].tobytes()
+        g += k
+        assert a.global_step == g
+        sa, sb = a.to_host(), b.to_host()
+        for n in sa:
+            assert sa[n].tobytes() == sb[n].tobytes(), n
+    a.close(), b.close()
+
+
 def test_two_runs_are_byte_identical():
     import paper_2108_13976_amd as wd
 
