@@ -650,10 +650,20 @@ typedef const __attribute__((address_space(4))) Params* KernargParams;
   } while (0)
 #define p (*(const Params*)pk)
 
+// What the roll-out loop keeps on chip between the iterations of one launch: the env clock and
+// the live-runner count in registers, positions and live flags in the LDS position table.
+// Only the last iteration of a launch writes the in-place state arrays (all of them); nobody
+// can read the others' state before the launch ends.
+struct LoopState {
+  int t, nlr;
+  bool resident;  // false in the first iteration of a launch: state comes from device memory
+  bool last;      // the in-place state arrays are written in this iteration
+};
+
 template <int WIDE, int KX, bool CN, bool BIG, bool LOOPED>
 __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, const int mode,
                                          const float* __restrict__ probs, uint32_t g_lo, uint32_t g_hi,
-                                         unsigned char* smem, const int tid) {
+                                         unsigned char* smem, const int tid, LoopState& ls) {
   using SL = SortedList<WIDE>;
   using Key = typename SL::Key;
   const int ts = 1 << p.ts_log2;
@@ -669,12 +679,18 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
   const TeamLds<WIDE, BIG> L(smem, team, p, e);
   const Key idx_mask = (Key(1) << p.idx_bits) - 1;
 
+  const bool from_chip = LOOPED && ls.resident;
+  const bool write_state = !LOOPED || ls.last;
   int done_in = 0, t_in = 0, nlr_in = 0;
-  if (valid) {
+  if (from_chip) {  // an env that was done has been reset by the iteration before
+    t_in = ls.t;
+    nlr_in = ls.nlr;
+  } else if (valid) {
     done_in = p.done[e];
     t_in = p.t[e];
     nlr_in = p.n_live_runners[e];
   }
+  int nlr_out = nlr_in;
   const bool stepping = (mode == kModeStep || mode == kModeIterate);
   const bool step_act = stepping && valid && !done_in;
   bool out_act = false;  // this team's env gets new observation rows
@@ -717,10 +733,21 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
         }
         if (step_act) {
           int x[4], y[4], lv[4];
-          load4(p.pos_x, a0, n, vec, x);
-          load4(p.pos_y, a0, n, vec, y);
-          load4(p.live, a0, n, vec, lv);
-          bool moved = false;
+          if (from_chip) {
+            const uint4 q4 = *reinterpret_cast<const uint4*>(L.pl + i0);
+            const uint32_t q[4] = {q4.x, q4.y, q4.z, q4.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              x[j] = pos_x_of(q[j]);
+              y[j] = pos_y_of(q[j]);
+              lv[j] = (q[j] & kDeadBit) ? 0 : 1;
+            }
+          } else {
+            load4(p.pos_x, a0, n, vec, x);
+            load4(p.pos_y, a0, n, vec, y);
+            load4(p.live, a0, n, vec, lv);
+          }
+          bool moved = LOOPED;  // the last iteration of a roll-out writes every group
           uint32_t packed[4];
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
@@ -738,7 +765,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
             if (is_live) atomicAdd(&L.counts[bucket_of(nx, ny, bk)], 1u);
             L.best[i0 + j] = key_none<Key>();
           }
-          if (moved) {
+          if (moved && write_state) {
             store4(p.pos_x, a0, n, vec, x);
             store4(p.pos_y, a0, n, vec, y);
           }
@@ -799,7 +826,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
             }
             lv[j] = (me & kDeadBit) ? 0 : 1;
           }
-          if (any) store4(p.live, abase + i0, min(4, N - i0), vec, lv);
+          if ((any || LOOPED) && write_state) store4(p.live, abase + i0, min(4, N - i0), vec, lv);
         }
       }
       if (my_tags) atomicAdd(&L.misc[0], my_tags);
@@ -826,9 +853,10 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
       }
       const int tags = L.misc[0];
       const int nlr = nlr_in - tags;
+      nlr_out = nlr;
       t_out = t_in + 1;
       done_now = (nlr == 0) || (t_out >= p.T);
-      if (lt == 0) {
+      if (lt == 0 && write_state) {
         p.t[e] = t_out;
         p.n_live_runners[e] = nlr;
         p.tags_step[e] = tags;
@@ -879,14 +907,17 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
               ones[j] = 1;
               if (j < n) atomicAdd(&L.counts[bucket_of(x[j], y[j], bk)], 1u);
             }
-            store4(p.pos_x, a0, n, vec, x);
-            store4(p.pos_y, a0, n, vec, y);
-            store4(p.live, a0, n, vec, ones);
+            if (write_state) {
+              store4(p.pos_x, a0, n, vec, x);
+              store4(p.pos_y, a0, n, vec, y);
+              store4(p.live, a0, n, vec, ones);
+            }
             *reinterpret_cast<uint4*>(L.pl + i0) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
           }
         }
         t_out = 0;
-        if (lt == 0) {
+        nlr_out = N - N_tag;
+        if (lt == 0 && write_state) {
           p.t[e] = 0;
           p.n_live_runners[e] = N - N_tag;
           p.tags_step[e] = 0;
@@ -899,6 +930,11 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
     }
   }
 
+  if constexpr (LOOPED) {
+    ls.t = t_out;
+    ls.nlr = nlr_out;
+    ls.resident = true;
+  }
   WD_NEW_PHASE();
   // ---- observations ---------------------------------------------------------------------------
   if (lt == 0) {
@@ -1224,10 +1260,11 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
                                                              const float* __restrict__ probs, uint32_t g_lo,
                                                              uint32_t g_hi) {
   extern __shared__ __align__(16) unsigned char smem[];
+  LoopState ls = {0, 0, false, true};
   // p is the first kernel argument: offset 0 of the kernel-argument segment
   env_body<WIDE, KX, CN, BIG, false>((KernargParams)__builtin_amdgcn_kernarg_segment_ptr(),
                                      StepOut{p.action, p.reward, p.obs, p.done_log}, mode, probs, g_lo, g_hi, smem,
-                                     int(threadIdx.x));
+                                     int(threadIdx.x), ls);
 }
 
 // ----------------------------------------------------------------------------------
@@ -1354,7 +1391,9 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
   const int steps = args.roll.steps;
   int ring_at = args.roll.ring_pos;
   int tid = threadIdx.x;
+  LoopState ls = {0, 0, false, false};
   for (int s = 0; s < steps; ++s) {
+    ls.last = s + 1 == steps;
     asm volatile("" : "+s"(ak));
     asm volatile("" : "+v"(tid));  // likewise: what a thread derives from its id is recomputed per step, not kept
     const RollArgs& a = *(const RollArgs*)ak;
@@ -1369,7 +1408,7 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
     }
     const uint64_t g = a.g0 + uint64_t(s);
     env_body<WIDE, KX, CN, false, true>((KernargParams)ak, out, kModeIterate, a.ring + int64_t(ring_at) * EN * kNumActions, uint32_t(g),
-                                  uint32_t(g >> 32), smem, tid);
+                                  uint32_t(g >> 32), smem, tid, ls);
     ring_at = ring_at + 1 == roll.ring_len ? 0 : ring_at + 1;
     __syncthreads();  // this step's state and LDS use are complete before the next step starts
   }
