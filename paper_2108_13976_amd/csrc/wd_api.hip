@@ -104,7 +104,7 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   p->ts_log2 = ts_log2;
   p->teams_per_wg = p->wg_size / ts;
   p->gpt = (p->NG + ts - 1) / ts;
-  p->NPAD = (4 * p->NG + 63) / 64 * 64;
+  p->NPAD = (4 * p->NG + 7) / 8 * 8;
   p->vec4 = (N % 4 == 0) ? 1 : 0;
   uint32_t nb_cap = pow2_ceil(uint32_t(N)) / 2;
   if (nb_cap > 4096u) nb_cap = 4096u;

@@ -46,7 +46,7 @@ struct Params {
   // workgroup holds teams_per_wg teams of (1 << ts_log2) threads; a team owns one env;
   // thread lt of a team owns groups lt, lt + ts, ... (gpt of them).
   int32_t NG;            // groups per env = ceil(N / 4)
-  int32_t NPAD;          // 4 * NG rounded up to 64: per-agent LDS arrays are padded to this
+  int32_t NPAD;          // 4 * NG rounded up to 8: per-agent LDS arrays are padded to this
   int32_t wg_size;       // 256, or 512 when one env fills the workgroup (more lanes per env)
   int32_t stage_rows_log2;  // rows a wave transposes through LDS per flush: 32 or 16
   int32_t ts_log2, teams_per_wg, gpt;
