@@ -1041,10 +1041,14 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
           if (have) write_row<KX, CN>(row, p, Lr, i, KX, t_frac);
         }
         if constexpr (KX > 0 && KX <= 4) {
-          if (vec_ok && srl == 5 && R0 + kWaveSize <= rows_total) {
-            // a full chunk: two flushes of 32 rows = 168 16-byte pieces each, no bounds to test
-            constexpr int DD = 5 + 4 * KX;
+          constexpr int DD = 5 + 4 * KX;
+          // Two flushes of 32 rows = 168 16-byte pieces each.  A whole chunk has no bounds to
+          // test; the last chunk of the workgroup stores only the pieces that exist (its rows
+          // end on a 16-byte boundary when the row count times DD is a multiple of four).
+          const auto flush_chunk = [&](auto whole_chunk) {
+            constexpr bool kWhole = decltype(whole_chunk)::value;
             constexpr int kPieces = 32 * DD / 4;
+            const int limit = kWhole ? 0 : (rows_total - R0) * DD / 4 - lane;  // pieces of this chunk from this lane on
             float4* out4 = reinterpret_cast<float4*>(obs_wg + int64_t(R0) * DD) + lane;
             const float4* st4 = reinterpret_cast<const float4*>(stage) + lane;
             float* dst = stage + (lane & 31) * DD;
@@ -1058,12 +1062,22 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
               const float4 a = st4[0], b = st4[kWaveSize];
               float4 c = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
               if (lane + 2 * kWaveSize < kPieces) c = st4[2 * kWaveSize];
-              out4[h * kPieces] = a;
-              out4[h * kPieces + kWaveSize] = b;
-              if (lane + 2 * kWaveSize < kPieces) out4[h * kPieces + 2 * kWaveSize] = c;
+              if (kWhole || h * kPieces < limit) out4[h * kPieces] = a;
+              if (kWhole || h * kPieces + kWaveSize < limit) out4[h * kPieces + kWaveSize] = b;
+              if (lane + 2 * kWaveSize < kPieces && (kWhole || h * kPieces + 2 * kWaveSize < limit))
+                out4[h * kPieces + 2 * kWaveSize] = c;
               wave_sync_lds();
             }
-            continue;
+          };
+          if (vec_ok && srl == 5) {
+            if (R0 + kWaveSize <= rows_total) {
+              flush_chunk(std::true_type{});
+              continue;
+            }
+            if (((rows_total * DD) & 3) == 0) {
+              flush_chunk(std::false_type{});
+              continue;
+            }
           }
         }
         for (int h = 0; h < flushes; ++h) {
