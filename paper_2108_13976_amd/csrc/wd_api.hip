@@ -124,6 +124,10 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   p->lambda_c = 47.0f;
   p->lambda_min = 1.5f;
   p->lambda_max = 5.0f;
+  if (ts >= N) {  // a lane per agent: one search round, so fewer, fuller buckets shorten the chain
+    p->lambda_c = 70.0f;
+    p->lambda_max = 8.0f;
+  }
   p->div_N = wd::make_fastdiv(uint32_t(N));
   p->div_NG = wd::make_fastdiv(uint32_t(p->NG));
 
