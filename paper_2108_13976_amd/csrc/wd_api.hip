@@ -158,7 +158,7 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   if (flagged32) narrow = true;  // the same table layout as the 31-bit form
   p->wide = flagged32 ? 2 : (narrow ? 0 : 1);
   const int key_bytes = narrow ? 4 : 8;
-  const bool register_path = c.obs_mode == WD_OBS_PARTIAL && p->K <= wd::kMaxRegisterK;
+  const bool register_path = c.obs_mode == WD_OBS_PARTIAL && p->K <= wd::kMaxRegisterK2;
 
   int64_t off = 0;
   auto take = [&off](int64_t bytes) {

@@ -14,7 +14,10 @@ constexpr int kBigEnvWorkgroupSize = 1024; // or 1024 for an env too large for t
 constexpr int kBigObsWorkgroupSize = 512;  // observation kernel of the large-env layout
 constexpr int kWaveSize = 64;
 constexpr int kNumActions = 5;
-constexpr int kMaxRegisterK = 8;        // K up to this keeps the candidate list in registers
+constexpr int kMaxRegisterK = 8;        // K up to this keeps the candidate list in 8 registers,
+constexpr int kMaxRegisterK2 = 16;      // up to this in 16 (a variant of its own)
+// List size of a kernel variant KX (KX > 0: exactly K; 0: K <= 8; -2: K <= 16).
+constexpr int register_list_size(int kx) { return kx > 0 ? kx : (kx == -2 ? kMaxRegisterK2 : kMaxRegisterK); }
 constexpr uint32_t kStreamAction = 0;   // random streams (low byte of the fourth counter word)
 constexpr uint32_t kStreamInit = 1;
 

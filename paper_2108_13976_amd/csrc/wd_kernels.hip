@@ -53,8 +53,8 @@ __global__ __launch_bounds__(kWorkgroupSize) void init_start_positions_kernel(co
 
 // ----------------------------------------------------------------------------------
 // The env-per-team kernel: step, reset, or a whole iteration (sample + step + reset).
-// KX > 0: K == KX known at compile time.  KX == 0: K <= 8 at run time.  Both keep the
-// neighbour list in registers and send rows through the LDS transpose.  KX < 0: any K,
+// KX > 0: K == KX known at compile time.  KX == 0: K <= 8 at run time, KX == -2: K <= 16.  They keep
+// the neighbour list in registers and send rows through the LDS transpose.  KX == -1: any K,
 // by repeated selection, rows written directly (slow path).
 // ----------------------------------------------------------------------------------
 // Where one iteration's outputs go: the in-place buffers, or a slice of a roll-out's arrays.
@@ -384,8 +384,8 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
     }
     return;
   }
-  if constexpr (KX >= 0) {
-    constexpr int KT = KX > 0 ? KX : kMaxRegisterK;
+  if constexpr (KX != -1) {
+    constexpr int KT = register_list_size(KX);
     // K nearest, in bucket order (neighbouring lanes search neighbouring cells).  Two passes:
     // every live agent tries the 3x3 buckets around it; the few that this does not settle
     // (sparse spots, grid borders) queue up and are searched with widening rings afterwards,
@@ -721,7 +721,7 @@ __global__ __launch_bounds__(kBigObsWorkgroupSize) void big_obs_kernel(const Par
   extern __shared__ __align__(16) unsigned char smem[];
   using SL = SortedList<WIDE>;
   using Key = typename SL::Key;
-  constexpr int KT = KX > 0 ? KX : kMaxRegisterK;
+  constexpr int KT = register_list_size(KX);
   const int tid = threadIdx.x;
   const int e = blockIdx.x / p.big_slices, s = blockIdx.x - e * p.big_slices;
   {
@@ -882,11 +882,12 @@ hipError_t launch_rollout_variant(const Params& p, const Roll& roll, const float
   return hipGetLastError();
 }
 
-// Which compiled variant serves K: 4 (the benchmark shape), 0 (K <= 8 at run time), -1 (any K).
+// Which compiled variant serves K: 4 (the benchmark shape), 0 (K <= 8 at run time), -2 (K <= 16), -1 (any K).
 int variant_of(const Params& p) {
   if (p.obs_mode == 1) return -1;
   if (p.K == 4) return 4;
   if (p.K <= kMaxRegisterK) return 0;
+  if (p.K <= kMaxRegisterK2) return -2;
   return -1;
 }
 
@@ -898,23 +899,28 @@ int variant_of(const Params& p) {
     if (p.big) {                                                                           \
       if (p.wide == 2) {                                                                   \
         if (kx == 4) return fn<2, 4, false, true>(p, ##__VA_ARGS__);                       \
+        if (kx == -2) return fn<2, -2, false, true>(p, ##__VA_ARGS__);                     \
         return fn<2, 0, false, true>(p, ##__VA_ARGS__);                                    \
       }                                                                                    \
       if (!p.wide) {                                                                       \
         if (kx == 4) return fn<false, 4, false, true>(p, ##__VA_ARGS__);                   \
+        if (kx == -2) return fn<false, -2, false, true>(p, ##__VA_ARGS__);                 \
         return fn<false, 0, false, true>(p, ##__VA_ARGS__);                                \
       }                                                                                    \
       if (kx == 4) return fn<true, 4, false, true>(p, ##__VA_ARGS__);                      \
+      if (kx == -2) return fn<true, -2, false, true>(p, ##__VA_ARGS__);                    \
       return fn<true, 0, false, true>(p, ##__VA_ARGS__);                                   \
     }                                                                                      \
     if (!p.wide) {                                                                         \
       if (kx == 4 && p.compact_nbr) return fn<false, 4, true, false>(p, ##__VA_ARGS__);    \
       if (kx == 4) return fn<false, 4, false, false>(p, ##__VA_ARGS__);                    \
       if (kx == 0) return fn<false, 0, false, false>(p, ##__VA_ARGS__);                    \
+      if (kx == -2) return fn<false, -2, false, false>(p, ##__VA_ARGS__);                  \
       return fn<false, -1, false, false>(p, ##__VA_ARGS__);                                \
     }                                                                                      \
     if (kx == 4) return fn<true, 4, false, false>(p, ##__VA_ARGS__);                       \
     if (kx == 0) return fn<true, 0, false, false>(p, ##__VA_ARGS__);                       \
+    if (kx == -2) return fn<true, -2, false, false>(p, ##__VA_ARGS__);                     \
     return fn<true, -1, false, false>(p, ##__VA_ARGS__);                                   \
   } while (0)
 
@@ -937,7 +943,7 @@ hipError_t launch_rollout(const Params& p, const Roll& roll, const float* ring, 
   return launch_rollout_variant<true, 0, false>(p, roll, ring, g, stream);
 }
 
-bool env_kernel_available(const Params& p) { return !(p.big && (p.obs_mode == 1 || p.K > kMaxRegisterK)); }
+bool env_kernel_available(const Params& p) { return !(p.big && (p.obs_mode == 1 || p.K > kMaxRegisterK2)); }
 
 hipError_t launch_sample(const Params& p, const float* probs, uint64_t g, hipStream_t stream) {
   const int64_t total = int64_t(p.E) * p.NG;

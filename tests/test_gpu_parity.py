@@ -383,6 +383,11 @@ EDGE = {
     "k_zero": dict(num_envs=33, num_agents=12, num_taggers=3, grid_size=7, episode_length=15, obs_k=0),
     "k_three": dict(num_envs=9, num_agents=40, num_taggers=5, grid_size=13, episode_length=30, obs_k=3),
     "k_eight": dict(num_envs=9, num_agents=40, num_taggers=5, grid_size=11, episode_length=30, obs_k=8),
+    "k_twelve": dict(num_envs=7, num_agents=60, num_taggers=6, grid_size=14, episode_length=25, obs_k=12),
+    "k_sixteen_wide_keys": dict(num_envs=3, num_agents=200, num_taggers=15, grid_size=9000, episode_length=8, obs_k=16,
+                                tag_r2=10**7),
+    "k_seventeen": dict(num_envs=4, num_agents=30, num_taggers=4, grid_size=10, episode_length=15, obs_k=17),
+    "large_env_k_ten": dict(num_envs=2, num_agents=4200, num_taggers=50, grid_size=150, episode_length=3, obs_k=10),
     "k_all_others": dict(num_envs=5, num_agents=14, num_taggers=4, grid_size=9, episode_length=25, obs_k=13),
     "one_cell_grid": dict(num_envs=4, num_agents=6, num_taggers=2, grid_size=1, episode_length=5, obs_k=4),
     "tagging_disabled": dict(num_envs=6, num_agents=30, num_taggers=6, grid_size=6, episode_length=12, obs_k=4, tag_r2=-1),
