@@ -336,6 +336,40 @@ def test_multi_step_rollout_without_a_multi_step_kernel(name, k):
     a.close(), b.close()
 
 
+def test_multi_step_rollout_entered_with_envs_that_are_done():
+    """wd_rollout called on a state in which some envs are done and not yet reset (the caller
+    stepped without resetting): the first iteration must not step them, and resets them."""
+    import paper_2108_13976_amd as wd
+
+    kw = dict(num_envs=37, num_agents=12, num_taggers=3, grid_size=5, episode_length=6, obs_k=4, seed=5, tag_r2=2)
+    E, N = kw["num_envs"], kw["num_agents"]
+    ring_len = 4
+    host_ring = np.stack([probs_for_step(5, r, E, N) for r in range(ring_len)])
+    a, b = make_gpu(kw), make_gpu(kw)
+    orc = make_oracle(kw)
+    ring = upload(host_ring, a.device)
+    a.reset(wd.WD_RESET_ALL), b.reset(wd.WD_RESET_ALL), orc.reset()
+    g = 0
+    for _ in range(5):  # no resets: envs finish one after another (all tagged) and stay done
+        for env in (a, b):
+            env.sample(ring[g % ring_len]), env.step()
+        orc.sample(host_ring[g % ring_len], g), orc.step()
+        g += 1
+    done = a.to_host()["done"]
+    assert 0 < done.sum() < E, "the case needs a mix of done and running envs"
+    k = 7
+    rec = a.rollout(ring, k)
+    for s in range(k):
+        b.iterate(ring[(g + s) % ring_len])
+        orc.iterate(host_ring[(g + s) % ring_len], g + s)
+        assert rec["obs"][s].cpu().numpy().tobytes() == b.to_host()["obs"].tobytes(), s
+    sa, sb = a.to_host(), b.to_host()
+    for n in sa:
+        assert sa[n].tobytes() == sb[n].tobytes(), n
+    assert_equal_state(sa, orc, "after the roll-out")
+    a.close(), b.close()
+
+
 def test_two_runs_are_byte_identical():
     import paper_2108_13976_amd as wd
 
