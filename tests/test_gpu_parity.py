@@ -370,6 +370,42 @@ def test_multi_step_rollout_entered_with_envs_that_are_done():
     a.close(), b.close()
 
 
+def test_caller_supplied_stream_and_env_slices():
+    """Two env slices of one batch, each on a stream of its own (default priority), against the
+    whole batch on the default stream: the library enqueues on the stream it was given and the
+    random streams are keyed by global env id."""
+    import torch
+    import paper_2108_13976_amd as wd
+
+    cfg = CONFIGS["tag_100x50"]
+    kw = cfg.kwargs()
+    E, N = cfg.num_envs, cfg.num_agents
+    whole = make_gpu(kw)
+    whole.reset(wd.WD_RESET_ALL)
+    cuts = [(0, 37), (37, E)]
+    parts = []
+    for lo, hi in cuts:
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            env = wd.TagEnvs(stream=st, **dict(kw, num_envs=hi - lo, env_offset=lo))
+        env.reset(wd.WD_RESET_ALL)
+        parts.append(env)
+    for g in range(25):
+        probs = upload(probs_for_step(cfg.seed, g, E, N), whole.device)
+        torch.cuda.synchronize()
+        whole.iterate(probs)
+        for env, (lo, hi) in zip(parts, cuts):
+            env.iterate(probs[lo:hi])
+        torch.cuda.synchronize()  # probs is released below: no stream may still be reading it
+    ref = whole.to_host()
+    for env, (lo, hi) in zip(parts, cuts):
+        got = env.to_host()
+        for n in ref:
+            assert got[n].tobytes() == ref[n][lo:hi].tobytes(), (n, lo)
+        env.close()
+    whole.close()
+
+
 def test_two_runs_are_byte_identical():
     import paper_2108_13976_amd as wd
 
