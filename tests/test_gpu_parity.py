@@ -406,6 +406,30 @@ def test_caller_supplied_stream_and_env_slices():
     whole.close()
 
 
+def random_configuration(seed):
+    """A small random configuration: every size, radius, K, observation mode and reward constant
+    drawn from a seeded generator, the shapes skewed towards the layout boundaries."""
+    rng = np.random.default_rng(1000 + seed)
+    N = int(rng.choice([2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 33, 63, 64, 65, 100, 127, 129, 200, 257, 300, 511, 520]))
+    G = int(rng.choice([1, 2, 3, 5, 8, 13, 21, 40, 64, 100, 300, 1000, 5000, 32767]))
+    kw = dict(num_envs=int(rng.integers(1, 70)), num_agents=N, num_taggers=int(rng.integers(1, N)), grid_size=G,
+              episode_length=int(rng.integers(1, 14)), seed=int(rng.integers(0, 2**31)),
+              tag_r2=int(rng.choice([-1, 0, 1, 2, 4, 9, 50, 2 * G * G])),
+              tag_reward=float(rng.choice([1.0, 0.5, 2.25])), tag_penalty=float(rng.choice([-1.0, -0.125, 0.0])))
+    if rng.random() < 0.2 and N <= 129:
+        kw["obs_mode"] = 1
+    else:
+        kw["obs_k"] = int(min(N - 1, rng.choice([0, 1, 2, 3, 4, 4, 4, 5, 8, 9, 16, 17, 40])))
+    return kw
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_configuration(seed):
+    kw = random_configuration(seed)
+    steps = 2 * kw["episode_length"] + 3
+    lockstep(kw, steps, kw["seed"] % 1000, fused=bool(seed & 1))
+
+
 def test_two_runs_are_byte_identical():
     import paper_2108_13976_amd as wd
 
