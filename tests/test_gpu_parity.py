@@ -430,6 +430,36 @@ def test_random_configuration(seed):
     lockstep(kw, steps, kw["seed"] % 1000, fused=bool(seed & 1))
 
 
+@pytest.mark.parametrize("seed", range(100, 116))
+def test_random_configuration_multi_step(seed):
+    """wd_rollout on a random configuration: every recorded slice and the final state against one
+    wd_iterate per iteration, the final state also against the oracle."""
+    import paper_2108_13976_amd as wd
+
+    kw = random_configuration(seed)
+    E, N = kw["num_envs"], kw["num_agents"]
+    ring_len, k = 3, 2 * kw["episode_length"] + 2
+    host_ring = np.stack([probs_for_step(kw["seed"] % 1000, r, E, N) for r in range(ring_len)])
+    a, b, orc = make_gpu(kw), make_gpu(kw), make_oracle(kw)
+    ring = upload(host_ring, a.device)
+    a.reset(wd.WD_RESET_ALL), b.reset(wd.WD_RESET_ALL), orc.reset()
+    rec = {n: v.cpu().numpy() for n, v in a.rollout(ring, k).items()}
+    for s in range(k):
+        b.sample(ring[s % ring_len]), b.step()
+        sb = b.to_host()
+        assert np.array_equal(rec["action"][s], sb["action"]), s
+        assert np.array_equal(rec["done"][s], sb["done"]), s
+        assert rec["reward"][s].tobytes() == sb["reward"].tobytes(), s
+        b.reset(wd.WD_RESET_DONE)
+        assert rec["obs"][s].tobytes() == b.to_host()["obs"].tobytes(), s
+        orc.iterate(host_ring[s % ring_len], s)
+    sa, sb = a.to_host(), b.to_host()
+    for n in sa:
+        assert sa[n].tobytes() == sb[n].tobytes(), n
+    assert_equal_state(sa, orc, "after the roll-out")
+    a.close(), b.close()
+
+
 def test_two_runs_are_byte_identical():
     import paper_2108_13976_amd as wd
 
