@@ -58,6 +58,12 @@ __device__ __forceinline__ int32_t sample_action(float p0, float p1, float p2, f
   return (u < c0) ? 0 : (u < c1) ? 1 : (u < c2) ? 2 : (u < c3) ? 3 : 4;
 }
 
+// Sixteen bytes at a 4-byte aligned address, which global memory takes in one access: a
+// group's slices are 16-byte aligned only when the agent count is a multiple of four.
+struct __attribute__((packed, aligned(4))) Quad32 {
+  uint32_t a, b, c, d;
+};
+
 // Actions of the four agents of a group from their 20 probabilities and one random block.
 // a0 = flat index of the group's first agent, n = how many of the four agents exist.
 __device__ __forceinline__ void sample_group(const float* __restrict__ probs, int64_t a0, int n, bool vec,
@@ -74,8 +80,23 @@ __device__ __forceinline__ void sample_group(const float* __restrict__ probs, in
       f[4 * q + 3] = v.w;
     }
   } else {
+    // whole quads of the group's 5 n floats in one access each, the rest one by one
+    const int quads = (n * kNumActions) >> 2;
+    const Quad32* src = reinterpret_cast<const Quad32*>(probs + a0 * kNumActions);
 #pragma unroll
-    for (int q = 0; q < 20; ++q) f[q] = (q < n * kNumActions) ? probs[a0 * kNumActions + q] : 0.0f;
+    for (int q = 0; q < 5; ++q) {
+      if (q < quads) {
+        const Quad32 v = src[q];
+        f[4 * q + 0] = __uint_as_float(v.a);
+        f[4 * q + 1] = __uint_as_float(v.b);
+        f[4 * q + 2] = __uint_as_float(v.c);
+        f[4 * q + 3] = __uint_as_float(v.d);
+      } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          f[4 * q + c] = (4 * q + c < n * kNumActions) ? probs[a0 * kNumActions + 4 * q + c] : 0.0f;
+      }
+    }
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) act[j] = sample_action(f[5 * j], f[5 * j + 1], f[5 * j + 2], f[5 * j + 3], r.w[j]);
@@ -88,6 +109,12 @@ __device__ __forceinline__ void load4(const int32_t* __restrict__ src, int64_t a
     v[1] = q.y;
     v[2] = q.z;
     v[3] = q.w;
+  } else if (n == 4) {
+    const Quad32 q = *reinterpret_cast<const Quad32*>(src + a0);
+    v[0] = int(q.a);
+    v[1] = int(q.b);
+    v[2] = int(q.c);
+    v[3] = int(q.d);
   } else {
 #pragma unroll
     for (int j = 0; j < 4; ++j) v[j] = j < n ? src[a0 + j] : 0;
