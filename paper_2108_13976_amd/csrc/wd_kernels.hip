@@ -534,7 +534,14 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
             }
             for (int f = (nvec << 2) + lane; f < nfl; f += kWaveSize) out[f] = stage[f];
           } else {
-            for (int f = lane; f < nfl; f += kWaveSize) out[f] = stage[f];
+            // the rows start on a 4-byte boundary only: 16-byte stores at that alignment
+            const int nvec = nfl >> 2;
+            for (int v = lane; v < nvec; v += kWaveSize) {
+              const float4 q = reinterpret_cast<const float4*>(stage)[v];
+              reinterpret_cast<Quad32*>(out)[v] =
+                  Quad32{__float_as_uint(q.x), __float_as_uint(q.y), __float_as_uint(q.z), __float_as_uint(q.w)};
+            }
+            for (int f = (nvec << 2) + lane; f < nfl; f += kWaveSize) out[f] = stage[f];
           }
           wave_sync_lds();
         }
