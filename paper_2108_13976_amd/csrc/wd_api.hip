@@ -90,9 +90,10 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   // workgroup fewer envs (fewer row chunks per wave) while that still shortens the chain.
   while (!big && ts_log2 < 8) {
     const int ts_now = 1 << ts_log2, tpw_now = 256 / ts_now;
-    const int64_t wgs = (int64_t(c.num_envs) + tpw_now - 1) / tpw_now;
+    const int64_t waves_if_doubled = int64_t(c.num_envs) * std::max(1, 2 * ts_now / wd::kWaveSize);
     const int64_t rows_per_wg = int64_t(std::min(tpw_now, c.num_envs)) * N;
-    if (wgs >= 512 || (rows_per_wg <= 64 && N <= ts_now)) break;
+    // 8192 wave slots on the chip: beyond that, wider teams only add rounds of workgroups
+    if (waves_if_doubled > 8192 || (rows_per_wg <= 64 && N <= ts_now)) break;
     ++ts_log2;
   }
   p->wg_size = 256;
