@@ -99,6 +99,45 @@ def time_gpu(cfg, ring, steps, warmup, mode, per_launch=1, **over):
     return wall, event_s, stats, bytes_per_iteration, launches
 
 
+def window_statistics(cfg, ring, steps, warmup):
+    """Untimed pass over the timed window's iterations: mean fraction of agents in play and mean
+    number of envs reset per iteration (state read back after every iteration)."""
+    import torch
+    import paper_2108_13976_amd as wd
+
+    env = wd.TagEnvs(device="cuda:0", **cfg.kwargs())
+    env.reset(wd.WD_RESET_ALL)
+    run_iterations(env, ring, 0, warmup, "fused")
+    live = torch.zeros((), dtype=torch.float64, device="cuda:0")
+    resets = torch.zeros((), dtype=torch.int64, device="cuda:0")
+    for k in range(steps):
+        env.iterate(ring[(warmup + k) % RING])
+        live += env.live.sum(dtype=torch.float64)
+        resets += (env.t == 0).sum()
+    torch.cuda.synchronize()
+    out = {"mean_live_fraction": float(live.item()) / (steps * cfg.num_envs * cfg.num_agents),
+           "resets_per_iteration": float(resets.item()) / steps}
+    env.close()
+    return out
+
+
+def device_copy_gbs(mib=1024, reps=10):
+    """Bytes read plus bytes written per second by a plain device-to-device copy of `mib` MiB."""
+    import torch
+
+    src = torch.empty(mib << 20, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    start_ev, end_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start_ev.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    end_ev.record()
+    torch.cuda.synchronize()
+    return 2.0 * (mib << 20) * reps / (start_ev.elapsed_time(end_ev) / 1e3) / 1e9
+
+
 def time_sampler(cfg, ring, reps=200):
     """wd_sample and torch.multinomial on the same [E*N, 5] probabilities: actions per second."""
     import torch
@@ -293,6 +332,22 @@ def main():
 
     if not args.no_extras:
         extras = {}
+        # the same timed window four more times (each from a fresh reset): median and spread of five
+        runs = [env_steps]
+        for _ in range(4):
+            w_rep, _, _, _, _ = time_gpu(cfg, ring, args.steps, args.warmup, mode, per_launch)
+            runs.append(args.steps / w_rep * cfg.num_envs)
+        runs.sort()
+        extras["env_steps_per_s_5_runs"] = {"median": runs[2], "min": runs[0], "max": runs[-1]}
+        extras.update(window_statistics(cfg, ring, args.steps, args.warmup))
+        # the roofline fraction again, against a plain device-to-device copy instead of the published peak
+        copy_gbs = device_copy_gbs()
+        extras["device_copy_gbs"] = copy_gbs
+        extras["frac_of_device_copy"] = achieved_gbs / copy_gbs
+        # what a brute-force step would evaluate (runner x tagger pairs for the tag check, agent x
+        # agent pairs for the neighbour search); the kernels evaluate far fewer, by bucket
+        pairs = (cfg.num_agents - cfg.num_taggers) * cfg.num_taggers + cfg.num_agents * (cfg.num_agents - 1)
+        extras["brute_force_pair_evaluations_per_s"] = env_steps * pairs
         # worst case for the neighbour search: tagging disabled, every agent live in every step
         short = min(args.steps, 300)
         w2, e2, _, _, _ = time_gpu(cfg, ring, short, 25, mode, per_launch, tag_r2=-1)
