@@ -148,6 +148,13 @@ def test_rollout_10x8192_fused_across_episode_ends():
     lockstep(kw, 17, cfg.seed, fused=True, full_envs=3, sharded=3)
 
 
+def test_rollout_10x8192_full_episode():
+    """tag_10x8192 as configured (T = 200), all 10 envs, fused, over a whole episode and the
+    reset that ends it; oracle sharded one env per thread."""
+    cfg = CONFIGS["tag_10x8192"]
+    lockstep(cfg.kwargs(), cfg.episode_length + 5, cfg.seed, fused=True, check_every=20, sharded=10)
+
+
 # ---- the headline workload at full size, in the launch configuration the benchmark times ----------
 def test_headline_workload_full_size_sampled_envs_and_invariants():
     import paper_2108_13976_amd as wd
@@ -259,6 +266,74 @@ def test_headline_workload_full_size_multi_step_launches():
             assert np.abs(rec["reward"][s][e] - o.reward[0]).max() <= FLOAT_TOL, (s, e)
             o.reset(1)
             assert np.abs(rec["obs"][s][e].astype(np.float64) - o.obs[0]).max() <= FLOAT_TOL, (s, e)
+    gpu.close()
+
+
+def test_headline_workload_every_env_fifty_iterations():
+    """tag_2000x1000 at full size, every one of the 2000 envs against the oracle (sharded over
+    the host's threads) for 50 wd_iterate launches from the reset state: the whole state after
+    the reset and after iterations 1, 2, 10, 25 and 50."""
+    import paper_2108_13976_amd as wd
+    from oracle import tag_oracle
+
+    cfg = CONFIGS["tag_2000x1000"]
+    kw = cfg.kwargs()
+    threads = 16
+    gpu = make_gpu(kw)
+    orc = make_oracle(kw)
+    gpu.reset(wd.WD_RESET_ALL)
+    tag_oracle.run_sharded(orc, lambda s: s.reset(), threads)
+    assert_equal_state(gpu.to_host(), orc, "after reset(ALL)")
+    for g in range(50):
+        probs = probs_for_step(cfg.seed, g, cfg.num_envs, cfg.num_agents)
+        gpu.iterate(upload(probs, gpu.device))
+        tag_oracle.run_sharded(orc, lambda s: s.iterate(probs[s.cfg.env_offset:s.cfg.env_offset + s.E], g), threads)
+        if g + 1 in (1, 2, 10, 25, 50):
+            assert_equal_state(gpu.to_host(), orc, f"after iteration {g + 1}")
+    gpu.close()
+
+
+def test_headline_workload_full_size_two_episodes_sampled_envs():
+    """tag_2000x1000 at full size for more than two episode lengths (T = 500: every env is reset at least twice),
+    one wd_iterate launch per iteration; 32 random envs against the oracle at checkpoints on both
+    sides of each episode end.  Between checkpoints every sampled env's oracle advances on its own
+    thread (the policy outputs come from a ring, so nothing but the step counter is shared)."""
+    import paper_2108_13976_amd as wd
+    from concurrent.futures import ThreadPoolExecutor
+
+    cfg = CONFIGS["tag_2000x1000"]
+    kw = cfg.kwargs()
+    E, N, T = cfg.num_envs, cfg.num_agents, cfg.episode_length
+    ring_len = 4
+    host_ring = np.stack([probs_for_step(cfg.seed, r, E, N) for r in range(ring_len)])
+    gpu = make_gpu(kw)
+    ring = upload(host_ring, gpu.device)
+    gpu.reset(wd.WD_RESET_ALL)
+    rng = np.random.default_rng(41)
+    sample_envs = sorted(int(e) for e in rng.choice(E, size=32, replace=False))
+    oracles = {e: make_oracle(kw, e, e + 1) for e in sample_envs}
+    for o in oracles.values():
+        o.reset()
+    checkpoints = [60, T - 1, T, T + 1, T + 200, 2 * T - 1, 2 * T, 2 * T + 15]
+    g = 0
+    with ThreadPoolExecutor(max_workers=16) as pool:
+        for stop in checkpoints:
+            def advance(item, g0=g, g1=stop):
+                e, o = item
+                for s in range(g0, g1):
+                    o.iterate(host_ring[s % ring_len][e:e + 1], s)
+            futures = [pool.submit(advance, item) for item in oracles.items()]
+            for s in range(g, stop):
+                gpu.iterate(ring[s % ring_len])
+            for f in futures:
+                f.result()
+            g = stop
+            assert gpu.global_step == g
+            state = gpu.to_host()
+            for e, o in oracles.items():
+                assert_equal_state(state, o, f"after iteration {g} env {e}", env_lo=e)
+            assert (state["t"] <= T).all() and (state["done"] == 0).all()
+    check_obs_invariants(cfg, state, FLOAT_TOL)
     gpu.close()
 
 
