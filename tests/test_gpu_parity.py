@@ -337,6 +337,87 @@ def test_headline_workload_full_size_two_episodes_sampled_envs():
     gpu.close()
 
 
+def test_full_observations_at_headline_size_sampled_envs():
+    """Full observations at 2000 x 1000 (rows of 4005 floats: 8 * 10^9 observation elements,
+    32 GB), the shape the benchmark times with --obs full.  Whole envs against the oracle: the
+    first and the last env, the envs whose rows straddle element 2^31 and element 2^32 of the
+    observation array (offsets that need 64 bits), and two more."""
+    import paper_2108_13976_amd as wd
+
+    cfg = CONFIGS["tag_2000x1000"]
+    kw = dict(cfg.kwargs(), obs_mode=1)
+    E, N = cfg.num_envs, cfg.num_agents
+    per_env = N * (5 + 4 * N)
+    sample_envs = sorted({0, (1 << 31) // per_env, (1 << 32) // per_env, 777, 1600, E - 1})
+    assert sample_envs[1] * per_env < (1 << 31) < (sample_envs[1] + 1) * per_env
+    gpu = make_gpu(kw)
+    gpu.reset(wd.WD_RESET_ALL)
+    oracles = {e: make_oracle(kw, e, e + 1) for e in sample_envs}
+    for o in oracles.values():
+        o.reset()
+
+    def check(where):
+        gpu.torch_stream.synchronize()
+        for e, o in oracles.items():
+            one = {n: t[e:e + 1].cpu().numpy() for n, t in gpu.tensors.items()}
+            assert_equal_state(one, o, f"{where} env {e}")
+
+    check("after reset(ALL)")
+    for g in range(5):
+        probs = probs_for_step(cfg.seed, g, E, N)
+        gpu.iterate(upload(probs, gpu.device))
+        for e, o in oracles.items():
+            o.iterate(probs[e:e + 1], g)
+        check(f"after iteration {g + 1}")
+    gpu.close()
+
+
+def test_headline_workload_long_recorded_launch():
+    """One wd_rollout launch of 110 recorded iterations at 2000 x 1000: the recorded observations
+    hold 4.6 * 10^9 floats (18 GB), so slice offsets need 64 bits.  Sampled envs against the
+    oracle in the first slice, in the slices that straddle element 2^31 and element 2^32, and in
+    the last; every recorded action, reward and done flag of those envs as well."""
+    import paper_2108_13976_amd as wd
+
+    cfg = CONFIGS["tag_2000x1000"]
+    kw = cfg.kwargs()
+    E, N, D = cfg.num_envs, cfg.num_agents, 5 + 4 * cfg.obs_k
+    k, ring_len = 110, 3
+    per_slice = E * N * D
+    watch = sorted({0, (1 << 31) // per_slice, (1 << 32) // per_slice, k - 1})
+    assert watch[-2] < k - 1
+    host_ring = np.stack([probs_for_step(cfg.seed, r, E, N) for r in range(ring_len)])
+    gpu = make_gpu(kw)
+    ring = upload(host_ring, gpu.device)
+    gpu.reset(wd.WD_RESET_ALL)
+    sample_envs = [0, 1023, E - 1]  # and the envs that hold element 2^31 and element 2^32 in their slices
+    sample_envs += [((1 << 31) % per_slice) // (N * D), ((1 << 32) % per_slice) // (N * D)]
+    sample_envs = sorted(set(sample_envs))
+    oracles = {e: make_oracle(kw, e, e + 1) for e in sample_envs}
+    for o in oracles.values():
+        o.reset()
+    rec = gpu.rollout(ring, k)
+    gpu.torch_stream.synchronize()
+    assert gpu.global_step == k
+    small = {n: rec[n][:, sample_envs].cpu().numpy() for n in ("action", "reward", "done")}
+    obs_slices = {s: rec["obs"][s][sample_envs].cpu().numpy() for s in watch}
+    for s in range(k):
+        for j, (e, o) in enumerate(oracles.items()):
+            o.sample(host_ring[s % ring_len][e:e + 1], s)
+            o.step()
+            assert np.array_equal(small["action"][s][j], o.action[0]), (s, e)
+            assert small["done"][s][j] == o.done[0], (s, e)
+            assert np.abs(small["reward"][s][j] - o.reward[0]).max() <= FLOAT_TOL, (s, e)
+            o.reset(1)
+            if s in obs_slices:
+                assert np.abs(obs_slices[s][j].astype(np.float64) - o.obs[0]).max() <= FLOAT_TOL, (s, e)
+    state = {n: t[sample_envs].cpu().numpy() for n, t in gpu.tensors.items()}
+    for j, (e, o) in enumerate(oracles.items()):
+        one = {n: v[j:j + 1] for n, v in state.items()}
+        assert_equal_state(one, o, f"state after the launch, env {e}")
+    gpu.close()
+
+
 @pytest.mark.parametrize("name,k,rounds", [("tag_10x5", 37, 8), ("tag_100x50", 16, 5), ("tag_20000x100", 6, 2)])
 def test_multi_step_rollout_equals_single_iterations(name, k, rounds):
     """wd_rollout (k iterations in one launch, per-iteration outputs) against k calls of the
