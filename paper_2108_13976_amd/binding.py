@@ -77,6 +77,11 @@ def load_library(path=LIBRARY):
     if _lib is None:
         if not os.path.exists(path):
             raise FileNotFoundError(f"{path} is missing: build it with `python -m paper_2108_13976_amd.build`")
+        # PyTorch allocates the buffers and supplies the stream, so libwd has to bind to the HIP
+        # runtime that PyTorch brings: load that first (two runtimes in one process do not share
+        # a device context, and the second one loaded may not find the GPU at all)
+        import torch  # noqa: F401
+
         lib = ctypes.CDLL(path)
         H = ctypes.c_void_p
         lib.wd_query_layout.argtypes = [ctypes.POINTER(wd_config), ctypes.POINTER(wd_layout)]

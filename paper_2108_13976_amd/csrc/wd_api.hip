@@ -24,7 +24,9 @@ struct wd_handle {
 
 namespace {
 
-constexpr int64_t kLdsLimitBytes = 160 * 1024;  // LDS of one gfx950 compute unit
+// LDS of one gfx950 compute unit, less the 256 bytes of static LDS the env kernels carry (the
+// workgroup votes of __syncthreads_and / __syncthreads_or): what a launch may ask for dynamically
+constexpr int64_t kLdsLimitBytes = 160 * 1024 - 256;
 constexpr int kMaxAgents = 32768;
 constexpr int kMaxGrid = 32767;
 
@@ -266,8 +268,29 @@ int fill_params(const wd_config& c, const wd_buffers& b, wd::Params* p) {
   p->done = b.done;
   p->n_live_runners = b.n_live_runners;
   p->tags_step = b.tags_step;
-  if (!plan_env_kernels(c, p, false) && !plan_env_kernels(c, p, true)) return WD_E_UNSUPPORTED;
-  if (!wd::env_kernel_available(*p)) return WD_E_UNSUPPORTED;
+  // Two layouts serve an env: one 256-thread workgroup with every table in LDS, or the large-env
+  // pair of kernels (a 1024-thread workgroup for the step, then the neighbour search spread over
+  // many workgroups).  The pair costs a second launch and a round trip of the tables through
+  // device memory, but puts four times the lanes on the step and a whole chip on the search, so
+  // it wins wherever the batch is too small to fill the chip with one workgroup per env, and for
+  // every batch once a lane of the small layout would own more than three groups.  Measured on
+  // partial observations, K = 4, E from 10 to 2000: the large-env pair is the faster one up to
+  // E = 0.3 N for 500 <= N <= 3000 (at E = 10: 26 -> 22 us per iteration at N = 500, 64 -> 26 at
+  // N = 2000, 158 -> 36 at N = 6000) and at every E from N = 3500 on (E = 2000: 840 -> 578 us).
+  const bool pair_serves = c.obs_mode == WD_OBS_PARTIAL && p->K <= wd::kMaxRegisterK2;
+  const bool prefer_pair =
+      pair_serves && (c.num_agents > 3072 || (c.num_agents >= 384 && 10ll * c.num_envs <= 3ll * c.num_agents));
+  const wd::Params filled = *p;
+  bool planned = prefer_pair && plan_env_kernels(c, p, true);
+  if (!planned) {
+    *p = filled;
+    planned = plan_env_kernels(c, p, false);
+  }
+  if (!planned && !prefer_pair) {
+    *p = filled;
+    planned = plan_env_kernels(c, p, true);
+  }
+  if (!planned || !wd::env_kernel_available(*p)) return WD_E_UNSUPPORTED;
   return WD_OK;
 }
 

@@ -65,6 +65,22 @@ def test_bad_configurations_are_rejected(over):
     assert ei.value.status == binding.WD_E_CONFIG
 
 
+@pytest.mark.parametrize("over", [
+    dict(num_agents=32768, num_taggers=3000, grid_size=100),               # tables of one env beyond a workgroup's LDS
+    dict(num_agents=20000, num_taggers=100, grid_size=30000, tag_r2=50),   # the same with 64-bit keys
+    dict(num_agents=9000, num_taggers=100, grid_size=300, obs_mode=binding.WD_OBS_FULL),
+    dict(num_agents=9000, num_taggers=100, grid_size=300, obs_k=17),
+])
+def test_valid_configurations_without_a_kernel_are_refused(over):
+    """Sizes the header allows but no kernel of this build covers: WD_E_UNSUPPORTED from wd_create
+    (before anything is allocated), while the layout query still answers."""
+    cfg = good_config(**over)
+    assert wd.wd_query_layout(cfg).obs_dim > 0
+    with pytest.raises(wd.WdError) as ei:
+        wd.wd_create(cfg, fake_buffers())
+    assert ei.value.status == binding.WD_E_UNSUPPORTED
+
+
 def test_struct_size_is_checked():
     cfg = good_config()
     cfg.struct_size = 8

@@ -85,15 +85,21 @@ def lockstep(kw, steps, probs_seed, fused, env_lo=0, env_hi=None, full_envs=None
             if g % check_every == 0 or g == steps - 1:
                 assert_equal_state(gpu.to_host(), orc, f"after iterate {g}")
         else:
+            def on_oracle(fn):
+                if sharded:
+                    tag_oracle.run_sharded(orc, fn, sharded)
+                else:
+                    fn(orc)
+
             gpu.sample(dprobs)
-            orc.sample(probs, g)
+            on_oracle(lambda s: s.sample(probs[s.cfg.env_offset - env_lo:s.cfg.env_offset - env_lo + s.E], g))
             assert_equal_state(gpu.to_host(), orc, f"after sample {g}", names=("action",))
             gpu.step()
-            orc.step()
+            on_oracle(lambda s: s.step())
             assert_equal_state(gpu.to_host(), orc, f"after step {g}")
             resets += int(orc.done.sum())
             gpu.reset(wd.WD_RESET_DONE)
-            orc.reset(tag_oracle.RESET_DONE)
+            on_oracle(lambda s: s.reset(tag_oracle.RESET_DONE))
             assert_equal_state(gpu.to_host(), orc, f"after reset(DONE) {g}")
         assert gpu.global_step == g + 1
     gpu.close()
@@ -122,9 +128,17 @@ def test_rollout_100x50_fused_across_episode_ends():
 
 
 def test_rollout_2000x1000_env_slice():
-    """24 envs of the headline workload (global ids 1000..1023), separate calls, 40 steps."""
+    """320 envs of the headline workload (global ids 1000..1319: enough of them for the
+    one-workgroup-per-env layout the whole workload runs in), separate calls, 40 steps."""
     cfg = CONFIGS["tag_2000x1000"]
-    lockstep(cfg.kwargs(), 40, cfg.seed, fused=False, env_lo=1000, env_hi=1024, full_envs=cfg.num_envs)
+    lockstep(cfg.kwargs(), 40, cfg.seed, fused=False, env_lo=1000, env_hi=1320, full_envs=cfg.num_envs, sharded=16)
+
+
+def test_rollout_2000x1000_small_env_slice():
+    """24 envs of the headline workload (global ids 1000..1023): a batch this small runs in the
+    large-env pair of kernels.  Fused, 40 steps."""
+    cfg = CONFIGS["tag_2000x1000"]
+    lockstep(cfg.kwargs(), 40, cfg.seed, fused=True, env_lo=1000, env_hi=1024, full_envs=cfg.num_envs, sharded=8)
 
 
 def test_rollout_20000x100_env_slice():
@@ -153,6 +167,41 @@ def test_rollout_10x8192_full_episode():
     reset that ends it; oracle sharded one env per thread."""
     cfg = CONFIGS["tag_10x8192"]
     lockstep(cfg.kwargs(), cfg.episode_length + 5, cfg.seed, fused=True, check_every=20, sharded=10)
+
+
+def largest_accepted_agent_count(**kw):
+    """Largest N (with N / 10 taggers) that wd_create accepts for the rest of the configuration;
+    found by bisection with placeholder buffers, which wd_create never dereferences."""
+    import paper_2108_13976_amd as wd
+    from paper_2108_13976_amd import binding
+
+    bufs = binding.wd_buffers(*[0x10000 + 0x1000 * i for i in range(len(binding.BUFFER_NAMES))])
+
+    def accepted(n):
+        try:
+            wd.wd_destroy(wd.wd_create(binding.make_config(num_agents=n, num_taggers=n // 10, **kw), bufs))
+            return True
+        except wd.WdError as err:
+            assert err.status == binding.WD_E_UNSUPPORTED, err
+            return False
+
+    lo, hi = 2000, 32768
+    assert accepted(lo) and not accepted(hi)
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        lo, hi = (mid, hi) if accepted(mid) else (lo, mid)
+    return lo
+
+
+@pytest.mark.parametrize("grid_size,tag_r2", [(100, 2), (700, 30)], ids=["32_bit_keys", "64_bit_keys"])
+def test_largest_env_the_library_accepts(grid_size, tag_r2):
+    """The largest env one workgroup's tables hold (about 13 900 agents with 32-bit keys, 11 600
+    with 64-bit ones): two envs, three iterations, every element against the oracle."""
+    rest = dict(num_envs=2, grid_size=grid_size, episode_length=2, tag_r2=tag_r2)
+    n = largest_accepted_agent_count(**rest)
+    assert n > 10000
+    kw = dict(rest, num_agents=n, num_taggers=n // 10, obs_k=4, seed=77)
+    lockstep(kw, 3, 78, fused=True, sharded=2)
 
 
 # ---- the headline workload at full size, in the launch configuration the benchmark times ----------
@@ -697,6 +746,13 @@ EDGE = {
     "full_obs_one_wave": dict(num_envs=3, num_agents=132, num_taggers=9, grid_size=12, episode_length=8, obs_mode=1),
     "full_obs_two_waves": dict(num_envs=3, num_agents=260, num_taggers=20, grid_size=16, episode_length=6, obs_mode=1),
     "full_obs_thousand": dict(num_envs=2, num_agents=1000, num_taggers=100, grid_size=30, episode_length=5, obs_mode=1),
+    # enough envs for the one-workgroup-per-env layout at these agent counts (fewer envs run in the
+    # large-env pair of kernels): two, six and twelve agents per lane
+    "five_hundred_twenty_many_envs": dict(num_envs=170, num_agents=520, num_taggers=40, grid_size=60, episode_length=6),
+    "fifteen_hundred_many_envs": dict(num_envs=460, num_agents=1500, num_taggers=100, grid_size=120, episode_length=3),
+    "three_thousand_many_envs": dict(num_envs=910, num_agents=3000, num_taggers=250, grid_size=170, episode_length=2),
+    # the large-env pair at the smallest agent count it is chosen for
+    "large_env_pair_smallest": dict(num_envs=3, num_agents=384, num_taggers=30, grid_size=50, episode_length=10, obs_k=16),
     "odd_rewards": dict(num_envs=12, num_agents=25, num_taggers=5, grid_size=8, episode_length=20, obs_k=2,
                         tag_reward=0.3, tag_penalty=-2.5),
 }
@@ -707,4 +763,5 @@ EDGE = {
 def test_edge_case(name, fused):
     kw = dict(seed=77, **EDGE[name])
     steps = min(3 * kw["episode_length"], 60)
-    lockstep(kw, steps, 77, fused=fused, sharded=2 if kw["num_agents"] > 4000 else 0)
+    work = kw["num_envs"] * kw["num_agents"] ** 2  # pairs the oracle looks at per step
+    lockstep(kw, steps, 77, fused=fused, sharded=0 if work < 5e7 else min(16, kw["num_envs"]))
