@@ -109,10 +109,10 @@ int wd_query_layout(const wd_config* cfg, wd_layout* out);
  * returns a handle in *out.  Enqueues nothing; the buffers' contents are not read.
  * WD_E_UNSUPPORTED if no kernel of this build covers the configuration (an env whose
  * tables exceed one workgroup's LDS: beyond about 13 900 agents with 32-bit keys, 11 500
- * with 64-bit keys, 8192 for full observations or K > 16).  Envs of more than 3072
- * agents, and batches of few envs of 384 agents or more (E <= 0.3 N), run in the
- * large-env layout, whose work tables (about 20 bytes per agent) the library allocates
- * here with hipMalloc: WD_E_HIP if that fails. */
+ * with 64-bit keys, 8192 for full observations or K > 16).  Envs too large for one
+ * workgroup's LDS, and batches of few envs (at most 450, or 0.3 N up to 1024 agents) of
+ * 384 agents or more, run in the large-env layout, whose work tables (about 20 bytes per
+ * agent) the library allocates here with hipMalloc: WD_E_HIP if that fails. */
 int wd_create(const wd_config* cfg, const wd_buffers* bufs, wd_handle** out);
 
 /* Environment reset (Sec. 4.5 item 5 "Automatic Environment Resetting").

@@ -99,6 +99,14 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
     ++ts_log2;
   }
   p->wg_size = 256;
+  // An env of more than 1024 agents takes more LDS than lets eight 256-thread workgroups share
+  // a CU: wider workgroups keep the CU's wave slots filled.  Measured at E = 2000, us per
+  // iteration with 256 / 512 / 1024 threads: N = 1100 105 / 92 / -, N = 2000 249 / 218 / -,
+  // N = 3000 443 / 338 / 462, N = 3500 840 / 586 / 526, N = 4000 887 / 644 / 584.
+  if (!big && N > 1024) {
+    ts_log2 = N > 3072 ? 10 : 9;
+    p->wg_size = 1 << ts_log2;
+  }
   if (big) {  // one env per 1024-thread workgroup
     ts_log2 = 10;
     p->wg_size = wd::kBigEnvWorkgroupSize;
@@ -268,18 +276,17 @@ int fill_params(const wd_config& c, const wd_buffers& b, wd::Params* p) {
   p->done = b.done;
   p->n_live_runners = b.n_live_runners;
   p->tags_step = b.tags_step;
-  // Two layouts serve an env: one 256-thread workgroup with every table in LDS, or the large-env
-  // pair of kernels (a 1024-thread workgroup for the step, then the neighbour search spread over
-  // many workgroups).  The pair costs a second launch and a round trip of the tables through
-  // device memory, but puts four times the lanes on the step and a whole chip on the search, so
-  // it wins wherever the batch is too small to fill the chip with one workgroup per env, and for
-  // every batch once a lane of the small layout would own more than three groups.  Measured on
-  // partial observations, K = 4, E from 10 to 2000: the large-env pair is the faster one up to
-  // E = 0.3 N for 500 <= N <= 3000 (at E = 10: 26 -> 22 us per iteration at N = 500, 64 -> 26 at
-  // N = 2000, 158 -> 36 at N = 6000) and at every E from N = 3500 on (E = 2000: 840 -> 578 us).
+  // Two layouts serve an env: one workgroup with every table in LDS, or the large-env pair of
+  // kernels (a 1024-thread workgroup for the step, then the neighbour search spread over many
+  // workgroups).  The pair costs a second launch and a round trip of the tables through device
+  // memory, but puts a whole chip on the search of a few envs, so it wins while the batch is too
+  // small to fill the chip with one workgroup per env.  Measured crossovers (partial
+  // observations, K = 4, us per iteration one workgroup -> pair): E = 10: N = 500 26 -> 22,
+  // N = 2000 64 -> 26, N = 6000 158 -> 36; E = 320: N = 1000 39 -> 45, N = 2000 82 -> 66,
+  // N = 4000 133 -> 114; E = 640: N = 2000 92 -> 106, N = 4000 215 -> 226, N = 6000 306 -> 381.
   const bool pair_serves = c.obs_mode == WD_OBS_PARTIAL && p->K <= wd::kMaxRegisterK2;
-  const bool prefer_pair =
-      pair_serves && (c.num_agents > 3072 || (c.num_agents >= 384 && 10ll * c.num_envs <= 3ll * c.num_agents));
+  const int64_t pair_up_to = c.num_agents <= 1024 ? 3ll * c.num_agents / 10 : 450;  // envs
+  const bool prefer_pair = pair_serves && c.num_agents >= 384 && c.num_envs <= pair_up_to;
   const wd::Params filled = *p;
   bool planned = prefer_pair && plan_env_kernels(c, p, true);
   if (!planned) {

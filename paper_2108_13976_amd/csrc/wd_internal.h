@@ -9,8 +9,8 @@
 namespace wd {
 
 constexpr int kWorkgroupSize = 256;     // flat per-agent kernels: four wave64s
-constexpr int kMaxEnvWorkgroupSize = 512;  // env-per-team kernels run 256 or 512 threads,
-constexpr int kBigEnvWorkgroupSize = 1024; // or 1024 for an env too large for the small layout
+constexpr int kMaxEnvWorkgroupSize = 1024; // env-per-team kernels run 256, 512 or 1024 threads (by agent count);
+constexpr int kBigEnvWorkgroupSize = 1024; // 1024 in the step kernel of the large-env layout
 constexpr int kBigObsWorkgroupSize = 512;  // observation kernel of the large-env layout
 constexpr int kWaveSize = 64;
 constexpr int kNumActions = 5;
@@ -50,7 +50,7 @@ struct Params {
   // thread lt of a team owns groups lt, lt + ts, ... (gpt of them).
   int32_t NG;            // groups per env = ceil(N / 4)
   int32_t NPAD;          // 4 * NG rounded up to 8: per-agent LDS arrays are padded to this
-  int32_t wg_size;       // 256, or 512 when one env fills the workgroup (more lanes per env)
+  int32_t wg_size;       // 256; 512 or 1024 for one env of more than 1024 or 3072 agents
   int32_t stage_rows_log2;  // rows a wave transposes through LDS per flush: 32 or 16
   int32_t ts_log2, teams_per_wg, gpt;
   int32_t vec4;          // N % 4 == 0: a group's global slices are 16-byte aligned

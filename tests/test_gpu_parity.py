@@ -509,10 +509,12 @@ def test_multi_step_rollout_equals_single_iterations(name, k, rounds):
     a.close(), b.close()
 
 
-@pytest.mark.parametrize("name,k", [("large_env_k_two", 3), ("full_obs_fifty", 4), ("k_all_others", 5)])
-def test_multi_step_rollout_without_a_multi_step_kernel(name, k):
-    """Large-env layout, full observations, K > 8: wd_rollout runs one launch per iteration;
-    its slices and final state against k calls of wd_iterate."""
+@pytest.mark.parametrize("name,k", [("large_env_k_two", 3), ("full_obs_fifty", 4), ("k_all_others", 5),
+                                    ("fifteen_hundred_many_envs", 4), ("thirty_five_hundred_many_envs", 3)])
+def test_multi_step_rollout_of_other_launch_shapes(name, k):
+    """Large-env layout, full observations, K > 8 (wd_rollout runs one launch per iteration) and
+    the multi-step kernel in 512- and 1024-thread workgroups: slices and final state against k
+    calls of wd_iterate."""
     import paper_2108_13976_amd as wd
 
     kw = dict(EDGE[name], seed=77)
@@ -747,10 +749,14 @@ EDGE = {
     "full_obs_two_waves": dict(num_envs=3, num_agents=260, num_taggers=20, grid_size=16, episode_length=6, obs_mode=1),
     "full_obs_thousand": dict(num_envs=2, num_agents=1000, num_taggers=100, grid_size=30, episode_length=5, obs_mode=1),
     # enough envs for the one-workgroup-per-env layout at these agent counts (fewer envs run in the
-    # large-env pair of kernels): two, six and twelve agents per lane
+    # large-env pair of kernels): 256, 512 and 1024 threads per env
     "five_hundred_twenty_many_envs": dict(num_envs=170, num_agents=520, num_taggers=40, grid_size=60, episode_length=6),
     "fifteen_hundred_many_envs": dict(num_envs=460, num_agents=1500, num_taggers=100, grid_size=120, episode_length=3),
     "three_thousand_many_envs": dict(num_envs=910, num_agents=3000, num_taggers=250, grid_size=170, episode_length=2),
+    "thirty_five_hundred_many_envs": dict(num_envs=455, num_agents=3500, num_taggers=300, grid_size=180, episode_length=2),
+    # the any-K variant and full observations in 512-thread workgroups
+    "k_seventeen_fifteen_hundred": dict(num_envs=3, num_agents=1500, num_taggers=90, grid_size=70, episode_length=4, obs_k=17),
+    "full_obs_twelve_hundred": dict(num_envs=2, num_agents=1200, num_taggers=100, grid_size=40, episode_length=3, obs_mode=1),
     # the large-env pair at the smallest agent count it is chosen for
     "large_env_pair_smallest": dict(num_envs=3, num_agents=384, num_taggers=30, grid_size=50, episode_length=10, obs_k=16),
     "odd_rewards": dict(num_envs=12, num_agents=25, num_taggers=5, grid_size=8, episode_length=20, obs_k=2,
