@@ -326,6 +326,10 @@ def main():
             **({"note": "inside a launch positions, live flags and env scalars stay on chip (36 of the 140 "
                         "algorithmic bytes per agent-step are not moved in 24 of 25 iterations)"}
                if mode == "rollout" else {}),
+            **({"note": "rows of agents that were already out of play are kept in place, only their time feature "
+                        "is rewritten: fewer bytes move than the algorithmic figure, so frac can exceed 1; "
+                        "extras.all_live_hbm_frac is the figure with every row written"}
+               if args.obs == "full" else {}),
         },
         "state_at_end": stats,
     }

@@ -26,6 +26,14 @@
  *     memory, with one exception: for envs too large for a workgroup's LDS
  *     (thousands of agents) wd_create allocates per-env work tables once on the
  *     current device (about 20 bytes per agent) and wd_destroy frees them.
+ *   - The observations are part of that in-place state (one data store, modified
+ *     in place: Sec. 4.2).  The row of an agent that was already out of play
+ *     before a step differs from the row the previous call left in `obs` in its
+ *     time feature only, and a step may rewrite just that element.  A caller that
+ *     overwrites `obs` between calls, or restores the other arrays from a
+ *     checkpoint without it, calls wd_set_step (with the step counter to go on
+ *     from): the next call then writes every row whole.  Rows recorded through
+ *     wd_rollout_buffers are always written whole.
  *   - Random numbers are Philox4x32-10 blocks keyed by (seed, global env id,
  *     agent, global step g, stream), so results do not depend on launch shape,
  *     and a run over envs [a, b) with env_offset = a reproduces those envs of the
@@ -85,7 +93,7 @@ typedef struct wd_buffers {
   int32_t* live;            /* [E][N] 1 = in play, 0 = tagged runner                     */
   int32_t* action;          /* [E][N] written by wd_sample, read by wd_step              */
   float* reward;            /* [E][N] overwritten for every agent by each step           */
-  float* obs;               /* [E][N][D]                                                 */
+  float* obs;               /* [E][N][D] kept up to date in place (see Conventions)        */
   int32_t *t, *done, *n_live_runners, *tags_step; /* [E]                                 */
 } wd_buffers;
 
@@ -161,7 +169,9 @@ typedef struct wd_rollout_buffers {
  * with the same results.  On WD_E_HIP part of the iterations may have been enqueued. */
 int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const wd_rollout_buffers* out);
 
-/* The global step counter g used as the RNG step index (checkpoint / resume). */
+/* The global step counter g used as the RNG step index (checkpoint / resume).
+ * wd_set_step also tells the library that `obs` may not hold the rows of the current
+ * state any more (see Conventions): the next step writes every row whole. */
 int wd_get_step(wd_handle* h, uint64_t* g);
 int wd_set_step(wd_handle* h, uint64_t g);
 

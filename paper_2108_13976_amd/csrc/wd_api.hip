@@ -18,6 +18,7 @@ struct wd_handle {
   hipStream_t stream;
   uint64_t g;          // global step: RNG step index
   bool started;        // wd_reset(WD_RESET_ALL) has run
+  bool rows_valid;     // bufs.obs holds the rows this library wrote for the current state
   void* scratch;       // device memory of the large-env tables (NULL for the small layout)
   std::string last_error;
 };
@@ -363,6 +364,7 @@ int wd_create(const wd_config* cfg, const wd_buffers* bufs, wd_handle** out) {
   h->stream = static_cast<hipStream_t>(cfg->stream);
   h->g = 0;
   h->started = false;
+  h->rows_valid = false;
   *out = h;
   return WD_OK;
 }
@@ -383,6 +385,7 @@ int wd_reset(wd_handle* h, int mode) {
     if (err != hipSuccess) return hip_failed(h, err, "reset kernel");
     h->g = 0;
     h->started = true;
+    h->rows_valid = true;
     return WD_OK;
   }
   err = wd::launch_env_kernel(h->params, wd::kModeResetDone, nullptr, 0, h->stream);
@@ -402,8 +405,11 @@ int wd_sample(wd_handle* h, const float* probs) {
 int wd_step(wd_handle* h) {
   if (!h) return WD_E_NULL;
   if (!h->started) return WD_E_STATE;
-  const hipError_t err = wd::launch_env_kernel(h->params, wd::kModeStep, nullptr, h->g, h->stream);
+  wd::Params q = h->params;
+  q.rows_kept = h->rows_valid ? 1 : 0;
+  const hipError_t err = wd::launch_env_kernel(q, wd::kModeStep, nullptr, h->g, h->stream);
   if (err != hipSuccess) return hip_failed(h, err, "step kernel");
+  h->rows_valid = true;
   h->g += 1;
   return WD_OK;
 }
@@ -412,8 +418,11 @@ int wd_iterate(wd_handle* h, const float* probs) {
   if (!h || !probs) return WD_E_NULL;
   if (!probs_aligned(h->params, probs)) return WD_E_ALIGN;
   if (!h->started) return WD_E_STATE;
-  const hipError_t err = wd::launch_env_kernel(h->params, wd::kModeIterate, probs, h->g, h->stream);
+  wd::Params q = h->params;
+  q.rows_kept = h->rows_valid ? 1 : 0;
+  const hipError_t err = wd::launch_env_kernel(q, wd::kModeIterate, probs, h->g, h->stream);
   if (err != hipSuccess) return hip_failed(h, err, "iterate kernel");
+  h->rows_valid = true;
   h->g += 1;
   return WD_OK;
 }
@@ -428,6 +437,9 @@ int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const
       if (reinterpret_cast<uintptr_t>(ptr) & 15u) return WD_E_ALIGN;
   }
   if (!h->started) return WD_E_STATE;
+  // recorded observations go to slices that hold nothing yet, and the in-place rows that the last
+  // iteration then meets date from before the call: every row is written whole
+  const int rows_kept = (h->rows_valid && !(out && out->obs)) ? 1 : 0;
   if (!wd::rollout_available(h->params)) {
     // Configurations without a multi-step kernel (large-env layout, full observations,
     // K > 8): the same results from one launch of the iteration kernels per iteration,
@@ -435,6 +447,7 @@ int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const
     const int64_t EN = int64_t(h->cfg.num_envs) * h->cfg.num_agents, D = h->params.D;
     for (int s = 0; s < k; ++s) {
       wd::Params q = h->params;
+      q.rows_kept = rows_kept;
       if (out && s + 1 < k) {
         if (out->action) q.action = out->action + int64_t(s) * EN;
         if (out->reward) q.reward = out->reward + int64_t(s) * EN;
@@ -456,6 +469,7 @@ int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const
         err = hipMemcpyAsync(out->obs + last * D, h->bufs.obs, size_t(EN * D) * 4, hipMemcpyDeviceToDevice, h->stream);
       if (err != hipSuccess) return hip_failed(h, err, "copy of the last roll-out slice");
     }
+    h->rows_valid = true;
     h->g += uint64_t(k);
     return WD_OK;
   }
@@ -470,8 +484,11 @@ int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const
     roll.done = out->done;
     roll.obs = out->obs;
   }
-  const hipError_t err = wd::launch_rollout(h->params, roll, probs_ring, h->g, h->stream);
+  wd::Params q = h->params;
+  q.rows_kept = rows_kept;
+  const hipError_t err = wd::launch_rollout(q, roll, probs_ring, h->g, h->stream);
   if (err != hipSuccess) return hip_failed(h, err, "rollout kernel");
+  h->rows_valid = true;
   h->g += uint64_t(k);
   return WD_OK;
 }
@@ -485,6 +502,7 @@ int wd_get_step(wd_handle* h, uint64_t* g) {
 int wd_set_step(wd_handle* h, uint64_t g) {
   if (!h) return WD_E_NULL;
   h->g = g;
+  h->rows_valid = false;  // a resumed run: the caller may have restored the state arrays without the observations
   return WD_OK;
 }
 

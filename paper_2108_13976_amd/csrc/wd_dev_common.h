@@ -9,6 +9,7 @@ namespace wd {
 namespace dev {
 
 constexpr uint32_t kDeadBit = 0x80000000u;  // in a packed position or entry: agent is out of play
+constexpr uint32_t kStaleBit = 0x8000u;  // in a packed position: out of play since before this step began
 constexpr uint32_t kNoNeighbour = 0xFFFFu;
 
 // ----------------------------------------------------------------------------------

@@ -89,6 +89,9 @@ struct Params {
   float* obs;
   int32_t *t, *done, *n_live_runners, *tags_step;
   int32_t* done_log;     // optional [E]: done flags of an iteration before its reset (roll-outs)
+  int32_t rows_kept;     // 1: the obs buffer this launch writes still holds the rows this library wrote for
+                         // the state the step starts from (a row whose agent was already out of play then
+                         // differs from it in the time feature only)
 };
 
 // A multi-step roll-out: iteration s reads ring entry (ring_pos + s) mod ring_len and writes

@@ -188,7 +188,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
             moved |= (nx != x[j]) | (ny != y[j]);
             x[j] = nx;
             y[j] = ny;
-            packed[j] = pack_pos(nx, ny, is_live);
+            packed[j] = pack_pos(nx, ny, is_live) | (is_live ? 0u : kStaleBit);
             if (is_live) atomicAdd(&L.counts[bucket_of(nx, ny, bk)], 1u);
             L.best[i0 + j] = key_none<Key>();
           }
@@ -581,7 +581,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
             const uint32_t g_lo = (row_f + 3u) >> 2, g_hi = (row_f + Du + 3u) >> 2;  // pieces that start in row i
             const uint32_t shift = (4u * g_lo - row_f - 5u) & 3u;          // slot component a piece starts with
             const uint32_t me = L.pl[i];
-            for (uint32_t g = g_lo + uint32_t(lane); g < g_hi; g += kWaveSize) {
+            const auto emit = [&](uint32_t g) {
               const int c0 = int(4u * g - row_f);  // column of the piece's first float
               float4 v;
               if (c0 >= 5 && c0 + 3 < int(Du)) {
@@ -621,6 +621,18 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
                 v = make_float4(f[0], f[1], f[2], f[3]);
               }
               env_q[g] = v;
+            };
+            // A row whose agent was out of play before the step began differs from what a kept
+            // buffer holds in its time feature only: its first two pieces (one of them holds
+            // that feature) and its last (which may run into the next row) are written.  A row
+            // has at least five pieces.
+            if (p.rows_kept && (me & kStaleBit)) {
+              if (lane < 2)
+                emit(g_lo + uint32_t(lane));
+              else if (lane == 2)
+                emit(g_hi - 1u);
+            } else {
+              for (uint32_t g = g_lo + uint32_t(lane); g < g_hi; g += kWaveSize) emit(g);
             }
           }
         } else {
@@ -629,8 +641,12 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
             const uint32_t i = fastdiv(u, p.div_N);
             const uint32_t j = u - i * uint32_t(N);
             const uint32_t me = L.pl[i];
-            const FullSlot S = full_slot(me, L.pl[j], int(j) < N_tag, p.inv_G);
             float* row = env_obs + int64_t(i) * D;
+            if (p.rows_kept && (me & kStaleBit)) {  // only the time feature of such a row changes
+              if (j == 0) row[4] = tf;
+              continue;
+            }
+            const FullSlot S = full_slot(me, L.pl[j], int(j) < N_tag, p.inv_G);
             Slot4 v;
             v.a = S.a;
             v.b = S.b;
@@ -655,6 +671,10 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
       for (int i = lt; i < N; i += ts) {
         float* row = out.obs + (abase + i) * D;
         const uint32_t me = L.pl[i];
+        if (p.rows_kept && (me & kStaleBit)) {  // only the time feature of such a row changes
+          row[4] = tf;
+          continue;
+        }
         const int x = pos_x_of(me), y = pos_y_of(me);
         const bool lv = !(me & kDeadBit);
         row[0] = static_cast<float>(x) * p.inv_G;
@@ -768,7 +788,12 @@ __global__ __launch_bounds__(kBigObsWorkgroupSize) void big_obs_kernel(const Par
   const int i_chunk = (N + p.big_slices - 1) / p.big_slices;
   const int i_end = min(N, (s + 1) * i_chunk);
   for (int i = s * i_chunk + tid; i < i_end; i += kBigObsWorkgroupSize) {
-    if (!(L.pl[i] & kDeadBit)) continue;
+    const uint32_t me = L.pl[i];
+    if (!(me & kDeadBit)) continue;
+    if (p.rows_kept && (me & kStaleBit)) {  // out of play before this step: only the time feature changes
+      env_obs[int64_t(i) * D + 4] = t_frac;
+      continue;
+    }
     Key keys[KT];
 #pragma unroll
     for (int kk = 0; kk < KT; ++kk) keys[kk] = key_none<Key>();

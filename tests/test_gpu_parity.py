@@ -667,6 +667,32 @@ def test_random_configuration_multi_step(seed):
     a.close(), b.close()
 
 
+@pytest.mark.parametrize("name", ["full_obs_fifty", "full_obs_one_wave", "k_seventeen", "large_env_narrow_keys",
+                                  "wide_radius"])
+def test_observations_overwritten_by_the_caller(name):
+    """Rows of agents that were out of play before a step are kept up to date in place (only their
+    time feature is rewritten by some kernels).  A caller that overwrites the observation buffer
+    says so with wd_set_step; the next call then writes every row whole."""
+    import paper_2108_13976_amd as wd
+
+    kw = dict(seed=77, **EDGE[name])
+    E, N = kw["num_envs"], kw["num_agents"]
+    gpu, orc = make_gpu(kw), make_oracle(kw)
+    gpu.reset(wd.WD_RESET_ALL), orc.reset()
+    tagged = False
+    for g in range(min(2 * kw["episode_length"], 40)):
+        probs = probs_for_step(77, g, E, N)
+        if g % 3 == 2:
+            tagged = tagged or bool((orc.live == 0).any())
+            gpu.tensors["obs"].fill_(-123.5)
+            gpu.global_step = g
+        gpu.iterate(upload(probs, gpu.device))
+        orc.iterate(probs, g)
+        assert_equal_state(gpu.to_host(), orc, f"after iteration {g}")
+    assert tagged, "the case never had an agent out of play when the buffer was overwritten"
+    gpu.close()
+
+
 def test_two_runs_are_byte_identical():
     import paper_2108_13976_amd as wd
 
