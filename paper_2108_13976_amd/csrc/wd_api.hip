@@ -75,7 +75,7 @@ int32_t obs_dim(const wd_config* c) {
 
 bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
-// probs is read with 16-byte loads when N % 4 == 0, with 4-byte loads otherwise
+// probs is read with aligned 16-byte loads when N % 4 == 0, else with loads that need 4-byte alignment
 bool probs_aligned(const wd::Params& p, const void* probs) {
   return (reinterpret_cast<uintptr_t>(probs) & (p.vec4 ? 15u : 3u)) == 0;
 }

@@ -3,7 +3,7 @@
 // Three services of the roll-out loop (arXiv 2108.13976, Sec. 4.4: sampler and reset
 // kernels of the service layer, step kernel of the environment; Sec. 4.5 items 3-6),
 // for the discrete Tag rules of Sec. 5.1.  The paper maps one thread block to an env
-// and one thread to an agent; here a TEAM of 8..256 threads owns an env (several small
+// and one thread to an agent; here a TEAM of 8..1024 threads owns an env (several small
 // envs share a 256-thread workgroup), a thread owns groups of four consecutive agents
 // (16-byte loads and stores, one random block per group), the env's positions are staged
 // in LDS, the pairwise passes (tag check, K-nearest search) run over a bucket-sorted copy
