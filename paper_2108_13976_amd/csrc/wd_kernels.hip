@@ -469,12 +469,14 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
         }
         if constexpr (KX > 0 && KX <= 4) {
           constexpr int DD = 5 + 4 * KX;
-          // Two flushes of 32 rows = 168 16-byte pieces each.  A whole chunk has no bounds to
-          // test; the last chunk of the workgroup stores only the pieces that exist (its rows
-          // end on a 16-byte boundary when the row count times DD is a multiple of four).
+          // Two flushes of 32 rows = 8 DD 16-byte pieces each (168 at K = 4): kFull stores that
+          // every lane takes part in and one more for the first kRem lanes.  A whole chunk has
+          // no bounds to test; the last chunk of the workgroup stores only the pieces that exist
+          // (its rows end on a 16-byte boundary when the row count times DD is a multiple of four).
           const auto flush_chunk = [&](auto whole_chunk) {
             constexpr bool kWhole = decltype(whole_chunk)::value;
             constexpr int kPieces = 32 * DD / 4;
+            constexpr int kFull = kPieces / kWaveSize, kRem = kPieces % kWaveSize;
             const int limit = kWhole ? 0 : (rows_total - R0) * DD / 4 - lane;  // pieces of this chunk from this lane on
             float4* out4 = reinterpret_cast<float4*>(obs_wg + int64_t(R0) * DD) + lane;
             const float4* st4 = reinterpret_cast<const float4*>(stage) + lane;
@@ -486,13 +488,16 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
                 for (int d = 0; d < DD; ++d) dst[d] = row[d];
               }
               wave_sync_lds();
-              const float4 a = st4[0], b = st4[kWaveSize];
-              float4 c = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-              if (lane + 2 * kWaveSize < kPieces) c = st4[2 * kWaveSize];
-              if (kWhole || h * kPieces < limit) out4[h * kPieces] = a;
-              if (kWhole || h * kPieces + kWaveSize < limit) out4[h * kPieces + kWaveSize] = b;
-              if (lane + 2 * kWaveSize < kPieces && (kWhole || h * kPieces + 2 * kWaveSize < limit))
-                out4[h * kPieces + 2 * kWaveSize] = c;
+              float4 v[kFull + 1];
+#pragma unroll
+              for (int m = 0; m < kFull; ++m) v[m] = st4[m * kWaveSize];
+              v[kFull] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+              if (kRem > 0 && lane < kRem) v[kFull] = st4[kFull * kWaveSize];
+#pragma unroll
+              for (int m = 0; m < kFull; ++m)
+                if (kWhole || h * kPieces + m * kWaveSize < limit) out4[h * kPieces + m * kWaveSize] = v[m];
+              if (kRem > 0 && lane < kRem && (kWhole || h * kPieces + kFull * kWaveSize < limit))
+                out4[h * kPieces + kFull * kWaveSize] = v[kFull];
               wave_sync_lds();
             }
           };
@@ -914,10 +919,12 @@ hipError_t launch_rollout_variant(const Params& p, const Roll& roll, const float
   return hipGetLastError();
 }
 
-// Which compiled variant serves K: 4 (the benchmark shape), 0 (K <= 8 at run time), -2 (K <= 16), -1 (any K).
+// Which compiled variant serves K: 1..4 (K compiled in; 4 is the benchmark shape), 0 (K <= 8 at run time),
+// -2 (K <= 16), -1 (any K).
 int variant_of(const Params& p) {
   if (p.obs_mode == 1) return -1;
   if (p.K == 4) return 4;
+  if (p.K >= 1 && p.K <= 3 && !p.wide && !p.big) return p.K;  // compiled in as well, for 32-bit keys in the small layout
   if (p.K <= kMaxRegisterK) return 0;
   if (p.K <= kMaxRegisterK2) return -2;
   return -1;
@@ -946,6 +953,9 @@ int variant_of(const Params& p) {
     if (!p.wide) {                                                                         \
       if (kx == 4 && p.compact_nbr) return fn<false, 4, true, false>(p, ##__VA_ARGS__);    \
       if (kx == 4) return fn<false, 4, false, false>(p, ##__VA_ARGS__);                    \
+      if (kx == 3) return fn<false, 3, false, false>(p, ##__VA_ARGS__);                    \
+      if (kx == 2) return fn<false, 2, false, false>(p, ##__VA_ARGS__);                    \
+      if (kx == 1) return fn<false, 1, false, false>(p, ##__VA_ARGS__);                    \
       if (kx == 0) return fn<false, 0, false, false>(p, ##__VA_ARGS__);                    \
       if (kx == -2) return fn<false, -2, false, false>(p, ##__VA_ARGS__);                  \
       return fn<false, -1, false, false>(p, ##__VA_ARGS__);                                \
@@ -969,6 +979,9 @@ hipError_t launch_rollout(const Params& p, const Roll& roll, const float* ring, 
   if (!p.wide) {
     if (kx == 4 && p.compact_nbr) return launch_rollout_variant<false, 4, true>(p, roll, ring, g, stream);
     if (kx == 4) return launch_rollout_variant<false, 4, false>(p, roll, ring, g, stream);
+    if (kx == 3) return launch_rollout_variant<false, 3, false>(p, roll, ring, g, stream);
+    if (kx == 2) return launch_rollout_variant<false, 2, false>(p, roll, ring, g, stream);
+    if (kx == 1) return launch_rollout_variant<false, 1, false>(p, roll, ring, g, stream);
     return launch_rollout_variant<false, 0, false>(p, roll, ring, g, stream);
   }
   if (kx == 4) return launch_rollout_variant<true, 4, false>(p, roll, ring, g, stream);

@@ -510,11 +510,12 @@ def test_multi_step_rollout_equals_single_iterations(name, k, rounds):
 
 
 @pytest.mark.parametrize("name,k", [("large_env_k_two", 3), ("full_obs_fifty", 4), ("k_all_others", 5),
-                                    ("fifteen_hundred_many_envs", 4), ("thirty_five_hundred_many_envs", 3)])
+                                    ("fifteen_hundred_many_envs", 4), ("thirty_five_hundred_many_envs", 3),
+                                    ("k_one_packed_envs", 5), ("k_two_odd_agent_count", 4), ("k_three", 6)])
 def test_multi_step_rollout_of_other_launch_shapes(name, k):
-    """Large-env layout, full observations, K > 8 (wd_rollout runs one launch per iteration) and
-    the multi-step kernel in 512- and 1024-thread workgroups: slices and final state against k
-    calls of wd_iterate."""
+    """Large-env layout, full observations, K > 8 (wd_rollout runs one launch per iteration), the
+    multi-step kernel in 512- and 1024-thread workgroups and its variants for K = 1, 2, 3: slices
+    and final state against k calls of wd_iterate."""
     import paper_2108_13976_amd as wd
 
     kw = dict(EDGE[name], seed=77)
@@ -783,6 +784,12 @@ EDGE = {
     # the any-K variant and full observations in 512-thread workgroups
     "k_seventeen_fifteen_hundred": dict(num_envs=3, num_agents=1500, num_taggers=90, grid_size=70, episode_length=4, obs_k=17),
     "full_obs_twelve_hundred": dict(num_envs=2, num_agents=1200, num_taggers=100, grid_size=40, episode_length=3, obs_mode=1),
+    # K = 1, 2, 3 compiled in (one env per 256-thread workgroup, whole 64-row chunks and a ragged last one)
+    "k_one_thousand_agents": dict(num_envs=310, num_agents=1000, num_taggers=100, grid_size=100, episode_length=3, obs_k=1),
+    "k_two_thousand_agents": dict(num_envs=305, num_agents=1000, num_taggers=100, grid_size=90, episode_length=3, obs_k=2),
+    "k_three_six_hundred_agents": dict(num_envs=190, num_agents=600, num_taggers=50, grid_size=70, episode_length=4, obs_k=3),
+    "k_one_packed_envs": dict(num_envs=37, num_agents=90, num_taggers=9, grid_size=30, episode_length=8, obs_k=1),
+    "k_two_odd_agent_count": dict(num_envs=21, num_agents=101, num_taggers=9, grid_size=30, episode_length=8, obs_k=2),
     # the large-env pair at the smallest agent count it is chosen for
     "large_env_pair_smallest": dict(num_envs=3, num_agents=384, num_taggers=30, grid_size=50, episode_length=10, obs_k=16),
     "odd_rewards": dict(num_envs=12, num_agents=25, num_taggers=5, grid_size=8, episode_length=20, obs_k=2,
