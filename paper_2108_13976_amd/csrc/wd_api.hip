@@ -140,6 +140,12 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
     p->lambda_c = 70.0f;
     p->lambda_max = 8.0f;
   }
+  if (p->K > 4) {  // more neighbours wanted: the 3x3 block of the first pass has to hold more agents
+    const float ks = float(p->K) / 4.0f;
+    p->lambda_c *= ks;
+    p->lambda_min *= ks;
+    p->lambda_max *= ks;
+  }
   p->div_N = wd::make_fastdiv(uint32_t(N));
   p->div_NG = wd::make_fastdiv(uint32_t(p->NG));
 

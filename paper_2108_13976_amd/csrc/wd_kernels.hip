@@ -53,9 +53,10 @@ __global__ __launch_bounds__(kWorkgroupSize) void init_start_positions_kernel(co
 
 // ----------------------------------------------------------------------------------
 // The env-per-team kernel: step, reset, or a whole iteration (sample + step + reset).
-// KX > 0: K == KX known at compile time.  KX == 0: K <= 8 at run time, KX == -2: K <= 16.  They keep
-// the neighbour list in registers and send rows through the LDS transpose.  KX == -1: any K,
-// by repeated selection, rows written directly (slow path).
+// KX > 0: K == KX known at compile time (1..8): the neighbour list and the row live in registers
+// and rows leave through the LDS transpose.  KX == 0: K <= 8 at run time, KX == -2: K <= 16 (the
+// list in registers, rows built in LDS).  KX == -1: any K, by repeated selection, rows written
+// directly (slow path).
 // ----------------------------------------------------------------------------------
 // Where one iteration's outputs go: the in-place buffers, or a slice of a roll-out's arrays.
 struct StepOut {
@@ -467,7 +468,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
         if constexpr (KX > 0) {
           if (have) write_row<KX, CN>(row, p, Lr, i, KX, t_frac);
         }
-        if constexpr (KX > 0 && KX <= 4) {
+        if constexpr (KX > 0) {
           constexpr int DD = 5 + 4 * KX;
           // Two flushes of 32 rows = 8 DD 16-byte pieces each (168 at K = 4): kFull stores that
           // every lane takes part in and one more for the first kRem lanes.  A whole chunk has
@@ -729,7 +730,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
 
 template <int WIDE, int KX, bool CN, bool BIG>
 __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
-    __attribute__((amdgpu_waves_per_eu((WIDE || BIG || KX <= 0) ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
+    __attribute__((amdgpu_waves_per_eu((WIDE || BIG || KX <= 0 || KX > 4) ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
                                                              const float* __restrict__ probs, uint32_t g_lo,
                                                              uint32_t g_hi) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -832,7 +833,7 @@ struct RollArgs {  // the one kernel argument of rollout_kernel
 
 template <int WIDE, int KX, bool CN>
 __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
-    __attribute__((amdgpu_waves_per_eu((WIDE || KX == 0) ? 4 : 8, 8))) void rollout_kernel(const RollArgs args) {
+    __attribute__((amdgpu_waves_per_eu((WIDE || KX == 0 || KX > 4) ? 4 : 8, 8))) void rollout_kernel(const RollArgs args) {
   extern __shared__ __align__(16) unsigned char smem[];
   // The loop reads its parameters from the kernel-argument segment (args is the only argument,
   // at offset 0) through a pointer that is opaque to the optimiser in every iteration: loads of
@@ -919,12 +920,12 @@ hipError_t launch_rollout_variant(const Params& p, const Roll& roll, const float
   return hipGetLastError();
 }
 
-// Which compiled variant serves K: 1..4 (K compiled in; 4 is the benchmark shape), 0 (K <= 8 at run time),
-// -2 (K <= 16), -1 (any K).
+// Which compiled variant serves K: 1..8 (K compiled in; 4 is the benchmark shape, the only one that every key
+// width and layout has), 0 (K <= 8 at run time), -2 (K <= 16), -1 (any K).
 int variant_of(const Params& p) {
   if (p.obs_mode == 1) return -1;
   if (p.K == 4) return 4;
-  if (p.K >= 1 && p.K <= 3 && !p.wide && !p.big) return p.K;  // compiled in as well, for 32-bit keys in the small layout
+  if (p.K >= 1 && p.K <= kMaxRegisterK && !p.wide && !p.big) return p.K;  // 32-bit keys in the small layout
   if (p.K <= kMaxRegisterK) return 0;
   if (p.K <= kMaxRegisterK2) return -2;
   return -1;
@@ -953,6 +954,10 @@ int variant_of(const Params& p) {
     if (!p.wide) {                                                                         \
       if (kx == 4 && p.compact_nbr) return fn<false, 4, true, false>(p, ##__VA_ARGS__);    \
       if (kx == 4) return fn<false, 4, false, false>(p, ##__VA_ARGS__);                    \
+      if (kx == 8) return fn<false, 8, false, false>(p, ##__VA_ARGS__);                    \
+      if (kx == 7) return fn<false, 7, false, false>(p, ##__VA_ARGS__);                    \
+      if (kx == 6) return fn<false, 6, false, false>(p, ##__VA_ARGS__);                    \
+      if (kx == 5) return fn<false, 5, false, false>(p, ##__VA_ARGS__);                    \
       if (kx == 3) return fn<false, 3, false, false>(p, ##__VA_ARGS__);                    \
       if (kx == 2) return fn<false, 2, false, false>(p, ##__VA_ARGS__);                    \
       if (kx == 1) return fn<false, 1, false, false>(p, ##__VA_ARGS__);                    \
@@ -979,6 +984,10 @@ hipError_t launch_rollout(const Params& p, const Roll& roll, const float* ring, 
   if (!p.wide) {
     if (kx == 4 && p.compact_nbr) return launch_rollout_variant<false, 4, true>(p, roll, ring, g, stream);
     if (kx == 4) return launch_rollout_variant<false, 4, false>(p, roll, ring, g, stream);
+    if (kx == 8) return launch_rollout_variant<false, 8, false>(p, roll, ring, g, stream);
+    if (kx == 7) return launch_rollout_variant<false, 7, false>(p, roll, ring, g, stream);
+    if (kx == 6) return launch_rollout_variant<false, 6, false>(p, roll, ring, g, stream);
+    if (kx == 5) return launch_rollout_variant<false, 5, false>(p, roll, ring, g, stream);
     if (kx == 3) return launch_rollout_variant<false, 3, false>(p, roll, ring, g, stream);
     if (kx == 2) return launch_rollout_variant<false, 2, false>(p, roll, ring, g, stream);
     if (kx == 1) return launch_rollout_variant<false, 1, false>(p, roll, ring, g, stream);

@@ -511,10 +511,11 @@ def test_multi_step_rollout_equals_single_iterations(name, k, rounds):
 
 @pytest.mark.parametrize("name,k", [("large_env_k_two", 3), ("full_obs_fifty", 4), ("k_all_others", 5),
                                     ("fifteen_hundred_many_envs", 4), ("thirty_five_hundred_many_envs", 3),
-                                    ("k_one_packed_envs", 5), ("k_two_odd_agent_count", 4), ("k_three", 6)])
+                                    ("k_one_packed_envs", 5), ("k_two_odd_agent_count", 4), ("k_three", 6),
+                                    ("k_eight", 5), ("k_seven_packed_envs", 4)])
 def test_multi_step_rollout_of_other_launch_shapes(name, k):
     """Large-env layout, full observations, K > 8 (wd_rollout runs one launch per iteration), the
-    multi-step kernel in 512- and 1024-thread workgroups and its variants for K = 1, 2, 3: slices
+    multi-step kernel in 512- and 1024-thread workgroups and its variants for other K than 4: slices
     and final state against k calls of wd_iterate."""
     import paper_2108_13976_amd as wd
 
@@ -790,6 +791,10 @@ EDGE = {
     "k_three_six_hundred_agents": dict(num_envs=190, num_agents=600, num_taggers=50, grid_size=70, episode_length=4, obs_k=3),
     "k_one_packed_envs": dict(num_envs=37, num_agents=90, num_taggers=9, grid_size=30, episode_length=8, obs_k=1),
     "k_two_odd_agent_count": dict(num_envs=21, num_agents=101, num_taggers=9, grid_size=30, episode_length=8, obs_k=2),
+    # K = 5 .. 8 compiled in
+    "k_six_thousand_agents": dict(num_envs=305, num_agents=1000, num_taggers=100, grid_size=100, episode_length=3, obs_k=6),
+    "k_seven_packed_envs": dict(num_envs=30, num_agents=120, num_taggers=12, grid_size=25, episode_length=8, obs_k=7),
+    "k_five_odd_agent_count": dict(num_envs=11, num_agents=203, num_taggers=20, grid_size=45, episode_length=8, obs_k=5),
     # the large-env pair at the smallest agent count it is chosen for
     "large_env_pair_smallest": dict(num_envs=3, num_agents=384, num_taggers=30, grid_size=50, episode_length=10, obs_k=16),
     "odd_rewards": dict(num_envs=12, num_agents=25, num_taggers=5, grid_size=8, episode_length=20, obs_k=2,
