@@ -296,12 +296,6 @@ __device__ __forceinline__ void insert_key(unsigned long long (&keys)[KT], unsig
   keys[0] = keys[0] < key ? keys[0] : key;
 }
 
-// The K smallest (squared distance, index) keys among the other live agents, exactly.
-// Scans the (2r+1)^2 buckets around the agent's own; every agent outside that block is
-// beyond a side of the block, so once the K-th key is nearer than the nearest cell beyond any
-// side (or the block covers the grid) no unseen agent can enter the list; otherwise r doubles
-// and only the buckets that the wider block adds, and that are near enough to matter, are scanned.  The agent's own entry is left
-// out by splitting its bucket row at its slot.
 // dx*dx + dy*dy of a packed pair of 16-bit differences, in one instruction (the form without
 // an accumulator register, which the compiler otherwise zeroes for every candidate)
 __device__ __forceinline__ uint32_t squared_length(short2v d) {
@@ -352,6 +346,13 @@ __device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, ui
   }
 }
 
+// The K smallest (squared distance, index) keys among the other live agents, exactly.
+// Scans the (2r+1)^2 buckets around the agent's own; every agent outside that block is
+// beyond a side of the block, so once the K-th key is nearer than the nearest cell beyond any
+// side (or the block covers the grid) no unseen agent can enter the list; otherwise r doubles
+// and only the buckets that the wider block adds, and that are near enough to matter, are
+// scanned.  The agent's own entry is left out by splitting its bucket row at its slot.  FIRST: give
+// up (return false) when the first ring does not settle the list; the caller queues the agent.
 template <int WIDE, int KT, bool FIRST>
 __device__ __forceinline__ bool nearest_keys(typename SortedList<WIDE>::Key (&keys)[KT], int K, int x, int y,
                                              uint32_t self_slot, const Buckets bk, int ib,
