@@ -304,6 +304,8 @@ __device__ __forceinline__ uint32_t squared_length(short2v d) {
   return r;
 }
 
+// The agents in slots [qb, qe) of the bucket-sorted list as candidates for the key list of the agent
+// at (x, y); one overload per key form.
 template <int KT>
 __device__ __forceinline__ void scan_range(unsigned long long (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y,
                                            int ib, const SortedList<kKeys64>& sorted) {
