@@ -34,6 +34,10 @@
  *     checkpoint without it, calls wd_set_step (with the step counter to go on
  *     from): the next call then writes every row whole.  Rows recorded through
  *     wd_rollout_buffers are always written whole.
+ *   - The global step g reaches the kernels as a launch argument.  A HIP graph
+ *     captured around calls of this library therefore replays the random numbers
+ *     of the steps it was captured at; to run many iterations with one launch,
+ *     use wd_rollout.
  *   - Random numbers are Philox4x32-10 blocks keyed by (seed, global env id,
  *     agent, global step g, stream), so results do not depend on launch shape,
  *     and a run over envs [a, b) with env_offset = a reproduces those envs of the
