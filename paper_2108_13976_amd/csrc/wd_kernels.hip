@@ -489,16 +489,28 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
                 for (int d = 0; d < DD; ++d) dst[d] = row[d];
               }
               wave_sync_lds();
-              float4 v[kFull + 1];
+              if constexpr (kFull == 2) {
+                // (K = 3, 4, written out: this form keeps the multi-step kernel's loop to the
+                // fewest spilled registers)
+                const float4 a = st4[0], b = st4[kWaveSize];
+                float4 c = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                if (lane < kRem) c = st4[2 * kWaveSize];
+                if (kWhole || h * kPieces < limit) out4[h * kPieces] = a;
+                if (kWhole || h * kPieces + kWaveSize < limit) out4[h * kPieces + kWaveSize] = b;
+                if (lane < kRem && (kWhole || h * kPieces + 2 * kWaveSize < limit)) out4[h * kPieces + 2 * kWaveSize] = c;
+              } else {
+                // (the last load is unconditional: lanes from kRem on read past the staged rows,
+                // still inside LDS, and store nothing; a predicated load makes the compiler emit
+                // the whole sequence twice, once per half of the lanes)
+                float4 v[kFull + 1];
 #pragma unroll
-              for (int m = 0; m < kFull; ++m) v[m] = st4[m * kWaveSize];
-              v[kFull] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-              if (kRem > 0 && lane < kRem) v[kFull] = st4[kFull * kWaveSize];
+                for (int m = 0; m <= kFull; ++m) v[m] = st4[m * kWaveSize];
 #pragma unroll
-              for (int m = 0; m < kFull; ++m)
-                if (kWhole || h * kPieces + m * kWaveSize < limit) out4[h * kPieces + m * kWaveSize] = v[m];
-              if (kRem > 0 && lane < kRem && (kWhole || h * kPieces + kFull * kWaveSize < limit))
-                out4[h * kPieces + kFull * kWaveSize] = v[kFull];
+                for (int m = 0; m < kFull; ++m)
+                  if (kWhole || h * kPieces + m * kWaveSize < limit) out4[h * kPieces + m * kWaveSize] = v[m];
+                if (kRem > 0 && lane < kRem && (kWhole || h * kPieces + kFull * kWaveSize < limit))
+                  out4[h * kPieces + kFull * kWaveSize] = v[kFull];
+              }
               wave_sync_lds();
             }
           };
