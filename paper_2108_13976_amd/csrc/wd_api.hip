@@ -132,9 +132,11 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   if (G > 1) mul_max = uint32_t(std::min<uint64_t>(65536u, ((uint64_t(side) << 16) - 1) / uint64_t(G - 1)));
   p->bucket_mul_max = mul_max;
   p->bucket_scale = float(65536.0 / double(G));
-  // target live agents per bucket: about 5 in an env of a hundred agents, 1.5 at a thousand
+  // target live agents per bucket: about 5 in an env of a hundred agents, 2.2 from five hundred on
+  // (with every agent of the headline shape in play: 80.2 us per iteration at 1.5 .. 2.0, where the
+  // size of the bucket table sets the width, 78.2 at 2.2, 78.9 at 2.6, 80.9 at 3.0)
   p->lambda_c = 47.0f;
-  p->lambda_min = 1.5f;
+  p->lambda_min = 2.2f;
   p->lambda_max = 5.0f;
   if (ts >= N) {  // a lane per agent: one search round, so fewer, fuller buckets shorten the chain
     p->lambda_c = 70.0f;
