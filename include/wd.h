@@ -30,9 +30,9 @@
  *     in place: Sec. 4.2).  The row of an agent that was already out of play
  *     before a step differs from the row the previous call left in `obs` in its
  *     time feature only, and a step may rewrite just that element.  A caller that
- *     overwrites `obs` between calls, or restores the other arrays from a
- *     checkpoint without it, calls wd_set_step (with the step counter to go on
- *     from): the next call then writes every row whole.  Rows recorded through
+ *     overwrites `obs` or the state arrays between calls (a restored checkpoint,
+ *     an agent taken out of play by hand) calls wd_set_step (with the step
+ *     counter to go on from): the next call then writes every row whole.  Rows recorded through
  *     wd_rollout_buffers are always written whole.
  *   - The global step g reaches the kernels as a launch argument.  A HIP graph
  *     captured around calls of this library therefore replays the random numbers
