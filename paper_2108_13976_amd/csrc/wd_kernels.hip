@@ -499,12 +499,13 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
                 if (kWhole || h * kPieces + kWaveSize < limit) out4[h * kPieces + kWaveSize] = b;
                 if (lane < kRem && (kWhole || h * kPieces + 2 * kWaveSize < limit)) out4[h * kPieces + 2 * kWaveSize] = c;
               } else {
-                // (the last load is unconditional: lanes from kRem on read past the staged rows,
-                // still inside LDS, and store nothing; a predicated load makes the compiler emit
-                // the whole sequence twice, once per half of the lanes)
+                // (the last load is unconditional, lanes from kRem on re-read the last staged piece
+                // and store nothing: a predicated load makes the compiler emit the whole sequence
+                // twice, once per half of the lanes)
                 float4 v[kFull + 1];
 #pragma unroll
-                for (int m = 0; m <= kFull; ++m) v[m] = st4[m * kWaveSize];
+                for (int m = 0; m < kFull; ++m) v[m] = st4[m * kWaveSize];
+                v[kFull] = reinterpret_cast<const float4*>(stage)[min(kFull * kWaveSize + lane, kPieces - 1)];
 #pragma unroll
                 for (int m = 0; m < kFull; ++m)
                   if (kWhole || h * kPieces + m * kWaveSize < limit) out4[h * kPieces + m * kWaveSize] = v[m];
