@@ -639,6 +639,28 @@ def test_random_configuration(seed):
     lockstep(kw, steps, kw["seed"] % 1000, fused=bool(seed & 1))
 
 
+def test_many_more_random_configurations():
+    """A batch of further random configurations in one test (WD_EXTRA_SEEDS of them, 240 by default):
+    every third with 384 .. 3073 agents in a few envs, the shapes that run in the large-env pair of
+    kernels or in wide workgroups, with K from 0 to 16."""
+    import os
+
+    count = int(os.environ.get("WD_EXTRA_SEEDS", "240"))
+    for seed in range(5000, 5000 + count):
+        kw = random_configuration(seed)
+        large = seed % 3 == 0
+        if large:
+            rng = np.random.default_rng(77000 + seed)
+            n = int(rng.choice([384, 385, 640, 700, 1023, 1024, 1025, 1300, 2050, 3073]))
+            kw.update(num_agents=n, num_taggers=int(rng.integers(1, max(2, n // 8))), num_envs=int(rng.integers(1, 6)),
+                      episode_length=int(rng.integers(1, 5)), obs_k=int(rng.choice([0, 1, 2, 3, 4, 5, 6, 8, 9, 16])))
+            kw.pop("obs_mode", None)
+        try:
+            lockstep(kw, 2 * kw["episode_length"] + 3, kw["seed"] % 1000, fused=bool(seed & 1), sharded=4 if large else 0)
+        except AssertionError as err:
+            raise AssertionError(f"seed {seed}, configuration {kw}: {err}") from err
+
+
 @pytest.mark.parametrize("seed", range(100, 116))
 def test_random_configuration_multi_step(seed):
     """wd_rollout on a random configuration: every recorded slice and the final state against one
