@@ -80,6 +80,98 @@ bool probs_aligned(const wd::Params& p, const void* probs) {
   return (reinterpret_cast<uintptr_t>(probs) & (p.vec4 ? 15u : 3u)) == 0;
 }
 
+// LDS map of the strip variant: per team a kept part (positions by index, scalars, strip edges),
+// an X part (the padded strip-sorted list and the table of bin starts) that the row staging area
+// overlays once the neighbour search is done, and a Y part (slots, tag keys, credits) that the
+// retry queue and the neighbour lists overlay once the rewards are out.  The columns are as narrow
+// as the table's share of LDS allows without costing the launch a workgroup per CU.
+bool plan_strip_layout(const wd_config& c, wd::Params* p) {
+  const int N = c.num_agents, G = c.grid_size, K = p->K;
+  const int64_t NPAD = p->NPAD;
+  const int tpw = p->teams_per_wg;
+  // strips about 1.5 expected K-th-neighbour distances tall: G / R = 1.5 G sqrt(K / (pi n))
+  p->strip_scale = float(std::sqrt(3.14159265358979 / double(K)) / 1.5);
+  // the own window overhangs the list by up to its half width, and the window of a neighbouring strip then sits beyond it
+  p->pad_l = wd::strip_pad(K);
+  p->pad_r = wd::strip_pad(K);
+  const int64_t slots = NPAD + p->pad_l + p->pad_r;
+  const int r_want = std::min<int64_t>(G, int64_t(std::ceil(double(p->strip_scale) * std::sqrt(double(N)))) + 1);
+  const int64_t waves = p->wg_size / wd::kWaveSize;
+  int srl = 5;  // rows per wave and flush of the staging area: 32, or 16 if an env does not fit otherwise
+  const int64_t nbr_bytes = align16((K == 4 && N < 1024) ? 5 * NPAD : 2 * NPAD * K);
+  const int64_t retry_bytes = align16(2 * NPAD);
+  auto layout = [&](int cshift, bool commit) -> int64_t {
+    const int64_t stage = waves * (int64_t(1) << srl) * p->D * 4;
+    const int C = ((G - 1) >> cshift) + 1;
+    const int64_t entries = int64_t(r_want) * C + 1;
+    int64_t off = 0;
+    auto take = [&off](int64_t bytes) {
+      const int64_t at = off;
+      off = align16(off + bytes);
+      return int32_t(at);
+    };
+    const int32_t o_pl = take(4 * NPAD), o_misc = take(128), o_edges = take(2 * (r_want + 2));
+    const int64_t keep = off;
+    off = 0;
+    const int32_t o_sorted = take(4 * slots), o_id = take(2 * slots), o_t = take(2 * (entries + 1));
+    const int64_t x_stride = off;
+    off = 0;
+    const int32_t o_slot = take(2 * NPAD), o_best = take(4 * NPAD), o_credits = take(4ll * c.num_taggers);
+    const int64_t y_tables = off;
+    const int64_t x_area = x_stride * tpw;
+    int64_t x_span, y_stride;
+    if (tpw == 1) {
+      x_span = x_area;
+      y_stride = align16(std::max<int64_t>(std::max<int64_t>(y_tables, retry_bytes + nbr_bytes), stage + nbr_bytes - x_area));
+    } else {
+      x_span = std::max<int64_t>(x_area, stage);
+      y_stride = align16(std::max<int64_t>(y_tables, retry_bytes + nbr_bytes));
+    }
+    const int64_t total = keep * tpw + x_span + y_stride * tpw;
+    if (commit) {
+      p->cshift = cshift;
+      p->strip_C = C;
+      p->strip_rmax = r_want;
+      p->off_pl = o_pl;
+      p->off_misc = o_misc;
+      p->off_edges = o_edges;
+      p->keep_stride = int32_t(keep);
+      p->off_sorted = o_sorted + 4 * p->pad_l;
+      p->off_sorted_id = o_id + 2 * p->pad_l;
+      p->off_starts = o_t;
+      p->x_stride = int32_t(x_stride);
+      p->off_slot = o_slot;
+      p->off_best = o_best;
+      p->off_credits = o_credits;
+      p->off_counts = 0;
+      p->off_retry = 0;
+      p->compact_nbr = (K == 4 && N < 1024) ? 1 : 0;
+      p->stage_rows_log2 = srl;
+      p->y_stride = int32_t(y_stride);
+      p->off_nbr = int32_t(y_stride - nbr_bytes);
+      p->x_base = int32_t(keep * tpw);
+      p->y_base = int32_t(p->x_base + x_span);
+      p->lds_bytes = int32_t(std::min<int64_t>(total, INT32_MAX));
+      p->g_stride_image = p->y_base;
+    }
+    return total;
+  };
+  // the share of LDS that keeps as many workgroups on a CU as the coarsest columns would
+  int64_t total_min = layout(15, false);
+  if (total_min > kLdsLimitBytes) {
+    srl = 4;
+    total_min = layout(15, false);
+  }
+  if (total_min > kLdsLimitBytes) return false;
+  const int64_t by_threads = std::max<int64_t>(1, 2048 / p->wg_size);
+  const int64_t wgs = std::max<int64_t>(1, std::min<int64_t>(by_threads, kLdsLimitBytes / total_min));
+  const int64_t budget = kLdsLimitBytes / wgs;
+  int cshift = 0;
+  while (cshift < 15 && layout(cshift, false) > budget) ++cshift;
+  layout(cshift, true);
+  return true;
+}
+
 // Launch geometry and LDS map of the env-per-team kernels.  Returns false if an env does
 // not fit one workgroup's LDS.
 bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
@@ -179,6 +271,10 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   p->wide = flagged32 ? 2 : (narrow ? 0 : 1);
   const int key_bytes = narrow ? 4 : 8;
   const bool register_path = c.obs_mode == WD_OBS_PARTIAL && p->K <= wd::kMaxRegisterK2;
+  // The variants with 32-bit keys and K compiled in (small layout) sort by strip and column
+  // instead of by square bucket (wd_dev_strips.h).
+  p->strips = (!big && p->wide == 0 && c.obs_mode == WD_OBS_PARTIAL && p->K >= 1 && p->K <= wd::kMaxRegisterK) ? 1 : 0;
+  if (p->strips) return plan_strip_layout(c, p);
 
   int64_t off = 0;
   auto take = [&off](int64_t bytes) {

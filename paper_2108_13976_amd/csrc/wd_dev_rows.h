@@ -9,6 +9,7 @@ namespace wd {
 namespace dev {
 
 constexpr int kMiscBucketMul = 22, kMiscBucketSide = 23;  // misc[] slots that carry the bucket geometry to big_obs_kernel
+constexpr int kMiscQueue2 = 24;  // misc[] slot: agents waiting for the block search of the strip variant
 constexpr uint32_t kCompactNone = 1023u;  // "no neighbour" in the compact 10-bit form
 
 // One observation row (own features + K neighbour slots) written to `row` (registers, LDS

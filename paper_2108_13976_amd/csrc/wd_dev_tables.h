@@ -14,9 +14,10 @@ namespace dev {
 // position and index of the live agents, grouped by bucket.
 //   NARROW (32-bit keys): positions x | y << 16 in one array, 16-bit indices in another; the
 //     squared distance of a candidate is one packed 16-bit subtract and one two-element dot
-//     product.  A runner tagged in this step is marked by adding `dead_dx` to its x: that
+//     product.  A runner tagged in this step is marked by adding `dead_dx` to its y: that
 //     puts its squared distance from any agent on the grid into the band whose key has bit
-//     31 set, above every live key, so it sorts last and reads as "no neighbour".
+//     31 set, above every live key, so it sorts last and reads as "no neighbour" (its x stays
+//     what it was: the strip-sorted list is ordered by it).
 //   WIDE = 1 (64-bit keys): entries (x | y << 16 | dead bit, index).
 //   WIDE = 2 (32-bit keys that need all 32 bits, so that no band is left for the dead mark):
 //     arrays as in the narrow form; a tagged runner is marked in bit 15 of its index, which
@@ -44,8 +45,8 @@ struct SortedList<kKeys31> {
     pos[q] = uint32_t(x) | (uint32_t(y) << 16);
     id[q] = uint16_t(i);
   }
-  __device__ __forceinline__ void mark_dead(uint32_t q) const { pos[q] += uint32_t(dead_dx); }
-  __device__ __forceinline__ bool dead(const Ent& e) const { return int(e.pos & 0xFFFFu) >= dead_dx; }
+  __device__ __forceinline__ void mark_dead(uint32_t q) const { pos[q] += uint32_t(dead_dx) << 16; }
+  __device__ __forceinline__ bool dead(const Ent& e) const { return int(e.pos >> 16) >= dead_dx; }
   static __device__ __forceinline__ int x(const Ent& e) { return int(e.pos & 0xFFFFu); }
   static __device__ __forceinline__ int y(const Ent& e) { return int(e.pos >> 16); }
 };
@@ -185,7 +186,7 @@ struct TeamLds {
   uint16_t* nbr;     // [NPAD][K] neighbour indices; overlays the tail of slot/best/credits/counts
   uint32_t* nbr_lo;  // compact form for K = 4, N < 1024: ids 0..2 and two bits of id 3 per agent,
   uint8_t* nbr_hi;   // and the other eight bits of id 3 (same memory as nbr)
-  int32_t* misc;     // [0] tags this step, [1] t after the call, [2] rows to be written, [3] length of retry[], [4..19] scan scratch, [20..21] of the first team: workgroup votes, [22..23] bucket geometry for big_obs_kernel
+  int32_t* misc;     // [0] tags this step, [1] t after the call, [2] rows to be written, [3] length of retry[], [4..19] scan scratch (strip variant, during the search: slots waiting for the block search), [20..21] of the first team: workgroup votes, [22..23] bucket geometry for big_obs_kernel, [24] length of that waiting list
   uint16_t* edges;   // [nbx + 1] first cell of each bucket coordinate; edges[nbx] = G
   SortedList<WIDE> sorted;  // [NPAD + pad] the live agents, grouped by bucket
   uint16_t* slot;    // [NPAD] where agent i sits in `sorted`

@@ -13,6 +13,7 @@
 
 #include "wd_dev_common.h"
 #include "wd_dev_rows.h"
+#include "wd_dev_strips.h"
 #include "wd_dev_tables.h"
 #include "wd_internal.h"
 
@@ -88,16 +89,22 @@ struct LoopState {
   bool last;      // the in-place state arrays are written in this iteration
 };
 
-template <int WIDE, int KX, bool CN, bool BIG, bool LOOPED>
+template <int WIDE, int KX, bool CN, bool BIG, bool LOOPED, bool ONE>
 __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, const int mode,
                                          const float* __restrict__ probs, uint32_t g_lo, uint32_t g_hi,
                                          unsigned char* smem, const int tid, LoopState& ls) {
   using SL = SortedList<WIDE>;
   using Key = typename SL::Key;
+  // 32-bit keys with K compiled in, small layout: the live agents are sorted by strip and column
+  // and the neighbour search reads fixed windows of that list; the other variants sort by
+  // square buckets and search bucket rings
+  constexpr bool STRIP = WIDE == kKeys31 && !BIG && KX > 0;
+  // ONE: the launch has one team per workgroup, so everything that depends on the team (table
+  // addresses, the env's scalars, the strip geometry) is uniform and lives in scalar registers
   const int ts = 1 << p.ts_log2;
-  const int team = tid >> p.ts_log2;
-  const int lt = tid & (ts - 1);
-  const int e0 = blockIdx.x * p.teams_per_wg;
+  const int team = ONE ? 0 : tid >> p.ts_log2;
+  const int lt = ONE ? tid : tid & (ts - 1);
+  const int e0 = ONE ? int(blockIdx.x) : blockIdx.x * p.teams_per_wg;
   const int e = e0 + team;
   const int N = p.N, N_tag = p.N_tag, G = p.G, NG = p.NG;
   const int K = KX > 0 ? KX : p.K;
@@ -124,8 +131,16 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
   bool out_act = false;  // this team's env gets new observation rows
   int t_out = t_in;
   bool done_now = done_in != 0;
-  Buckets bk = choose_buckets(p, nlr_in + N_tag);
-  if (lt == 0) L.misc[3] = 0;  // every mode passes a barrier before the neighbour search appends
+  Buckets bk = {};
+  Strips sg = {};
+  if constexpr (STRIP)
+    sg = choose_strips(p, nlr_in + N_tag);
+  else
+    bk = choose_buckets(p, nlr_in + N_tag);
+  if (lt == 0) {  // every mode passes a barrier before the neighbour search appends
+    L.misc[3] = 0;
+    L.misc[kMiscQueue2] = 0;
+  }
   // Two workgroup-wide votes: some env of the workgroup is being reset; some env gets no new
   // rows.  Inside the roll-out loop (LOOPED) they are flags in the first team's scalars, cleared
   // here, set before a barrier that the code needs anyway and read after it; the one-step
@@ -138,8 +153,12 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
 
   if (stepping) {
     if (step_act) {
-      for (int j = lt; j < p.nb_cap; j += ts) L.counts[j] = 0u;
-      for (int j = lt; j <= bk.nbx; j += ts) L.edges[j] = uint16_t(min(bucket_first_cell(j, bk), G));
+      if constexpr (STRIP) {
+        strip_prepare(p, L, sg, lt, ts);
+      } else {
+        for (int j = lt; j < p.nb_cap; j += ts) L.counts[j] = 0u;
+        for (int j = lt; j <= bk.nbx; j += ts) L.edges[j] = uint16_t(min(bucket_first_cell(j, bk), G));
+      }
       for (int j = lt; j < N_tag; j += ts) L.credits[j] = 0;
       if (lt == 0) L.misc[0] = 0;
     }
@@ -190,7 +209,12 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
             x[j] = nx;
             y[j] = ny;
             packed[j] = pack_pos(nx, ny, is_live) | (is_live ? 0u : kStaleBit);
-            if (is_live) atomicAdd(&L.counts[bucket_of(nx, ny, bk)], 1u);
+            if (is_live) {
+              if constexpr (STRIP)
+                strip_count(reinterpret_cast<uint32_t*>(L.starts), strip_bin(nx, ny, sg));
+              else
+                atomicAdd(&L.counts[bucket_of(nx, ny, bk)], 1u);
+            }
             L.best[i0 + j] = key_none<Key>();
           }
           if (moved && write_state) {
@@ -203,12 +227,18 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
     }
     __syncthreads();
     WD_NEW_PHASE();
-    scan_and_scatter<WIDE>(p, L, step_act, lt, ts, bk);
+    if constexpr (STRIP)
+      strip_scan_and_scatter(p, L, step_act, lt, ts, sg);
+    else
+      scan_and_scatter<WIDE>(p, L, step_act, lt, ts, bk);
     WD_NEW_PHASE();
 
     // ---- tag check, from the tagger's side: runners in range get the smallest
     //      (distance, tagger) key; min is order-independent, so the result is unique ----
-    if (step_act && p.tag_r2 >= 0) {
+    if constexpr (STRIP) {
+      if (step_act && p.tag_r2 >= 0)
+        for (int i = lt; i < N_tag; i += ts) strip_tag_scan(p, L, sg, i);
+    } else if (step_act && p.tag_r2 >= 0) {
       for (int i = lt; i < N_tag; i += ts) {
         const uint32_t me = L.pl[i];
         const int x = pos_x_of(me), y = pos_y_of(me);
@@ -311,9 +341,14 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
     }
     if (any_reset) {
       if (reset_act) {
-        bk = choose_buckets(p, N);
-        for (int j = lt; j < p.nb_cap; j += ts) L.counts[j] = 0u;
-        for (int j = lt; j <= bk.nbx; j += ts) L.edges[j] = uint16_t(min(bucket_first_cell(j, bk), G));
+        if constexpr (STRIP) {
+          sg = choose_strips(p, N);
+          strip_prepare(p, L, sg, lt, ts);
+        } else {
+          bk = choose_buckets(p, N);
+          for (int j = lt; j < p.nb_cap; j += ts) L.counts[j] = 0u;
+          for (int j = lt; j <= bk.nbx; j += ts) L.edges[j] = uint16_t(min(bucket_first_cell(j, bk), G));
+        }
       }
       __syncthreads();
       if (reset_act) {
@@ -333,7 +368,12 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
               y[j] = min(max(y[j], 0), G - 1);
               packed[j] = pack_pos(x[j], y[j], j < n);
               ones[j] = 1;
-              if (j < n) atomicAdd(&L.counts[bucket_of(x[j], y[j], bk)], 1u);
+              if (j < n) {
+                if constexpr (STRIP)
+                  strip_count(reinterpret_cast<uint32_t*>(L.starts), strip_bin(x[j], y[j], sg));
+                else
+                  atomicAdd(&L.counts[bucket_of(x[j], y[j], bk)], 1u);
+              }
             }
             if (write_state) {
               store4(p.pos_x, a0, n, vec, x);
@@ -354,7 +394,10 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
         out_act = true;
       }
       __syncthreads();
-      scan_and_scatter<WIDE>(p, L, reset_act, lt, ts, bk);
+      if constexpr (STRIP)
+        strip_scan_and_scatter(p, L, reset_act, lt, ts, sg);
+      else
+        scan_and_scatter<WIDE>(p, L, reset_act, lt, ts, bk);
     }
   }
 
@@ -407,7 +450,50 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
     };
     const bool search = out_act && K > 0;
     if (LOOPED && valid && !out_act && lt == 0) wg_flags[1] = 1;  // read after the two barriers below
-    if (search) {
+    if constexpr (STRIP) {
+      // the fixed windows of the strip-sorted list; what they do not settle is queued
+      if (search) {
+        const int n_sorted = int(L.starts[sg.R * sg.C]);
+        for (int q = lt; q < n_sorted; q += ts) {
+          const uint32_t me = L.sorted.pos[q];
+          if (int(me >> 16) < p.dead_dx) {  // not tagged in this step
+            Key keys[KT];
+            if (strip_window_search<KX, strip_half_own(KX), strip_half_adj(KX), 0, false>(
+                    keys, me, q, 0, sg, p.idx_bits, n_sorted, p.pad_l, L.sorted.pos, L.sorted.id, L.starts, L.edges))
+              put_neighbours(L.sorted.id[q], keys);
+            else
+              L.retry[atomicAdd(&L.misc[3], 1)] = uint16_t(q);
+          }
+        }
+      }
+      // second try, wider windows and two more strips, for the few that are queued; what is left
+      // after that (hardly ever anything) waits in a short queue of its own for the block search
+      __syncthreads();
+      if (search) {
+        const int n_sorted = int(L.starts[sg.R * sg.C]);
+        const int n_retry = L.misc[3];
+        uint16_t* const queue2 = reinterpret_cast<uint16_t*>(L.misc + 4);  // (the scan scratch, idle by now)
+        // (two lanes per agent: lane 2 j takes what lies below agent j's slot, lane 2 j + 1 what lies above)
+        for (int j = lt >> 1; j < n_retry; j += ts >> 1) {
+          const int q = L.retry[j];
+          const uint32_t me = L.sorted.pos[q];
+          Key keys[KT];
+          bool ok = strip_window_search<KX, strip_half_own2(KX), strip_half_adj2(KX), strip_half_far2(KX), true>(
+              keys, me, q, lt & 1, sg, p.idx_bits, n_sorted, p.pad_l, L.sorted.pos, L.sorted.id, L.starts, L.edges);
+          if (lt & 1) continue;  // the even lane goes on for both
+          if (!ok) {
+            const int at = atomicAdd(&L.misc[kMiscQueue2], 1);
+            if (at < kStripQueue2) {
+              queue2[at] = uint16_t(q);
+            } else {  // the queue is full: search here and now
+              strip_block_search<KX>(keys, me, uint32_t(q), sg, p.idx_bits, G, L.sorted.pos, L.sorted.id, L.starts, L.edges);
+              ok = true;
+            }
+          }
+          if (ok) put_neighbours(L.sorted.id[q], keys);
+        }
+      }
+    } else if (search) {
       const int n_sorted = int(L.starts[p.nb_cap]);
       for (int q = lt; q < n_sorted; q += ts) {
         const Ent ent = L.sorted.get(q);
@@ -423,12 +509,16 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
     }
     __syncthreads();
     if (search) {
-      const int n_retry = L.misc[3];
+      const int n_retry = STRIP ? min(L.misc[kMiscQueue2], kStripQueue2) : L.misc[3];
+      const uint16_t* const queue = STRIP ? reinterpret_cast<const uint16_t*>(L.misc + 4) : L.retry;
       for (int j = lt; j < n_retry; j += ts) {
-        const uint32_t q = L.retry[j];
+        const uint32_t q = queue[j];
         const Ent ent = L.sorted.get(q);
         Key keys[KT];
-        nearest_keys<WIDE, KT, false>(keys, K, SL::x(ent), SL::y(ent), q, bk, p.idx_bits, L.sorted, L.starts, L.edges);
+        if constexpr (STRIP)
+          strip_block_search<KX>(keys, ent.pos, q, sg, p.idx_bits, G, L.sorted.pos, L.sorted.id, L.starts, L.edges);
+        else
+          nearest_keys<WIDE, KT, false>(keys, K, SL::x(ent), SL::y(ent), q, bk, p.idx_bits, L.sorted, L.starts, L.edges);
         put_neighbours(ent.id, keys);
       }
     }
@@ -446,7 +536,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
     // instruction writes a contiguous run.
     const int wave = tid >> 6, lane = tid & (kWaveSize - 1);
     const int D = KX > 0 ? 5 + 4 * KX : p.D;
-    const int rows_total = min(p.teams_per_wg, p.E - e0) * N;
+    const int rows_total = ONE ? N : min(p.teams_per_wg, p.E - e0) * N;
     float* const obs_wg = out.obs + int64_t(e0) * N * D;
     if (all_out) {
       const int srl = p.stage_rows_log2, stage_rows = 1 << srl, flushes = kWaveSize >> srl;
@@ -458,7 +548,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
         const int Rr = R0 + lane;
         const bool have = Rr < rows_total;
         int tm = 0, i = Rr;
-        if (p.teams_per_wg > 1) {
+        if (!ONE && p.teams_per_wg > 1) {
           tm = int(fastdiv(uint32_t(Rr), p.div_N));
           i = Rr - tm * N;
         }
@@ -741,7 +831,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
 #undef p
 #undef WD_NEW_PHASE
 
-template <int WIDE, int KX, bool CN, bool BIG>
+template <int WIDE, int KX, bool CN, bool BIG, bool ONE>
 __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
     __attribute__((amdgpu_waves_per_eu((WIDE || BIG || KX <= 0 || KX > 4) ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
                                                              const float* __restrict__ probs, uint32_t g_lo,
@@ -749,7 +839,7 @@ __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
   extern __shared__ __align__(16) unsigned char smem[];
   LoopState ls = {0, 0, false, true};
   // p is the first kernel argument: offset 0 of the kernel-argument segment
-  env_body<WIDE, KX, CN, BIG, false>((KernargParams)__builtin_amdgcn_kernarg_segment_ptr(),
+  env_body<WIDE, KX, CN, BIG, false, ONE>((KernargParams)__builtin_amdgcn_kernarg_segment_ptr(),
                                      StepOut{p.action, p.reward, p.obs, p.done_log}, mode, probs, g_lo, g_hi, smem,
                                      int(threadIdx.x), ls);
 }
@@ -844,7 +934,7 @@ struct RollArgs {  // the one kernel argument of rollout_kernel
   uint64_t g0;
 };
 
-template <int WIDE, int KX, bool CN>
+template <int WIDE, int KX, bool CN, bool ONE>
 __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
     __attribute__((amdgpu_waves_per_eu((WIDE || KX == 0 || KX > 4) ? 4 : 8, 8))) void rollout_kernel(const RollArgs args) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -873,7 +963,7 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
       if (roll.obs) out.obs = roll.obs + s * EN * p.D;
     }
     const uint64_t g = a.g0 + uint64_t(s);
-    env_body<WIDE, KX, CN, false, true>((KernargParams)ak, out, kModeIterate, a.ring + int64_t(ring_at) * EN * kNumActions, uint32_t(g),
+    env_body<WIDE, KX, CN, false, true, ONE>((KernargParams)ak, out, kModeIterate, a.ring + int64_t(ring_at) * EN * kNumActions, uint32_t(g),
                                   uint32_t(g >> 32), smem, tid, ls);
     ring_at = ring_at + 1 == roll.ring_len ? 0 : ring_at + 1;
     __syncthreads();  // this step's state and LDS use are complete before the next step starts
@@ -890,10 +980,17 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
   if (roll.obs) copy_words(roll.obs + (last + first) * p.D, p.obs + first * p.D, count * p.D);
 }
 
-template <int WIDE, int KX, bool CN, bool BIG>
+// (one team per workgroup gets the variant whose team-dependent values are uniform, where one is compiled)
+template <int WIDE, int KX, bool BIG>
+constexpr bool kHasOneTeamVariant = WIDE == 0 && !BIG && KX > 0;
+
+template <int WIDE, int KX, bool CN, bool BIG, bool ONE = false>
 hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream) {
+  if constexpr (!ONE && kHasOneTeamVariant<WIDE, KX, BIG>) {
+    if (p.teams_per_wg == 1) return launch_env_variant<WIDE, KX, CN, BIG, true>(p, mode, probs, g, stream);
+  }
   const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
-  hipLaunchKernelGGL((env_kernel<WIDE, KX, CN, BIG>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, p,
+  hipLaunchKernelGGL((env_kernel<WIDE, KX, CN, BIG, ONE>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, p,
                      mode, probs, uint32_t(g), uint32_t(g >> 32));
   hipError_t err = hipGetLastError();
   if constexpr (BIG) {
@@ -906,9 +1003,12 @@ hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uin
   return err;
 }
 
-template <int WIDE, int KX, bool CN, bool BIG>
+template <int WIDE, int KX, bool CN, bool BIG, bool ONE = false>
 hipError_t prepare_env_variant(const Params& p) {
-  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&env_kernel<WIDE, KX, CN, BIG>),
+  if constexpr (!ONE && kHasOneTeamVariant<WIDE, KX, BIG>) {
+    if (p.teams_per_wg == 1) return prepare_env_variant<WIDE, KX, CN, BIG, true>(p);
+  }
+  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&env_kernel<WIDE, KX, CN, BIG, ONE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
   if constexpr (BIG) {
     if (err != hipSuccess) return err;
@@ -918,9 +1018,12 @@ hipError_t prepare_env_variant(const Params& p) {
   return err;
 }
 
-template <int WIDE, int KX, bool CN>
+template <int WIDE, int KX, bool CN, bool ONE = false>
 hipError_t launch_rollout_variant(const Params& p, const Roll& roll, const float* ring, uint64_t g, hipStream_t stream) {
-  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&rollout_kernel<WIDE, KX, CN>),
+  if constexpr (!ONE && kHasOneTeamVariant<WIDE, KX, false>) {
+    if (p.teams_per_wg == 1) return launch_rollout_variant<WIDE, KX, CN, true>(p, roll, ring, g, stream);
+  }
+  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&rollout_kernel<WIDE, KX, CN, ONE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
   if (err != hipSuccess) return err;
   const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
@@ -929,7 +1032,7 @@ hipError_t launch_rollout_variant(const Params& p, const Roll& roll, const float
   args.roll = roll;
   args.ring = ring;
   args.g0 = g;
-  hipLaunchKernelGGL((rollout_kernel<WIDE, KX, CN>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, args);
+  hipLaunchKernelGGL((rollout_kernel<WIDE, KX, CN, ONE>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, args);
   return hipGetLastError();
 }
 
