@@ -17,6 +17,8 @@
 #ifndef WD_DEV_STRIPS_H
 #define WD_DEV_STRIPS_H
 
+#include <utility>
+
 #include "wd_dev_tables.h"
 
 namespace wd {
@@ -166,51 +168,52 @@ __device__ __forceinline__ void strip_tag_scan(const Params& p, const Tables& L,
 // `dist` columns-rounded cells away in x.
 __device__ __forceinline__ int side_bound(bool done, int dist) { return done ? kFar : max(dist, 0); }
 
-// N consecutive slots from `wp` / `wi` as candidates; x | y << 16 of the first and the last slot come back.
-// kChunk > 0: unrolled, kChunk loads in flight before their candidates are inserted; the scheduling
-// barriers keep the compiler from hoisting the loads of all chunks to the front, which costs more
-// registers than there are.  kChunk == 0: a plain loop, four slots per turn (the second try, which
-// runs once per env: small code and few registers matter more than latency there).
-template <int K, int N, int kChunk>
-__device__ __forceinline__ void scan_slots(uint32_t (&keys)[K], const uint32_t* __restrict__ wp,
-                                           const uint16_t* __restrict__ wi, short2v mev, int ib, uint32_t& first,
-                                           uint32_t& last) {
-  if constexpr (kChunk == 0) {
-    first = wp[0];
-    last = wp[N - 1];
-#pragma unroll 1
-    for (int c0 = 0; c0 < N; c0 += 4) {
-      uint32_t pv[4], iv[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        pv[j] = wp[min(c0 + j, N - 1)];
-        iv[j] = wi[min(c0 + j, N - 1)];
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t key = (squared_length(__builtin_bit_cast(short2v, pv[j]) - mev) << ib) | iv[j];
-        insert_key<K>(keys, c0 + j < N ? key : ~0u);
-      }
-    }
-  } else {
-#pragma unroll
-    for (int c0 = 0; c0 < N; c0 += kChunk) {
-      __builtin_amdgcn_sched_barrier(0);
-      uint32_t pv[kChunk], iv[kChunk];
-#pragma unroll
-      for (int j = 0; j < kChunk; ++j)
-        if (c0 + j < N) {
-          pv[j] = wp[c0 + j];
-          iv[j] = wi[c0 + j];
-        }
-#pragma unroll
-      for (int j = 0; j < kChunk; ++j)
-        if (c0 + j < N) insert_key<K>(keys, (squared_length(__builtin_bit_cast(short2v, pv[j]) - mev) << ib) | iv[j]);
-      if (c0 == 0) first = pv[0];
-      if (c0 + kChunk >= N) last = pv[N - 1 - c0];
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  }
+// A 2-byte LDS load at a constant offset from `base`, zero-extended.  Written out: left to the
+// compiler, neighbouring index loads are merged into wide loads at 2-byte alignment (several LDS
+// passes per access) and unpacked again, one more instruction per candidate.  The result must not
+// be used before lds_wait().
+template <int kByteOffset>
+__device__ __forceinline__ uint32_t lds_read_u16(const uint16_t* base) {
+  uint32_t v;
+  // (the low word of a pointer into LDS is its LDS address)
+  asm volatile("ds_read_u16 %0, %1 offset:%2" : "=v"(v) : "v"(uint32_t(reinterpret_cast<uintptr_t>(base))), "n"(kByteOffset));
+  return v;
+}
+__device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+// ties a value loaded by lds_read_u16 to the lds_wait() in front of it
+__device__ __forceinline__ void lds_loaded(uint32_t& v) { asm volatile("" : "+v"(v)); }
+
+// kN consecutive slots from slot kFirst of `wp` / `wi` on as candidates (one chunk of a window).
+template <int K, int kFirst, int... J>
+__device__ __forceinline__ void scan_chunk(uint32_t (&keys)[K], const uint32_t* __restrict__ wp, const uint16_t* wi,
+                                           short2v mev, int ib, uint32_t& first, uint32_t& last,
+                                           std::integer_sequence<int, J...>) {
+  constexpr int kN = sizeof...(J);
+  uint32_t pv[kN], iv[kN];
+  ((pv[J] = wp[kFirst + J]), ...);
+  ((iv[J] = lds_read_u16<2 * (kFirst + J)>(wi)), ...);
+  lds_wait();
+  (lds_loaded(iv[J]), ...);
+  (insert_key<K>(keys, (squared_length(__builtin_bit_cast(short2v, pv[J]) - mev) << ib) | iv[J]), ...);
+  first = pv[0];
+  last = pv[kN - 1];
+}
+
+// N consecutive slots from `wp` / `wi` as candidates; x | y << 16 of the first and the last slot come
+// back.  In chunks of eight: eight position and eight index loads are in flight before their
+// candidates are inserted (all loads of a long window up front cost more registers than there are).
+template <int K, int N, int kFirst = 0>
+__device__ __forceinline__ void scan_slots(uint32_t (&keys)[K], const uint32_t* __restrict__ wp, const uint16_t* wi,
+                                           short2v mev, int ib, uint32_t& first, uint32_t& last) {
+  constexpr int kChunk = 8;
+  constexpr int kN = N - kFirst < kChunk ? N - kFirst : kChunk;
+  uint32_t f, l;
+  scan_chunk<K, kFirst>(keys, wp, wi, mev, ib, f, l, std::make_integer_sequence<int, kN>{});
+  if constexpr (kFirst == 0) first = f;
+  if constexpr (kFirst + kN >= N)
+    last = l;
+  else
+    scan_slots<K, N, kFirst + kN>(keys, wp, wi, mev, ib, first, last);
 }
 
 // The windows of the agent in slot q: HO slots on either side of it in its own strip, 2 HA slots
@@ -232,7 +235,6 @@ __device__ __forceinline__ bool strip_window_search(uint32_t (&keys)[K], uint32_
                                                     const uint16_t* id, const uint16_t* __restrict__ T,
                                                     const uint16_t* __restrict__ edges) {
   constexpr int kLevels = HF > 0 ? 2 : 1;
-  constexpr int kChunk = 8;
   const short2v mev = __builtin_bit_cast(short2v, me);
   const int X = int(me & 0xFFFFu), Y = int(me >> 16);
   const int r = strip_of(Y, sg);
@@ -252,10 +254,10 @@ __device__ __forceinline__ bool strip_window_search(uint32_t (&keys)[K], uint32_
     uint32_t first = 0, last = 0, unused;
     if constexpr (PAIR) {
       const int a = side ? q + 1 : q - HO;
-      scan_slots<K, HO, kChunk>(keys, pos + a, id + a, mev, ib, first, last);
+      scan_slots<K, HO>(keys, pos + a, id + a, mev, ib, first, last);
     } else {
-      scan_slots<K, HO, kChunk>(keys, pos + (q - HO), id + (q - HO), mev, ib, first, unused);
-      scan_slots<K, HO, kChunk>(keys, pos + (q + 1), id + (q + 1), mev, ib, unused, last);
+      scan_slots<K, HO>(keys, pos + (q - HO), id + (q - HO), mev, ib, first, unused);
+      scan_slots<K, HO>(keys, pos + (q + 1), id + (q + 1), mev, ib, unused, last);
     }
     const int bl = side_bound(!below || q - HO <= s_own, X - int((first & 0xFFFFu) | cm));
     const int br = side_bound(!above || q + HO >= e_own - 1, int((last & 0xFFFFu) & ~cm) - X);
@@ -286,9 +288,9 @@ __device__ __forceinline__ bool strip_window_search(uint32_t (&keys)[K], uint32_
       if (!has || lost) a = n_sorted;  // the pad behind the list
       uint32_t first, last;
       if (lv == 1)
-        scan_slots<K, 2 * HA, kChunk>(keys, pos + a, id + a, mev, ib, first, last);
+        scan_slots<K, 2 * HA>(keys, pos + a, id + a, mev, ib, first, last);
       else
-        scan_slots<K, 2 * (HF > 0 ? HF : kNone), kChunk>(keys, pos + a, id + a, mev, ib, first, last);
+        scan_slots<K, 2 * (HF > 0 ? HF : kNone)>(keys, pos + a, id + a, mev, ib, first, last);
       const bool done_l = up ? a <= near_end : a <= far_end;
       const bool done_r = up ? a + 2 * H >= far_end : a + 2 * H >= near_end;
       const int bl = side_bound(done_l, X - int((first & 0xFFFFu) | cm));
