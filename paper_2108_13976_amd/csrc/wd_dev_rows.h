@@ -10,6 +10,7 @@ namespace dev {
 
 constexpr int kMiscBucketMul = 22, kMiscBucketSide = 23;  // misc[] slots that carry the bucket geometry to big_obs_kernel
 constexpr int kMiscQueue2 = 24;  // misc[] slot: agents waiting for the block search of the strip variant
+constexpr int kMiscStripMul = 25, kMiscStripRows = 26;  // misc[] slots: strip geometry of the list the env's search runs on
 constexpr uint32_t kCompactNone = 1023u;  // "no neighbour" in the compact 10-bit form
 
 // One observation row (own features + K neighbour slots) written to `row` (registers, LDS

@@ -51,6 +51,17 @@ __device__ __forceinline__ Strips choose_strips(const Params& p, int n_live) {
   return s;
 }
 
+// The geometry again from the multiplier and the strip count that choose_strips picked.
+__device__ __forceinline__ Strips strips_of_env(const Params& p, uint32_t mul, int rows) {
+  Strips s;
+  s.mul = mul;
+  s.R = rows;
+  s.C = p.strip_C;
+  s.cshift = p.cshift;
+  s.hu = int(max(65536u / max(mul, 1u), 1u));
+  return s;
+}
+
 __device__ __forceinline__ int strip_of(int y, const Strips sg) { return int(__umul24(uint32_t(y), sg.mul) >> 16); }
 // first cell of strip r: the smallest y with (y * mul) >> 16 == r
 __device__ __forceinline__ int strip_first_cell(int r, const Strips sg) {

@@ -138,6 +138,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
   else
     bk = choose_buckets(p, nlr_in + N_tag);
   if (lt == 0) {  // every mode passes a barrier before the neighbour search appends
+    L.misc[2] = 0;  // set where the team's env is stepped or reset
     L.misc[3] = 0;
     L.misc[kMiscQueue2] = 0;
   }
@@ -321,6 +322,12 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
         p.done[e] = done_now ? 1 : 0;
       }
       out_act = true;
+      if (lt == 0) {  // for the observation phase, where waves also serve teams other than their lanes' own
+        L.misc[1] = t_out;
+        L.misc[2] = 1;
+        L.misc[kMiscStripMul] = int32_t(sg.mul);
+        L.misc[kMiscStripRows] = sg.R;
+      }
     }
     __syncthreads();  // tag keys and credits are read; the neighbour lists may overlay them
   }
@@ -392,6 +399,12 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
           p.done[e] = 0;
         }
         out_act = true;
+        if (lt == 0) {
+          L.misc[1] = 0;
+          L.misc[2] = 1;
+          L.misc[kMiscStripMul] = int32_t(sg.mul);
+          L.misc[kMiscStripRows] = sg.R;
+        }
       }
       __syncthreads();
       if constexpr (STRIP)
@@ -408,10 +421,8 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
   }
   WD_NEW_PHASE();
   // ---- observations ---------------------------------------------------------------------------
-  if (lt == 0) {
-    L.misc[1] = t_out;
-    L.misc[2] = out_act ? 1 : 0;
-  }
+  // (misc[1], the env clock, and misc[2], "this env gets new rows", were written where the env was
+  // stepped or reset, in front of a barrier)
   if constexpr (BIG) {
     // A large env hands its tables (positions, bucket-sorted list, bucket starts and edges) to
     // big_obs_kernel, which spreads the neighbour search and the rows of this env over many
@@ -434,65 +445,85 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
     // every live agent tries the 3x3 buckets around it; the few that this does not settle
     // (sparse spots, grid borders) queue up and are searched with widening rings afterwards,
     // packed into full waves, so that a wave of the first pass never waits for one such lane.
-    const auto put_neighbours = [&](uint32_t me, const Key(&keys)[KT]) {
+    const auto put_neighbours_of = [&](const TeamLds<WIDE, BIG>& Lt, uint32_t me, const Key(&keys)[KT]) {
       if constexpr (CN) {
         uint32_t id[4];
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) id[kk] = key_is_none<WIDE>(keys[kk]) ? kCompactNone : uint32_t(keys[kk] & idx_mask);
-        L.nbr_lo[me] = id[0] | (id[1] << 10) | (id[2] << 20) | (id[3] << 30);
-        L.nbr_hi[me] = uint8_t(id[3] >> 2);
+        Lt.nbr_lo[me] = id[0] | (id[1] << 10) | (id[2] << 20) | (id[3] << 30);
+        Lt.nbr_hi[me] = uint8_t(id[3] >> 2);
       } else {
 #pragma unroll
         for (int kk = 0; kk < KT; ++kk)
           if (kk < K)
-            L.nbr[me * K + kk] = key_is_none<WIDE>(keys[kk]) ? uint16_t(kNoNeighbour) : uint16_t(keys[kk] & idx_mask);
+            Lt.nbr[me * K + kk] = key_is_none<WIDE>(keys[kk]) ? uint16_t(kNoNeighbour) : uint16_t(keys[kk] & idx_mask);
       }
     };
+    const auto put_neighbours = [&](uint32_t me, const Key(&keys)[KT]) { put_neighbours_of(L, me, keys); };
     const bool search = out_act && K > 0;
     if (LOOPED && valid && !out_act && lt == 0) wg_flags[1] = 1;  // read after the two barriers below
+    // Strip variant: a wave serves the teams that its lanes belong to one after the other, with all
+    // 64 lanes (a team of 32 lanes or fewer shares its wave with others), so that everything that
+    // depends on the team is uniform over the wave and lives in scalar registers.
+    const int wave_teams = ONE ? 1 : (p.ts_log2 >= 6 ? 1 : kWaveSize >> p.ts_log2);
+    const int wave_team0 = ONE ? 0 : (p.ts_log2 >= 6 ? team : (tid >> 6) * wave_teams);
+    const int wave_lane = ONE ? tid : (p.ts_log2 >= 6 ? lt : (tid & (kWaveSize - 1)));
+    const int wave_stride = p.ts_log2 >= 6 ? ts : kWaveSize;
+    // calls body(tables, strips, number of agents in the list) for each of the wave's teams whose env gets new rows
+    const auto for_each_wave_team = [&](auto body) {
+      for (int w = 0; w < wave_teams; ++w) {
+        const int tm = ONE ? 0 : __builtin_amdgcn_readfirstlane(wave_team0 + w);
+        const TeamLds<WIDE, BIG> Lt(smem, tm, p, e0 + tm);
+        if (K > 0 && __builtin_amdgcn_readfirstlane(Lt.misc[2]) != 0) {
+          const Strips st = strips_of_env(p, uint32_t(__builtin_amdgcn_readfirstlane(Lt.misc[kMiscStripMul])),
+                                          __builtin_amdgcn_readfirstlane(Lt.misc[kMiscStripRows]));
+          body(Lt, st, __builtin_amdgcn_readfirstlane(int(Lt.starts[st.R * st.C])));
+        }
+      }
+    };
     if constexpr (STRIP) {
       // the fixed windows of the strip-sorted list; what they do not settle is queued
-      if (search) {
-        const int n_sorted = int(L.starts[sg.R * sg.C]);
-        for (int q = lt; q < n_sorted; q += ts) {
-          const uint32_t me = L.sorted.pos[q];
+      for_each_wave_team([&](const TeamLds<WIDE, BIG>& Lt, const Strips st, int n_sorted) {
+        for (int q = wave_lane; q < n_sorted; q += wave_stride) {
+          const uint32_t me = Lt.sorted.pos[q];
           if (int(me >> 16) < p.dead_dx) {  // not tagged in this step
             Key keys[KT];
             if (strip_window_search<KX, strip_half_own(KX), strip_half_adj(KX), 0, false>(
-                    keys, me, q, 0, sg, p.idx_bits, n_sorted, p.pad_l, L.sorted.pos, L.sorted.id, L.starts, L.edges))
-              put_neighbours(L.sorted.id[q], keys);
+                    keys, me, q, 0, st, p.idx_bits, n_sorted, p.pad_l, Lt.sorted.pos, Lt.sorted.id, Lt.starts, Lt.edges))
+              put_neighbours_of(Lt, Lt.sorted.id[q], keys);
             else
-              L.retry[atomicAdd(&L.misc[3], 1)] = uint16_t(q);
+              Lt.retry[atomicAdd(&Lt.misc[3], 1)] = uint16_t(q);
           }
         }
-      }
+      });
       // second try, wider windows and two more strips, for the few that are queued; what is left
       // after that (hardly ever anything) waits in a short queue of its own for the block search
       __syncthreads();
-      if (search) {
-        const int n_sorted = int(L.starts[sg.R * sg.C]);
-        const int n_retry = L.misc[3];
-        uint16_t* const queue2 = reinterpret_cast<uint16_t*>(L.misc + 4);  // (the scan scratch, idle by now)
+      for_each_wave_team([&](const TeamLds<WIDE, BIG>& Lt, const Strips st, int n_sorted) {
+        const int n_retry = __builtin_amdgcn_readfirstlane(Lt.misc[3]);
+        uint16_t* const queue2 = reinterpret_cast<uint16_t*>(Lt.misc + 4);  // (the scan scratch, idle by now)
         // (two lanes per agent: lane 2 j takes what lies below agent j's slot, lane 2 j + 1 what lies above)
-        for (int j = lt >> 1; j < n_retry; j += ts >> 1) {
-          const int q = L.retry[j];
-          const uint32_t me = L.sorted.pos[q];
+        for (int j = wave_lane >> 1; j < n_retry; j += wave_stride >> 1) {
+          const int q = Lt.retry[j];
+          const uint32_t me = Lt.sorted.pos[q];
           Key keys[KT];
           bool ok = strip_window_search<KX, strip_half_own2(KX), strip_half_adj2(KX), strip_half_far2(KX), true>(
-              keys, me, q, lt & 1, sg, p.idx_bits, n_sorted, p.pad_l, L.sorted.pos, L.sorted.id, L.starts, L.edges);
-          if (lt & 1) continue;  // the even lane goes on for both
+              keys, me, q, wave_lane & 1, st, p.idx_bits, n_sorted, p.pad_l, Lt.sorted.pos, Lt.sorted.id, Lt.starts,
+              Lt.edges);
+          if (wave_lane & 1) continue;  // the even lane goes on for both
           if (!ok) {
-            const int at = atomicAdd(&L.misc[kMiscQueue2], 1);
+            const int at = atomicAdd(&Lt.misc[kMiscQueue2], 1);
             if (at < kStripQueue2) {
               queue2[at] = uint16_t(q);
             } else {  // the queue is full: search here and now
-              strip_block_search<KX>(keys, me, uint32_t(q), sg, p.idx_bits, G, L.sorted.pos, L.sorted.id, L.starts, L.edges);
+              strip_block_search<KX>(keys, me, uint32_t(q), st, p.idx_bits, G, Lt.sorted.pos, Lt.sorted.id, Lt.starts,
+                                     Lt.edges);
               ok = true;
             }
           }
-          if (ok) put_neighbours(L.sorted.id[q], keys);
+          if (ok) put_neighbours_of(Lt, Lt.sorted.id[q], keys);
         }
-      }
+      });
     } else if (search) {
       const int n_sorted = int(L.starts[p.nb_cap]);
       for (int q = lt; q < n_sorted; q += ts) {
@@ -508,17 +539,25 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
       }
     }
     __syncthreads();
-    if (search) {
-      const int n_retry = STRIP ? min(L.misc[kMiscQueue2], kStripQueue2) : L.misc[3];
-      const uint16_t* const queue = STRIP ? reinterpret_cast<const uint16_t*>(L.misc + 4) : L.retry;
+    if constexpr (STRIP) {
+      for_each_wave_team([&](const TeamLds<WIDE, BIG>& Lt, const Strips st, int) {
+        const int n_wait = min(__builtin_amdgcn_readfirstlane(Lt.misc[kMiscQueue2]), kStripQueue2);
+        const uint16_t* const queue2 = reinterpret_cast<const uint16_t*>(Lt.misc + 4);
+        for (int j = wave_lane; j < n_wait; j += wave_stride) {
+          const uint32_t q = queue2[j];
+          Key keys[KT];
+          strip_block_search<KX>(keys, Lt.sorted.pos[q], q, st, p.idx_bits, G, Lt.sorted.pos, Lt.sorted.id, Lt.starts,
+                                 Lt.edges);
+          put_neighbours_of(Lt, Lt.sorted.id[q], keys);
+        }
+      });
+    } else if (search) {
+      const int n_retry = L.misc[3];
       for (int j = lt; j < n_retry; j += ts) {
-        const uint32_t q = queue[j];
+        const uint32_t q = L.retry[j];
         const Ent ent = L.sorted.get(q);
         Key keys[KT];
-        if constexpr (STRIP)
-          strip_block_search<KX>(keys, ent.pos, q, sg, p.idx_bits, G, L.sorted.pos, L.sorted.id, L.starts, L.edges);
-        else
-          nearest_keys<WIDE, KT, false>(keys, K, SL::x(ent), SL::y(ent), q, bk, p.idx_bits, L.sorted, L.starts, L.edges);
+        nearest_keys<WIDE, KT, false>(keys, K, SL::x(ent), SL::y(ent), q, bk, p.idx_bits, L.sorted, L.starts, L.edges);
         put_neighbours(ent.id, keys);
       }
     }
