@@ -32,19 +32,25 @@ PAPER_ENV_STEPS_PER_S = 2.9e6  # Sec. 5.3, one A100: context only
 
 
 def read_traffic(workload, iterations_per_launch):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary
-    (None unless that summary was taken with the same number of iterations per launch)."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, and
+    where it comes from: (None, None) unless that summary was taken with the same number of
+    iterations per launch.  The counters cannot be read inside this run; the figure is the one of the
+    profile run that the file names."""
+    rel = os.path.join("profiles", f"hbm_traffic_{workload}.txt")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
+        return None, None
     found = {}
+    window = ""
     for line in open(path):
         parts = line.split()
         if len(parts) == 2 and parts[0] in ("traffic_bytes_per_launch", "iterations_per_launch"):
             found[parts[0]] = float(parts[1])
-    if found.get("iterations_per_launch", 1) != iterations_per_launch:
-        return None
-    return found.get("traffic_bytes_per_launch")
+        if line.startswith("window "):
+            window = line[len("window "):].strip()
+    if found.get("iterations_per_launch", 1) != iterations_per_launch or "traffic_bytes_per_launch" not in found:
+        return None, None
+    return found["traffic_bytes_per_launch"], f"{rel} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not measured in this run; {window})"
 
 
 def run_iterations(env, ring, first_g, count, mode, per_launch=1):
@@ -68,6 +74,43 @@ def run_iterations(env, ring, first_g, count, mode, per_launch=1):
             env.step()
             env.reset(wd.WD_RESET_DONE)
     return count
+
+
+def wake_device(cfg, ring, iterations=400):
+    """Untimed: runs the workload for a moment so that the device has left its idle clocks before
+    anything is timed (the first few hundred launches of a process run up to 15 % slower)."""
+    import torch
+    import paper_2108_13976_amd as wd
+
+    env = wd.TagEnvs(device="cuda:0", **cfg.kwargs())
+    env.reset(wd.WD_RESET_ALL)
+    run_iterations(env, ring, 0, iterations, "fused")
+    torch.cuda.synchronize()
+    env.close()
+
+
+def contract_window(cfg, ring, repetitions=5, warmup=50):
+    """The measurement window of the method's roll-out throughput whatever --steps says: 2 T iterations
+    (two episode lengths: runners leaving the game, envs ending early, staggered resets are all
+    inside) after `warmup` iterations from the reset state, `repetitions` times; one wd_iterate launch
+    per iteration, HIP events on the launch stream."""
+    steps = 2 * cfg.episode_length
+    launch_us, rates = [], []
+    bytes_per_iteration = None
+    for _ in range(repetitions):
+        wall, event_s, _, bytes_per_iteration, launches = time_gpu(cfg, ring, steps, warmup, "fused")
+        launch_us.append(event_s / launches * 1e6)
+        rates.append(steps / wall * cfg.num_envs)
+    launch_us.sort()
+    rates.sort()
+    mid = len(launch_us) // 2
+    gbs = bytes_per_iteration / (launch_us[mid] * 1e-6) / 1e9
+    out = {"iterations": steps, "warmup": warmup, "repetitions": repetitions,
+           "avg_launch_us": launch_us[mid], "avg_launch_us_min": launch_us[0], "avg_launch_us_max": launch_us[-1],
+           "env_steps_per_s": rates[mid], "env_steps_per_s_min": rates[0], "env_steps_per_s_max": rates[-1],
+           "achieved": gbs, "frac": gbs / HBM_PEAK_GBS}
+    out.update(window_statistics(cfg, ring, steps, warmup))
+    return out
 
 
 def time_gpu(cfg, ring, steps, warmup, mode, per_launch=1, **over):
@@ -277,6 +320,8 @@ def main():
         cfg = dataclasses.replace(cfg, obs_mode=1)
     ring = device_probs_ring(cfg.seed, RING, cfg.num_envs, cfg.num_agents, "cuda:0")
     torch.cuda.synchronize()
+    if args.obs == "partial":
+        wake_device(cfg, ring)
 
     mode = args.mode
     if mode == "rollout" and not rollout_offered(cfg):
@@ -290,7 +335,8 @@ def main():
     launch_s = event_s / launches  # average duration of one launch on its stream (gaps included)
     bytes_per_launch = bytes_per_iteration * args.steps / launches
     achieved_gbs = bytes_per_launch / launch_s / 1e9
-    traffic = read_traffic(args.workload, per_launch) if (args.obs == "partial" and mode != "separate") else None
+    traffic, traffic_source = (read_traffic(args.workload, per_launch) if (args.obs == "partial" and mode != "separate")
+                               else (None, None))
     kernel_name = {"rollout": f"rollout_kernel ({per_launch} iterations of sample + step + reset per launch)",
                    "fused": "env_kernel (sample + step + reset fused)",
                    "separate": "sample + step + reset kernels"}[mode]
@@ -323,6 +369,8 @@ def main():
             "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
             "algorithmic_bytes_per_launch": bytes_per_launch, "avg_launch_us": launch_s * 1e6,
             "traffic": traffic,
+            "traffic_source": traffic_source,
+            "window": f"{args.steps} iterations after {args.warmup} from the reset state (the arguments of this run)",
             **({"note": "inside a launch positions, live flags and env scalars stay on chip (36 of the 140 "
                         "algorithmic bytes per agent-step are not moved in 24 of 25 iterations)"}
                if mode == "rollout" else {}),
@@ -333,6 +381,10 @@ def main():
         },
         "state_at_end": stats,
     }
+
+    if not args.no_extras and args.obs == "partial" and mode == "fused":
+        # the contracted window, independent of --steps / --warmup
+        out["roofline"]["window_2T"] = contract_window(cfg, ring)
 
     if not args.no_extras:
         extras = {}
@@ -369,6 +421,20 @@ def main():
             k_other = args.iterations_per_launch if other == "rollout" else 1
             w3, _, _, _, _ = time_gpu(cfg, ring, args.steps, args.warmup, other, k_other)
             extras[f"{other}_env_steps_per_s"] = args.steps / w3 * cfg.num_envs
+        if args.obs == "partial" and mode == "fused":
+            # all five workloads over their own 2 T windows (one wd_iterate launch per iteration)
+            per_config = {}
+            for name, other in CONFIGS.items():
+                other_ring = ring if name == args.workload else device_probs_ring(other.seed, RING, other.num_envs,
+                                                                                   other.num_agents, "cuda:0")
+                w = contract_window(other, other_ring, repetitions=3)
+                per_config[name] = {"us_per_iteration": w["avg_launch_us"], "env_steps_per_s": w["env_steps_per_s"],
+                                    "agent_steps_per_s": w["env_steps_per_s"] * other.num_agents,
+                                    "hbm_frac": w["frac"], "iterations": w["iterations"],
+                                    "mean_live_fraction": w["mean_live_fraction"],
+                                    "resets_per_iteration": w["resets_per_iteration"]}
+                del other_ring
+            extras["configs"] = per_config
         out["extras"] = extras
 
     if not args.no_cpu_baseline:
