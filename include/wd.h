@@ -62,7 +62,9 @@ typedef enum wd_status {
   WD_E_ALIGN = -3,  /* a device buffer is not aligned as required                   */
   WD_E_STATE = -4,  /* call order: sample/step/reset(DONE) before the first reset(ALL) */
   WD_E_HIP = -5,    /* a HIP call failed; wd_last_error(handle) has the text        */
-  WD_E_UNSUPPORTED = -6 /* valid config that this build has no kernel for           */
+  WD_E_UNSUPPORTED = -6, /* valid config that this build has no kernel for          */
+  WD_E_SCRATCH = -7 /* wd_iterate_static: the configuration's work tables exceed
+                       WD_STATIC_SCRATCH_BYTES                                      */
 } wd_status;
 
 enum { WD_RESET_ALL = 0, WD_RESET_DONE = 1 };
@@ -152,6 +154,23 @@ int wd_step(wd_handle* h);
 /* One whole roll-out iteration in a single launch: wd_sample(probs), wd_step,
  * wd_reset(WD_RESET_DONE), with identical results. */
 int wd_iterate(wd_handle* h, const float* probs);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): wd_iterate without a handle and without
+ * any allocation, on the host or on the device.  One whole roll-out iteration (sample,
+ * step, reset of done envs) at global step g on the state in `bufs`, which must be a state
+ * that this library left there (wd_reset / wd_step / wd_iterate / wd_rollout on a handle of
+ * the same configuration, or earlier calls of this function).  Same arguments otherwise:
+ * cfg (host), bufs (DEVICE pointers, 256-byte aligned), probs (device [E][N][5]); the
+ * kernels are enqueued on cfg->stream and not synchronised; results equal wd_iterate's.
+ * Every observation row is written whole.  The work tables that a large-env configuration
+ * needs (see wd_create) live in a static device array of WD_STATIC_SCRATCH_BYTES that every
+ * call on a GPU shares (each GPU the library runs on holds it until the process ends):
+ * WD_E_SCRATCH if the configuration needs more; calls that overlap in time on one GPU, on
+ * any streams, race on that array and must be serialised by the caller.  Calls no
+ * hipMalloc / hipFree. */
+#define WD_STATIC_SCRATCH_BYTES (8u << 20)
+int wd_iterate_static(const wd_config* cfg, const wd_buffers* bufs, const float* probs, uint64_t g);
 
 /* Per-iteration outputs of a multi-step roll-out (the experience a trainer batches,
  * Sec. 4.5 item 7): DEVICE pointers, caller-owned, 16-byte aligned, each may be NULL.

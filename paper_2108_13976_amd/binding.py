@@ -10,7 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIBRARY = os.path.join(HERE, "libwd.so")
 
 WD_OK = 0
-WD_E_NULL, WD_E_CONFIG, WD_E_ALIGN, WD_E_STATE, WD_E_HIP, WD_E_UNSUPPORTED = -1, -2, -3, -4, -5, -6
+WD_E_NULL, WD_E_CONFIG, WD_E_ALIGN, WD_E_STATE, WD_E_HIP, WD_E_UNSUPPORTED, WD_E_SCRATCH = -1, -2, -3, -4, -5, -6, -7
+WD_STATIC_SCRATCH_BYTES = 8 << 20
 WD_RESET_ALL, WD_RESET_DONE = 0, 1
 WD_OBS_PARTIAL, WD_OBS_FULL = 0, 1
 
@@ -90,6 +91,8 @@ def load_library(path=LIBRARY):
         lib.wd_sample.argtypes = [H, ctypes.c_void_p]
         lib.wd_step.argtypes = [H]
         lib.wd_iterate.argtypes = [H, ctypes.c_void_p]
+        lib.wd_iterate_static.argtypes = [ctypes.POINTER(wd_config), ctypes.POINTER(wd_buffers), ctypes.c_void_p,
+                                          ctypes.c_uint64]
         lib.wd_rollout.argtypes = [H, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.POINTER(wd_rollout_buffers)]
         lib.wd_get_step.argtypes = [H, ctypes.POINTER(ctypes.c_uint64)]
         lib.wd_set_step.argtypes = [H, ctypes.c_uint64]
@@ -99,7 +102,7 @@ def load_library(path=LIBRARY):
         lib.wd_last_error.argtypes = [H]
         lib.wd_last_error.restype = ctypes.c_char_p
         for name in ("wd_query_layout", "wd_create", "wd_reset", "wd_sample", "wd_step", "wd_iterate", "wd_rollout",
-                     "wd_get_step", "wd_set_step", "wd_destroy"):
+                     "wd_get_step", "wd_set_step", "wd_destroy", "wd_iterate_static"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -150,6 +153,12 @@ def wd_step(handle):
 
 def wd_iterate(handle, probs_ptr):
     _call(handle, "wd_iterate", ctypes.c_void_p(probs_ptr))
+
+
+def wd_iterate_static(cfg, bufs, probs_ptr, g):
+    rc = load_library().wd_iterate_static(ctypes.byref(cfg), ctypes.byref(bufs), ctypes.c_void_p(probs_ptr), int(g))
+    if rc != WD_OK:
+        raise WdError(rc, "wd_iterate_static")
 
 
 def wd_rollout(handle, probs_ring_ptr, ring_len, k, out=None):

@@ -412,6 +412,27 @@ int hip_failed(wd_handle* h, hipError_t err, const char* what) {
   return WD_E_HIP;
 }
 
+// Work tables of the large-env layout (slots, tag keys, credits and the table image of every env):
+// total bytes, and the pointers into one block of that size.
+int64_t place_big_tables(wd::Params* p, int64_t E, unsigned char* base) {
+  const int64_t key_bytes = p->wide == 1 ? 8 : 4;
+  const int64_t slot_b = align16(2 * p->g_stride_agents * E), best_b = align16(key_bytes * p->g_stride_agents * E);
+  const int64_t cred_b = align16(4 * p->g_stride_credits * E), image_b = p->g_stride_image * E;
+  if (base) {
+    p->g_best = base;
+    p->g_credits = reinterpret_cast<int32_t*>(base + best_b);
+    p->g_slot = reinterpret_cast<uint16_t*>(base + best_b + cred_b);
+    p->g_image = base + best_b + cred_b + slot_b;
+  }
+  return slot_b + best_b + cred_b + image_b;
+}
+
+// The work tables of wd_iterate_static: one array per device, held until the process ends.
+constexpr size_t kStaticScratchBytes = size_t(WD_STATIC_SCRATCH_BYTES);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, once asked for
+
 }  // namespace
 
 extern "C" {
@@ -449,19 +470,12 @@ int wd_create(const wd_config* cfg, const wd_buffers* bufs, wd_handle** out) {
   h->scratch = nullptr;
   if (params.big) {
     // large envs: slots, tag keys, credits and the table image of every env, in one allocation
-    const int64_t E = cfg->num_envs, key_bytes = params.wide == 1 ? 8 : 4;
-    const int64_t slot_b = align16(2 * params.g_stride_agents * E), best_b = align16(key_bytes * params.g_stride_agents * E);
-    const int64_t cred_b = align16(4 * params.g_stride_credits * E), image_b = params.g_stride_image * E;
-    if (hipMalloc(&h->scratch, size_t(slot_b + best_b + cred_b + image_b)) != hipSuccess) {
+    if (hipMalloc(&h->scratch, size_t(place_big_tables(&params, cfg->num_envs, nullptr))) != hipSuccess) {
       (void)hipGetLastError();
       delete h;
       return WD_E_HIP;
     }
-    unsigned char* base = static_cast<unsigned char*>(h->scratch);
-    params.g_best = base;
-    params.g_credits = reinterpret_cast<int32_t*>(base + best_b);
-    params.g_slot = reinterpret_cast<uint16_t*>(base + best_b + cred_b);
-    params.g_image = base + best_b + cred_b + slot_b;
+    place_big_tables(&params, cfg->num_envs, static_cast<unsigned char*>(h->scratch));
   }
   h->cfg = *cfg;
   h->bufs = *bufs;
@@ -529,6 +543,50 @@ int wd_iterate(wd_handle* h, const float* probs) {
   if (err != hipSuccess) return hip_failed(h, err, "iterate kernel");
   h->rows_valid = true;
   h->g += 1;
+  return WD_OK;
+}
+
+int wd_iterate_static(const wd_config* cfg, const wd_buffers* bufs, const float* probs, uint64_t g) {
+  if (!cfg || !bufs || !probs) return WD_E_NULL;
+  int rc = check_config(cfg);
+  if (rc != WD_OK) return rc;
+  const void* ptrs[] = {bufs->pos_x, bufs->pos_y, bufs->pos_x0, bufs->pos_y0, bufs->live, bufs->action,
+                        bufs->reward, bufs->obs, bufs->t, bufs->done, bufs->n_live_runners, bufs->tags_step};
+  for (const void* ptr : ptrs)
+    if (!ptr) return WD_E_NULL;
+  for (const void* ptr : ptrs)
+    if (!aligned256(ptr)) return WD_E_ALIGN;
+  wd::Params params;
+  rc = fill_params(*cfg, *bufs, &params);
+  if (rc != WD_OK) return rc;
+  if (!probs_aligned(params, probs)) return WD_E_ALIGN;
+  if (params.big) {
+    if (size_t(place_big_tables(&params, cfg->num_envs, nullptr)) > kStaticScratchBytes) return WD_E_SCRATCH;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+      (void)hipGetLastError();
+      return WD_E_HIP;
+    }
+    if (!g_scratch_ptr[dev]) {  // this device's copy of the array, at its own address
+      void* ptr = nullptr;
+      if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+        (void)hipGetLastError();
+        return WD_E_HIP;
+      }
+      g_scratch_ptr[dev] = ptr;
+    }
+    // (nothing in the tables has to start at zero: the kernels write every entry before they read it)
+    place_big_tables(&params, cfg->num_envs, static_cast<unsigned char*>(g_scratch_ptr[dev]));
+  }
+  if (wd::prepare_env_kernels(params) != hipSuccess) {
+    (void)hipGetLastError();
+    return WD_E_HIP;
+  }
+  params.rows_kept = 0;  // no handle, so nothing is known about what `obs` holds: every row is written whole
+  if (wd::launch_env_kernel(params, wd::kModeIterate, probs, g, static_cast<hipStream_t>(cfg->stream)) != hipSuccess) {
+    (void)hipGetLastError();
+    return WD_E_HIP;
+  }
   return WD_OK;
 }
 
@@ -627,6 +685,7 @@ const char* wd_strerror(int status) {
     case WD_E_STATE: return "call before the first wd_reset(WD_RESET_ALL)";
     case WD_E_HIP: return "HIP call failed";
     case WD_E_UNSUPPORTED: return "configuration not covered by this build's kernels";
+    case WD_E_SCRATCH: return "work tables of this configuration exceed the static scratch array of wd_iterate_static";
     default: return "unknown status";
   }
 }

@@ -140,8 +140,26 @@ def test_call_order_is_enforced_before_any_launch():
 
 def test_status_texts():
     assert wd.wd_strerror(0) == "ok"
-    texts = {wd.wd_strerror(s) for s in range(-6, 1)}
-    assert len(texts) == 7 and wd.wd_strerror(-99) == "unknown status"
+    texts = {wd.wd_strerror(s) for s in range(-7, 1)}
+    assert len(texts) == 8 and wd.wd_strerror(-99) == "unknown status"
+
+
+def test_static_entry_point_checks_its_arguments_before_any_launch():
+    lib = wd.load_library()
+    assert lib.wd_iterate_static(None, None, None, 0) == binding.WD_E_NULL
+    bufs = fake_buffers()
+    with pytest.raises(wd.WdError) as ei:
+        wd.wd_iterate_static(good_config(num_agents=1), bufs, 0x40000, 0)
+    assert ei.value.status == binding.WD_E_CONFIG
+    with pytest.raises(wd.WdError) as ei:
+        wd.wd_iterate_static(good_config(num_agents=12), bufs, 0x40004, 0)  # probs: 16-byte alignment with N % 4 == 0
+    assert ei.value.status == binding.WD_E_ALIGN
+    # 160 envs of 8192 agents (large-env layout): work tables of about 25 MB, beyond the static array
+    big = binding.make_config(160, 8192, 512, 512, 10)
+    with pytest.raises(wd.WdError) as ei:
+        wd.wd_iterate_static(big, bufs, 0x40000, 0)
+    assert ei.value.status == binding.WD_E_SCRATCH
+    assert "static scratch" in wd.wd_strerror(binding.WD_E_SCRATCH)
 
 
 def test_missing_library_fails_loudly(tmp_path, monkeypatch):
