@@ -2,12 +2,11 @@
  * wd.h — C ABI of libwd: the batched discrete Tag roll-out path on one MI355X.
  *
  * The library runs the three device-side services of a WarpDrive-style roll-out
- * (arXiv 2108.13976, Sec. 4.4 "Software Layers and Components": the sampler and
- * reset kernels of the "CUDA Service" and the step kernel of the "CUDA
- * Environment"; Sec. 4.5 "The WarpDrive RL Workflow", items 2-6) for the discrete
- * Tag environment of Sec. 5.1, on ONE device-resident struct-of-arrays data store
- * that is updated in place (Sec. 4.2, "Minimal Communication"; the step signature
- * figure: float observations and rewards, int actions and done flags).
+ * (arXiv 2108.13976, Sec. 4.4: the sampler and reset kernels of the service layer and
+ * the step kernel of the environment layer; Sec. 4.5, items 2-6 of the workflow) for
+ * the discrete Tag environment of Sec. 5.1, on ONE device-resident struct-of-arrays
+ * data store that is updated in place (Sec. 4.2; the figure with the step signature:
+ * float observations and rewards, int actions and done flags).
  *
  * Conventions
  *   - Every function returns WD_OK (0) or a negative wd_status; none throws or
@@ -29,11 +28,17 @@
  *   - The observations are part of that in-place state (one data store, modified
  *     in place: Sec. 4.2).  The row of an agent that was already out of play
  *     before a step differs from the row the previous call left in `obs` in its
- *     time feature only, and a step may rewrite just that element.  A caller that
- *     overwrites `obs` or the state arrays between calls (a restored checkpoint,
- *     an agent taken out of play by hand) calls wd_set_step (with the step
- *     counter to go on from): the next call then writes every row whole.  Rows recorded through
- *     wd_rollout_buffers are always written whole.
+ *     time feature only, and in some configurations (full observations, K > 16,
+ *     the large-env layout: see wd_create) a step rewrites just that element; with
+ *     partial observations and K <= 16 in the small layout (the five benchmark
+ *     workloads but tag_10x8192) every row is always written whole.  What the
+ *     library knows about `obs` is kept per handle, so a region of the buffers must
+ *     be driven through ONE handle at a time, and a caller that overwrites `obs`
+ *     or the state arrays between calls (a restored checkpoint, an agent taken out
+ *     of play by hand, observations normalised in place, another handle or
+ *     wd_iterate_static used on the same buffers) calls wd_invalidate_obs: the next
+ *     call then writes every row whole.  Rows recorded through wd_rollout_buffers
+ *     are always written whole.
  *   - The global step g reaches the kernels as a launch argument.  A HIP graph
  *     captured around calls of this library therefore replays the random numbers
  *     of the steps it was captured at; to run many iterations with one launch,
@@ -84,15 +89,15 @@ typedef struct wd_config {
                              <= tag_r2 after the moves; negative disables tagging        */
   int32_t obs_mode;       /* WD_OBS_PARTIAL (K nearest agents) or WD_OBS_FULL            */
   int32_t obs_k;          /* K: 0 <= K <= N-1 (ignored in full mode)                     */
-  float tag_reward;       /* to the credited tagger, per tag ("e.g. +1")                 */
-  float tag_penalty;      /* to the runner on the step it is tagged ("e.g. -1")          */
+  float tag_reward;       /* to the credited tagger, per tag (Sec. 5.1 gives +1 as example) */
+  float tag_penalty;      /* to the runner on the step it is tagged (example there: -1)   */
   uint64_t seed;
   void* stream;           /* hipStream_t, borrowed                                       */
 } wd_config;
 
 /* The device-resident data store (Sec. 4.5 item 1: state arrays plus the
  * observation / action / reward / done placeholders; pos_x0, pos_y0 are the copies
- * "re-initialised at every reset"). */
+ * of the start state that item 5 puts back at every reset). */
 typedef struct wd_buffers {
   int32_t *pos_x, *pos_y;   /* [E][N] cell coordinates in [0, G)                         */
   int32_t *pos_x0, *pos_y0; /* [E][N] start positions, written by wd_reset(ALL)          */
@@ -116,11 +121,14 @@ typedef struct wd_layout {
 
 typedef struct wd_handle wd_handle;
 
-/* Fills *out for a configuration.  Host only; touches no device. */
+/* Fills *out for a configuration.  Host only; touches no device.  (No passage of the
+ * paper: this build's own; it takes the place of the data manager's placeholder
+ * set-up of Sec. 4.4.) */
 int wd_query_layout(const wd_config* cfg, wd_layout* out);
 
-/* Validates cfg and bufs (range, alignment), chooses the launch geometry and
- * returns a handle in *out.  Enqueues nothing; the buffers' contents are not read.
+/* (No passage of the paper: this build's own; the paper's managers load kernels and
+ * push data at this point, Sec. 4.4.)  Validates cfg and bufs (range, alignment),
+ * chooses the launch geometry and returns a handle in *out.  Enqueues nothing; the buffers' contents are not read.
  * WD_E_UNSUPPORTED if no kernel of this build covers the configuration (an env whose
  * tables exceed one workgroup's LDS: beyond about 13 900 agents with 32-bit keys, 11 500
  * with 64-bit keys, 8192 for full observations or K > 16).  Envs too large for one
@@ -129,7 +137,7 @@ int wd_query_layout(const wd_config* cfg, wd_layout* out);
  * agent) the library allocates here with hipMalloc: WD_E_HIP if that fails. */
 int wd_create(const wd_config* cfg, const wd_buffers* bufs, wd_handle** out);
 
-/* Environment reset (Sec. 4.5 item 5 "Automatic Environment Resetting").
+/* Environment reset (Sec. 4.5 item 5, the automatic reset of done envs).
  * WD_RESET_ALL : draws pos_x0/pos_y0 uniformly on the grid from the seed, then puts
  *                every env in its start state; sets the global step g to 0.
  * WD_RESET_DONE: every env with done == 1 is put back in its start state in place
@@ -138,7 +146,7 @@ int wd_create(const wd_config* cfg, const wd_buffers* bufs, wd_handle** out);
  *                reward and action untouched); other envs are untouched. */
 int wd_reset(wd_handle* h, int mode);
 
-/* Action sampling (Sec. 4.5 item 6 "Thread-parallelized Action Sampling").
+/* Action sampling (Sec. 4.5 item 6, one sampler thread per agent).
  * probs: device [E][N][5] float32 policy outputs.  Writes action[e][i] for EVERY
  * agent of EVERY env by inverse CDF (float32 running sum, left to right, strict
  * "u < sum", last action as fall-through) with u from word i mod 4 of the random
@@ -152,7 +160,8 @@ int wd_sample(wd_handle* h, const float* probs);
 int wd_step(wd_handle* h);
 
 /* One whole roll-out iteration in a single launch: wd_sample(probs), wd_step,
- * wd_reset(WD_RESET_DONE), with identical results. */
+ * wd_reset(WD_RESET_DONE), with identical results (Sec. 4.5 items 3-6 fused; the fusion
+ * itself is this build's own). */
 int wd_iterate(wd_handle* h, const float* probs);
 
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight
@@ -192,18 +201,24 @@ typedef struct wd_rollout_buffers {
  * with the same results.  On WD_E_HIP part of the iterations may have been enqueued. */
 int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const wd_rollout_buffers* out);
 
-/* The global step counter g used as the RNG step index (checkpoint / resume).
- * wd_set_step also tells the library that `obs` may not hold the rows of the current
- * state any more (see Conventions): the next step writes every row whole. */
+/* The global step counter g used as the RNG step index (checkpoint / resume; no passage
+ * of the paper: this build's own).  wd_set_step also does what wd_invalidate_obs does: a
+ * resumed run may have restored the state arrays without the observations. */
 int wd_get_step(wd_handle* h, uint64_t* g);
 int wd_set_step(wd_handle* h, uint64_t g);
 
+/* Tells the library that `obs` (or the state arrays) were changed by someone else since
+ * the last call on this handle (see Conventions): the next step, iteration or roll-out
+ * writes every observation row whole.  Host only.  (No passage of the paper: this build's
+ * own, a consequence of keeping the observations in the in-place store of Sec. 4.2.) */
+int wd_invalidate_obs(wd_handle* h);
+
 /* Frees the handle and, for large-env configurations, its work tables (the caller
  * must have synchronised the stream first in that case).  The caller's buffers are
- * not touched. */
+ * not touched.  (No passage of the paper: this build's own.) */
 int wd_destroy(wd_handle* h);
 
-/* Static text for a status code. */
+/* Static text for a status code.  (This build's own, like wd_last_error.) */
 const char* wd_strerror(int status);
 
 /* Text of the last HIP failure seen on this handle ("" if none).  The pointer is

@@ -96,13 +96,14 @@ def load_library(path=LIBRARY):
         lib.wd_rollout.argtypes = [H, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.POINTER(wd_rollout_buffers)]
         lib.wd_get_step.argtypes = [H, ctypes.POINTER(ctypes.c_uint64)]
         lib.wd_set_step.argtypes = [H, ctypes.c_uint64]
+        lib.wd_invalidate_obs.argtypes = [H]
         lib.wd_destroy.argtypes = [H]
         lib.wd_strerror.argtypes = [ctypes.c_int]
         lib.wd_strerror.restype = ctypes.c_char_p
         lib.wd_last_error.argtypes = [H]
         lib.wd_last_error.restype = ctypes.c_char_p
         for name in ("wd_query_layout", "wd_create", "wd_reset", "wd_sample", "wd_step", "wd_iterate", "wd_rollout",
-                     "wd_get_step", "wd_set_step", "wd_destroy", "wd_iterate_static"):
+                     "wd_get_step", "wd_set_step", "wd_destroy", "wd_iterate_static", "wd_invalidate_obs"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -159,6 +160,10 @@ def wd_iterate_static(cfg, bufs, probs_ptr, g):
     rc = load_library().wd_iterate_static(ctypes.byref(cfg), ctypes.byref(bufs), ctypes.c_void_p(probs_ptr), int(g))
     if rc != WD_OK:
         raise WdError(rc, "wd_iterate_static")
+
+
+def wd_invalidate_obs(handle):
+    _call(handle, "wd_invalidate_obs")
 
 
 def wd_rollout(handle, probs_ring_ptr, ring_len, k, out=None):

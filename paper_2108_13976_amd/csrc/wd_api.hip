@@ -494,10 +494,6 @@ int wd_reset(wd_handle* h, int mode) {
   if (mode == WD_RESET_DONE && !h->started) return WD_E_STATE;
   hipError_t err;
   if (mode == WD_RESET_ALL) {
-    if (!h->started) {
-      err = wd::prepare_env_kernels(h->params);
-      if (err != hipSuccess) return hip_failed(h, err, "kernel setup");
-    }
     err = wd::launch_init_start_positions(h->params, h->stream);
     if (err != hipSuccess) return hip_failed(h, err, "start-position kernel");
     err = wd::launch_env_kernel(h->params, wd::kModeResetAll, nullptr, 0, h->stream);
@@ -577,10 +573,6 @@ int wd_iterate_static(const wd_config* cfg, const wd_buffers* bufs, const float*
     }
     // (nothing in the tables has to start at zero: the kernels write every entry before they read it)
     place_big_tables(&params, cfg->num_envs, static_cast<unsigned char*>(g_scratch_ptr[dev]));
-  }
-  if (wd::prepare_env_kernels(params) != hipSuccess) {
-    (void)hipGetLastError();
-    return WD_E_HIP;
   }
   params.rows_kept = 0;  // no handle, so nothing is known about what `obs` holds: every row is written whole
   if (wd::launch_env_kernel(params, wd::kModeIterate, probs, g, static_cast<hipStream_t>(cfg->stream)) != hipSuccess) {
@@ -666,6 +658,12 @@ int wd_set_step(wd_handle* h, uint64_t g) {
   if (!h) return WD_E_NULL;
   h->g = g;
   h->rows_valid = false;  // a resumed run: the caller may have restored the state arrays without the observations
+  return WD_OK;
+}
+
+int wd_invalidate_obs(wd_handle* h) {
+  if (!h) return WD_E_NULL;
+  h->rows_valid = false;
   return WD_OK;
 }
 

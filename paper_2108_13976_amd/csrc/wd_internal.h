@@ -135,8 +135,6 @@ hipError_t launch_init_start_positions(const Params& p, hipStream_t stream);
 hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream);
 hipError_t launch_rollout(const Params& p, const Roll& roll, const float* ring, uint64_t g, hipStream_t stream);
 bool rollout_available(const Params& p);
-// One-time per-process setup of kernel attributes (dynamic LDS limit) for a plan.
-hipError_t prepare_env_kernels(const Params& p);
 // True if the env-per-team kernels cover this configuration.
 bool env_kernel_available(const Params& p);
 

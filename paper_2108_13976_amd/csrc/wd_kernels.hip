@@ -580,7 +580,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
     if (all_out) {
       const int srl = p.stage_rows_log2, stage_rows = 1 << srl, flushes = kWaveSize >> srl;
       float* stage = reinterpret_cast<float*>(smem + p.x_base) + wave * stage_rows * D;
-      const bool vec_ok = ((int64_t(e0) * N * D) & 3) == 0;
+      const bool vec_ok = (reinterpret_cast<uintptr_t>(obs_wg) & 15) == 0;  // (a roll-out slice may start on a 4-byte boundary)
       const int waves = p.wg_size >> 6;
       for (int c = wave; c * kWaveSize < rows_total; c += waves) {
         const int R0 = c * kWaveSize;
@@ -707,7 +707,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
   } else {
     __syncthreads();
     if (p.obs_mode == 1) {
-      // Full observations (Sec. 5.1, "partial or full observations"): row i holds the own
+      // Full observations (the second observation mode of Sec. 5.1): row i holds the own
       // features and one slot per agent j in index order, zeros unless both are in play.  The
       // team walks the N * N slots of its env; consecutive lanes write consecutive 16-byte
       // slots, so the stream to HBM is contiguous except for the five own features per row.
@@ -1019,6 +1019,23 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
   if (roll.obs) copy_words(roll.obs + (last + first) * p.D, p.obs + first * p.D, count * p.D);
 }
 
+// The limit on a kernel's dynamic LDS is a property of the kernel function on a device, not of a
+// handle: it is raised whenever a launch needs more than any launch before it on that device.
+constexpr int kMaxDevicesTracked = 64;
+template <typename Kernel>
+hipError_t ensure_dynamic_lds(Kernel kernel, int bytes) {
+  static int granted[kMaxDevicesTracked];  // per kernel function (one instance of this template each)
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return hipGetLastError();
+  if (dev < 0 || dev >= kMaxDevicesTracked || bytes > granted[dev]) {
+    const hipError_t err =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (err != hipSuccess) return err;
+    if (dev >= 0 && dev < kMaxDevicesTracked) granted[dev] = bytes;
+  }
+  return hipSuccess;
+}
+
 // (one team per workgroup gets the variant whose team-dependent values are uniform, where one is compiled)
 template <int WIDE, int KX, bool BIG>
 constexpr bool kHasOneTeamVariant = WIDE == 0 && !BIG && KX > 0;
@@ -1029,30 +1046,19 @@ hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uin
     if (p.teams_per_wg == 1) return launch_env_variant<WIDE, KX, CN, BIG, true>(p, mode, probs, g, stream);
   }
   const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
+  hipError_t lds_err = ensure_dynamic_lds(&env_kernel<WIDE, KX, CN, BIG, ONE>, p.lds_bytes);
+  if (lds_err != hipSuccess) return lds_err;
   hipLaunchKernelGGL((env_kernel<WIDE, KX, CN, BIG, ONE>), dim3(groups), dim3(p.wg_size), size_t(p.lds_bytes), stream, p,
                      mode, probs, uint32_t(g), uint32_t(g >> 32));
   hipError_t err = hipGetLastError();
   if constexpr (BIG) {
     if (err != hipSuccess) return err;
     // stream order puts the observation kernel behind the tables it reads
+    err = ensure_dynamic_lds(&big_obs_kernel<WIDE, KX>, p.y_base);
+    if (err != hipSuccess) return err;
     hipLaunchKernelGGL((big_obs_kernel<WIDE, KX>), dim3(p.E * p.big_slices), dim3(kBigObsWorkgroupSize),
                        size_t(p.y_base), stream, p);
     err = hipGetLastError();
-  }
-  return err;
-}
-
-template <int WIDE, int KX, bool CN, bool BIG, bool ONE = false>
-hipError_t prepare_env_variant(const Params& p) {
-  if constexpr (!ONE && kHasOneTeamVariant<WIDE, KX, BIG>) {
-    if (p.teams_per_wg == 1) return prepare_env_variant<WIDE, KX, CN, BIG, true>(p);
-  }
-  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&env_kernel<WIDE, KX, CN, BIG, ONE>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
-  if constexpr (BIG) {
-    if (err != hipSuccess) return err;
-    err = hipFuncSetAttribute(reinterpret_cast<const void*>(&big_obs_kernel<WIDE, KX>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, p.y_base);
   }
   return err;
 }
@@ -1062,8 +1068,7 @@ hipError_t launch_rollout_variant(const Params& p, const Roll& roll, const float
   if constexpr (!ONE && kHasOneTeamVariant<WIDE, KX, false>) {
     if (p.teams_per_wg == 1) return launch_rollout_variant<WIDE, KX, CN, true>(p, roll, ring, g, stream);
   }
-  hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&rollout_kernel<WIDE, KX, CN, ONE>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes);
+  const hipError_t err = ensure_dynamic_lds(&rollout_kernel<WIDE, KX, CN, ONE>, p.lds_bytes);
   if (err != hipSuccess) return err;
   const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
   RollArgs args;
@@ -1129,8 +1134,6 @@ int variant_of(const Params& p) {
 hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream) {
   WD_DISPATCH(launch_env_variant, mode, probs, g, stream);
 }
-
-hipError_t prepare_env_kernels(const Params& p) { WD_DISPATCH(prepare_env_variant); }
 
 bool rollout_available(const Params& p) { return !p.big && p.obs_mode == 0 && p.K <= kMaxRegisterK; }
 

@@ -22,7 +22,7 @@ class GpuTraceEnv:
         c = dict(config)
         self.wd = wd
         self.env = wd.TagEnvs(1, c["num_agents"], c["num_taggers"], c["grid_size"], c["episode_length"],
-                              seed=0, tag_r2=c["tag_r2"], obs_k=c["obs_k"])
+                              seed=0, tag_r2=c["tag_r2"], obs_k=c["obs_k"], obs_mode=c.get("obs_mode", 0))
         self.env.reset(wd.WD_RESET_ALL)
 
     def set_start(self, start):
@@ -639,14 +639,19 @@ def test_random_configuration(seed):
     lockstep(kw, steps, kw["seed"] % 1000, fused=bool(seed & 1))
 
 
-def test_many_more_random_configurations():
-    """A batch of further random configurations in one test (WD_EXTRA_SEEDS of them, 240 by default):
-    every third with 384 .. 3073 agents in a few envs, the shapes that run in the large-env pair of
-    kernels or in wide workgroups, with K from 0 to 16."""
+def _extra_seed_chunks(per_chunk=20):
     import os
 
     count = int(os.environ.get("WD_EXTRA_SEEDS", "240"))
-    for seed in range(5000, 5000 + count):
+    return [range(lo, min(lo + per_chunk, 5000 + count)) for lo in range(5000, 5000 + count, per_chunk)]
+
+
+@pytest.mark.parametrize("seeds", _extra_seed_chunks(), ids=lambda r: f"seeds{r.start}-{r.stop - 1}")
+def test_many_more_random_configurations(seeds):
+    """Further random configurations, twenty to a test (WD_EXTRA_SEEDS of them in all, 240 by default):
+    every third with 384 .. 3073 agents in a few envs, the shapes that run in the large-env pair of
+    kernels or in wide workgroups, with K from 0 to 16."""
+    for seed in seeds:
         kw = random_configuration(seed)
         large = seed % 3 == 0
         if large:
@@ -709,12 +714,52 @@ def test_observations_overwritten_by_the_caller(name):
         if g % 3 == 2:
             tagged = tagged or bool((orc.live == 0).any())
             gpu.tensors["obs"].fill_(-123.5)
-            gpu.global_step = g
+            if g % 2:
+                gpu.global_step = g  # (wd_set_step implies it)
+            else:
+                wd.wd_invalidate_obs(gpu.handle)
         gpu.iterate(upload(probs, gpu.device))
         orc.iterate(probs, g)
         assert_equal_state(gpu.to_host(), orc, f"after iteration {g}")
     assert tagged, "the case never had an agent out of play when the buffer was overwritten"
     gpu.close()
+
+
+def test_two_handles_of_different_lds_size_used_alternately():
+    """Two live handles on the same kernel variant whose workgroups need different amounts of LDS
+    (the limit on dynamic LDS is a property of the kernel, not of the handle), stepped in turn;
+    and two handles that drive the same buffers in turn, with wd_invalidate_obs at each change."""
+    import paper_2108_13976_amd as wd
+
+    small = dict(num_envs=3, num_agents=40, num_taggers=4, grid_size=16, episode_length=9, seed=5)
+    large = dict(num_envs=5, num_agents=900, num_taggers=90, grid_size=90, episode_length=9, seed=6)
+    pairs = [(make_gpu(kw), make_oracle(kw), kw) for kw in (large, small)]
+    for gpu, orc, _ in pairs:
+        gpu.reset(wd.WD_RESET_ALL), orc.reset()
+    for g in range(12):
+        for gpu, orc, kw in reversed(pairs) if g % 2 else pairs:
+            probs = probs_for_step(kw["seed"], g, kw["num_envs"], kw["num_agents"])
+            gpu.iterate(upload(probs, gpu.device))
+            orc.iterate(probs, g)
+            assert_equal_state(gpu.to_host(), orc, f"{kw['num_agents']} agents, iteration {g}")
+    for gpu, _, _ in pairs:
+        gpu.close()
+    # one set of buffers, two handles (full observations keep rows of agents out of play)
+    kw = dict(seed=77, **EDGE["full_obs"]) if "full_obs" in EDGE else dict(num_envs=4, num_agents=24, num_taggers=6, grid_size=8, episode_length=30, seed=77, obs_mode=1)
+    a, orc = make_gpu(kw), make_oracle(kw)
+    b_handle = wd.wd_create(a.cfg, a.bufs)
+    a.reset(wd.WD_RESET_ALL), orc.reset()
+    a.torch_stream.synchronize()
+    wd.wd_reset(b_handle, wd.WD_RESET_ALL)  # (same start state again; makes the second handle usable)
+    for g in range(24):
+        probs = probs_for_step(77, g, kw["num_envs"], kw["num_agents"])
+        h = a.handle if (g // 2) % 2 == 0 else b_handle
+        wd.wd_set_step(h, g)  # the other handle advanced the run (also invalidates what h knows of obs)
+        wd.wd_iterate(h, upload(probs, a.device).data_ptr())
+        orc.iterate(probs, g)
+        assert_equal_state(a.to_host(), orc, f"shared buffers, iteration {g}")
+    wd.wd_destroy(b_handle)
+    a.close()
 
 
 def test_two_runs_are_byte_identical():
