@@ -498,32 +498,58 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
       });
       // second try, wider windows and two more strips, for the few that are queued; what is left
       // after that (hardly ever anything) waits in a short queue of its own for the block search
+      // (two lanes per agent: an even lane takes what lies below the agent's slot, its odd neighbour
+      // what lies above)
       __syncthreads();
-      for_each_wave_team([&](const TeamLds<WIDE, BIG>& Lt, const Strips st, int n_sorted) {
-        const int n_retry = __builtin_amdgcn_readfirstlane(Lt.misc[3]);
-        uint16_t* const queue2 = reinterpret_cast<uint16_t*>(Lt.misc + 4);  // (the scan scratch, idle by now)
-        // (two lanes per agent: lane 2 j takes what lies below agent j's slot, lane 2 j + 1 what lies above)
-        for (int j = wave_lane >> 1; j < n_retry; j += wave_stride >> 1) {
-          const int q = Lt.retry[j];
-          const uint32_t me = Lt.sorted.pos[q];
-          Key keys[KT];
-          bool ok = strip_window_search<KX, strip_half_own2(KX), strip_half_adj2(KX), strip_half_far2(KX), true>(
-              keys, me, q, wave_lane & 1, st, p.idx_bits, n_sorted, p.pad_l, Lt.sorted.pos, Lt.sorted.id, Lt.starts,
-              Lt.edges);
-          if (wave_lane & 1) continue;  // the even lane goes on for both
-          if (!ok) {
-            const int at = atomicAdd(&Lt.misc[kMiscQueue2], 1);
-            if (at < kStripQueue2) {
-              queue2[at] = uint16_t(q);
-            } else {  // the queue is full: search here and now
-              strip_block_search<KX>(keys, me, uint32_t(q), st, p.idx_bits, G, Lt.sorted.pos, Lt.sorted.id, Lt.starts,
-                                     Lt.edges);
-              ok = true;
-            }
+      const auto second_try = [&](const TeamLds<WIDE, BIG>& Lt, const Strips st, int n_sorted, int j, int side) {
+        const int q = Lt.retry[j];
+        const uint32_t me = Lt.sorted.pos[q];
+        Key keys[KT];
+        bool ok = strip_window_search<KX, strip_half_own2(KX), strip_half_adj2(KX), strip_half_far2(KX), true>(
+            keys, me, q, side, st, p.idx_bits, n_sorted, p.pad_l, Lt.sorted.pos, Lt.sorted.id, Lt.starts, Lt.edges);
+        if (side) return;  // the even lane goes on for both
+        if (!ok) {
+          const int at = atomicAdd(&Lt.misc[kMiscQueue2], 1);
+          if (at < kStripQueue2) {
+            reinterpret_cast<uint16_t*>(Lt.misc + 4)[at] = uint16_t(q);  // (the scan scratch, idle by now)
+          } else {  // the queue is full: search here and now
+            strip_block_search<KX>(keys, me, uint32_t(q), st, p.idx_bits, G, Lt.sorted.pos, Lt.sorted.id, Lt.starts,
+                                   Lt.edges);
+            ok = true;
           }
-          if (ok) put_neighbours_of(Lt, Lt.sorted.id[q], keys);
         }
-      });
+        if (ok) put_neighbours_of(Lt, Lt.sorted.id[q], keys);
+      };
+      if constexpr (ONE) {
+        for_each_wave_team([&](const TeamLds<WIDE, BIG>& Lt, const Strips st, int n_sorted) {
+          const int n_retry = __builtin_amdgcn_readfirstlane(Lt.misc[3]);
+          for (int j = wave_lane >> 1; j < n_retry; j += wave_stride >> 1) second_try(Lt, st, n_sorted, j, wave_lane & 1);
+        });
+      } else {
+        // Several teams per workgroup: a team queues one or two agents as a rule, so the queues of all
+        // teams are served as one list by the lane pairs of the whole workgroup (what depends on the
+        // team is per lane here), instead of one run through this code per team.
+        const int pairs = p.wg_size >> 1;
+        for (int first = 0;; first += pairs) {
+          const int i = first + (tid >> 1);
+          int mine = -1, j = 0, seen = 0;
+          for (int tm = 0; tm < p.teams_per_wg; ++tm) {
+            const int32_t* m = reinterpret_cast<const int32_t*>(smem + tm * p.keep_stride + p.off_misc);
+            const int c = (K > 0 && e0 + tm < p.E && m[2]) ? m[3] : 0;
+            if (mine < 0 && i < seen + c) {
+              mine = tm;
+              j = i - seen;
+            }
+            seen += c;
+          }
+          if (first >= seen) break;  // (`seen` ends as the length of the whole list, the same in every lane)
+          if (mine >= 0) {
+            const TeamLds<WIDE, BIG> Lt(smem, mine, p, e0 + mine);
+            const Strips st = strips_of_env(p, uint32_t(Lt.misc[kMiscStripMul]), Lt.misc[kMiscStripRows]);
+            second_try(Lt, st, int(Lt.starts[st.R * st.C]), j, tid & 1);
+          }
+        }
+      }
     } else if (search) {
       const int n_sorted = int(L.starts[p.nb_cap]);
       for (int q = lt; q < n_sorted; q += ts) {
