@@ -421,6 +421,20 @@ def main():
             k_other = args.iterations_per_launch if other == "rollout" else 1
             w3, _, _, _, _ = time_gpu(cfg, ring, args.steps, args.warmup, other, k_other)
             extras[f"{other}_env_steps_per_s"] = args.steps / w3 * cfg.num_envs
+        if args.obs == "partial" and mode == "fused" and cfg.num_envs * cfg.num_agents * (5 + 4 * cfg.num_agents) * 4 <= 64 << 30:
+            # the same workload with full observations (one slot per agent, paper Sec. 5.1 / 5.5): a short
+            # window from the reset state, and the same with tagging switched off (every row written)
+            import dataclasses
+            full_cfg = dataclasses.replace(cfg, obs_mode=1)
+            wf, ef, _, bf, lf = time_gpu(full_cfg, ring, 20, 5, "fused")
+            wa, ea, _, _, la = time_gpu(full_cfg, ring, 20, 5, "fused", tag_r2=-1)
+            extras["full_observations"] = {
+                "obs_dim": full_cfg.obs_dim, "iterations": 20, "warmup": 5,
+                "us_per_iteration": ef / lf * 1e6, "env_steps_per_s": 20 / wf * cfg.num_envs,
+                "algorithmic_bytes_per_iteration": bf, "hbm_frac": bf / (ef / lf) / 1e9 / HBM_PEAK_GBS,
+                "all_rows_written_us_per_iteration": ea / la * 1e6,
+                "all_rows_written_hbm_frac": bf / (ea / la) / 1e9 / HBM_PEAK_GBS,
+            }
         if args.obs == "partial" and mode == "fused":
             # all five workloads over their own 2 T windows (one wd_iterate launch per iteration)
             per_config = {}
