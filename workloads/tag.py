@@ -1,4 +1,4 @@
-"""The five Tag workloads and the stand-in policy output.
+"""The five Tag workloads, three continuous-Tag workloads and the stand-in policy output.
 
 The paper benchmarks its discrete Tag environment (Sec. 5.1) with 5 to 1000 agents
 and up to 2000 environments (Sec. 5.3); its environment source and trained policies
@@ -46,6 +46,51 @@ CONFIGS = {
     "tag_20000x100": TagConfig("tag_20000x100", 20000, 100, 10, 40, 200, 3),
     "tag_10x8192": TagConfig("tag_10x8192", 10, 8192, 512, 512, 200, 4),
 }
+
+
+@dataclass(frozen=True)
+class CTagConfig:
+    """Continuous Tag (paper Sec. 5.1, second variant): sizes and the constants this build chose."""
+    name: str
+    num_envs: int
+    num_agents: int
+    num_taggers: int
+    episode_length: int
+    seed: int
+    world_size: float = 20.0
+    num_headings: int = 16
+    accel: float = 0.25
+    max_speed_tagger: float = 1.0
+    max_speed_runner: float = 0.75
+    tag_r2: float = 1.0
+    obs_k: int = 4
+    tag_reward: float = 1.0
+    tag_penalty: float = -1.0
+
+    def kwargs(self):
+        d = asdict(self)
+        d.pop("name")
+        return d
+
+    @property
+    def obs_dim(self):
+        return 8 + 6 * self.obs_k
+
+
+# 2000 x 5 is the shape of the paper's continuous-Tag throughput figure (Sec. 5.3); 5 taggers and
+# 100 runners on a 20 x 20 world is the shape of its snapshot figure
+CTAG_CONFIGS = {
+    "ctag_10x5": CTagConfig("ctag_10x5", 10, 5, 1, 100, 10),
+    "ctag_2000x5": CTagConfig("ctag_2000x5", 2000, 5, 1, 500, 11),
+    "ctag_2000x105": CTagConfig("ctag_2000x105", 2000, 105, 5, 500, 12),
+}
+
+
+def ctag_probs_for_step(seed, g, num_envs, num_agents, env_lo=0, env_hi=None):
+    """Host probabilities [E, N, 2, 5] float32 for global step ``g`` of a continuous-Tag workload:
+    one softmax per agent and action category (acceleration, turn)."""
+    flat = probs_for_step(seed, g, num_envs, 2 * num_agents, env_lo, env_hi)
+    return flat.reshape(flat.shape[0], num_agents, 2, NUM_ACTIONS)
 
 
 def _softmax32(logits):
