@@ -1,4 +1,4 @@
-"""ctypes binding of libwd's C ABI (``include/wd.h``): same names, argument marshalling only.
+"""ctypes binding of libwd's C ABI (``include/wd.h``, ``include/wdc.h``): same names, argument marshalling only.
 
 Every step of the path runs in the library's HIP kernels.  There is no fallback: if the
 library is missing, ``load_library`` raises.
@@ -105,6 +105,7 @@ def load_library(path=LIBRARY):
         for name in ("wd_query_layout", "wd_create", "wd_reset", "wd_sample", "wd_step", "wd_iterate", "wd_rollout",
                      "wd_get_step", "wd_set_step", "wd_destroy", "wd_iterate_static", "wd_invalidate_obs"):
             getattr(lib, name).restype = ctypes.c_int
+        _declare_continuous(lib)
         _lib = lib
     return _lib
 
@@ -280,6 +281,206 @@ class TagEnvs:
     def close(self):
         if self.handle is not None:
             wd_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# ================================================================================================
+# continuous Tag (include/wdc.h)
+# ================================================================================================
+class wdc_config(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("num_envs", ctypes.c_int32),
+        ("env_offset", ctypes.c_int32),
+        ("num_agents", ctypes.c_int32),
+        ("num_taggers", ctypes.c_int32),
+        ("num_headings", ctypes.c_int32),
+        ("episode_length", ctypes.c_int32),
+        ("obs_k", ctypes.c_int32),
+        ("world_size", ctypes.c_float),
+        ("accel", ctypes.c_float),
+        ("max_speed_tagger", ctypes.c_float),
+        ("max_speed_runner", ctypes.c_float),
+        ("tag_r2", ctypes.c_float),
+        ("tag_reward", ctypes.c_float),
+        ("tag_penalty", ctypes.c_float),
+        ("seed", ctypes.c_uint64),
+        ("stream", ctypes.c_void_p),
+    ]
+
+
+CBUFFER_NAMES = ("x", "y", "v", "h", "x0", "y0", "h0", "live", "action", "reward", "obs",
+                 "t", "done", "n_live_runners", "tags_step")
+
+
+class wdc_buffers(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in CBUFFER_NAMES]
+
+
+class wdc_layout(ctypes.Structure):
+    _fields_ = [
+        ("obs_dim", ctypes.c_int32),
+        ("agent_elems", ctypes.c_int64),
+        ("action_elems", ctypes.c_int64),
+        ("obs_elems", ctypes.c_int64),
+        ("env_elems", ctypes.c_int64),
+        ("probs_elems", ctypes.c_int64),
+        ("bytes_per_iteration", ctypes.c_int64),
+    ]
+
+
+def _declare_continuous(lib):
+    H = ctypes.c_void_p
+    lib.wdc_query_layout.argtypes = [ctypes.POINTER(wdc_config), ctypes.POINTER(wdc_layout)]
+    lib.wdc_create.argtypes = [ctypes.POINTER(wdc_config), ctypes.POINTER(wdc_buffers), ctypes.POINTER(H)]
+    lib.wdc_reset.argtypes = [H, ctypes.c_int]
+    lib.wdc_sample.argtypes = [H, ctypes.c_void_p]
+    lib.wdc_step.argtypes = [H]
+    lib.wdc_iterate.argtypes = [H, ctypes.c_void_p]
+    lib.wdc_get_step.argtypes = [H, ctypes.POINTER(ctypes.c_uint64)]
+    lib.wdc_set_step.argtypes = [H, ctypes.c_uint64]
+    lib.wdc_destroy.argtypes = [H]
+    lib.wdc_last_error.argtypes = [H]
+    lib.wdc_last_error.restype = ctypes.c_char_p
+    for name in ("wdc_query_layout", "wdc_create", "wdc_reset", "wdc_sample", "wdc_step", "wdc_iterate",
+                 "wdc_get_step", "wdc_set_step", "wdc_destroy"):
+        getattr(lib, name).restype = ctypes.c_int
+
+
+def make_cconfig(num_envs, num_agents, num_taggers, episode_length, seed=0, world_size=20.0, num_headings=16,
+                 accel=0.25, max_speed_tagger=1.0, max_speed_runner=0.75, tag_r2=1.0, obs_k=4, tag_reward=1.0,
+                 tag_penalty=-1.0, env_offset=0, stream=None):
+    return wdc_config(ctypes.sizeof(wdc_config), num_envs, env_offset, num_agents, num_taggers, num_headings,
+                      episode_length, obs_k, world_size, accel, max_speed_tagger, max_speed_runner, tag_r2,
+                      tag_reward, tag_penalty, seed, stream)
+
+
+def wdc_query_layout(cfg):
+    out = wdc_layout()
+    rc = load_library().wdc_query_layout(ctypes.byref(cfg), ctypes.byref(out))
+    if rc != WD_OK:
+        raise WdError(rc, "wdc_query_layout")
+    return out
+
+
+def wdc_create(cfg, bufs):
+    handle = ctypes.c_void_p()
+    rc = load_library().wdc_create(ctypes.byref(cfg), ctypes.byref(bufs), ctypes.byref(handle))
+    if rc != WD_OK:
+        raise WdError(rc, "wdc_create")
+    return handle
+
+
+def _ccall(handle, name, *args):
+    rc = getattr(load_library(), name)(handle, *args)
+    if rc != WD_OK:
+        raise WdError(rc, name, wdc_last_error(handle) if rc == WD_E_HIP else "")
+
+
+def wdc_reset(handle, mode):
+    _ccall(handle, "wdc_reset", int(mode))
+
+
+def wdc_sample(handle, probs_ptr):
+    _ccall(handle, "wdc_sample", ctypes.c_void_p(probs_ptr))
+
+
+def wdc_step(handle):
+    _ccall(handle, "wdc_step")
+
+
+def wdc_iterate(handle, probs_ptr):
+    _ccall(handle, "wdc_iterate", ctypes.c_void_p(probs_ptr))
+
+
+def wdc_get_step(handle):
+    g = ctypes.c_uint64()
+    _ccall(handle, "wdc_get_step", ctypes.byref(g))
+    return int(g.value)
+
+
+def wdc_set_step(handle, g):
+    _ccall(handle, "wdc_set_step", ctypes.c_uint64(int(g)))
+
+
+def wdc_destroy(handle):
+    _ccall(handle, "wdc_destroy")
+
+
+def wdc_last_error(handle):
+    return load_library().wdc_last_error(handle).decode()
+
+
+class CTagEnvs:
+    """E continuous-Tag environments resident on one GPU.  PyTorch allocates the state tensors and
+    supplies the stream; every call forwards to the C ABI."""
+
+    FLOAT_ARRAYS = ("x", "y", "v", "x0", "y0", "reward")
+
+    def __init__(self, num_envs, num_agents, num_taggers, episode_length, seed=0, world_size=20.0,
+                 num_headings=16, accel=0.25, max_speed_tagger=1.0, max_speed_runner=0.75, tag_r2=1.0, obs_k=4,
+                 tag_reward=1.0, tag_penalty=-1.0, env_offset=0, device="cuda:0", stream=None):
+        import torch
+
+        load_library()
+        if not torch.cuda.is_available():
+            raise RuntimeError("CTagEnvs needs a GPU: the HIP path has no CPU fallback")
+        self.device = torch.device(device)
+        self.torch_stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        self.cfg = make_cconfig(num_envs, num_agents, num_taggers, episode_length, seed, world_size, num_headings,
+                                accel, max_speed_tagger, max_speed_runner, tag_r2, obs_k, tag_reward, tag_penalty,
+                                env_offset, stream=self.torch_stream.cuda_stream)
+        self.layout = wdc_query_layout(self.cfg)
+        E, N, D = num_envs, num_agents, self.layout.obs_dim
+        self.E, self.N, self.D = E, N, D
+        i32, f32 = torch.int32, torch.float32
+        with torch.cuda.device(self.device):
+            self.tensors = {n: torch.zeros((E, N), dtype=f32 if n in self.FLOAT_ARRAYS else i32, device=self.device)
+                            for n in ("x", "y", "v", "h", "x0", "y0", "h0", "live", "reward")}
+            self.tensors["action"] = torch.zeros((E, N, 2), dtype=i32, device=self.device)
+            self.tensors["obs"] = torch.zeros((E, N, D), dtype=f32, device=self.device)
+            self.tensors.update({n: torch.zeros((E,), dtype=i32, device=self.device)
+                                 for n in ("t", "done", "n_live_runners", "tags_step")})
+        for n, ten in self.tensors.items():
+            setattr(self, n, ten)
+        self.bufs = wdc_buffers(*[self.tensors[n].data_ptr() for n in CBUFFER_NAMES])
+        self.handle = wdc_create(self.cfg, self.bufs)
+
+    def _check_probs(self, probs):
+        import torch
+
+        if (probs.dtype != torch.float32 or not probs.is_contiguous() or probs.device != self.device
+                or probs.numel() != self.layout.probs_elems):
+            raise ValueError("probs must be a contiguous float32 device tensor of shape [E, N, 2, 5]")
+
+    def reset(self, mode=WD_RESET_ALL):
+        wdc_reset(self.handle, mode)
+
+    def sample(self, probs):
+        self._check_probs(probs)
+        wdc_sample(self.handle, probs.data_ptr())
+
+    def step(self):
+        wdc_step(self.handle)
+
+    def iterate(self, probs):
+        self._check_probs(probs)
+        wdc_iterate(self.handle, probs.data_ptr())
+
+    def to_host(self):
+        """Synchronise the stream and copy every state array to numpy."""
+        self.torch_stream.synchronize()
+        return {n: t.cpu().numpy() for n, t in self.tensors.items()}
+
+    def close(self):
+        if self.handle is not None:
+            wdc_destroy(self.handle)
             self.handle = None
 
     def __del__(self):

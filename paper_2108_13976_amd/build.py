@@ -8,7 +8,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-SOURCES = [os.path.join(CSRC, "wd_api.hip"), os.path.join(CSRC, "wd_kernels.hip")]
+SOURCES = [os.path.join(CSRC, "wd_api.hip"), os.path.join(CSRC, "wd_kernels.hip"), os.path.join(CSRC, "wdc.hip")]
 LIBRARY = os.path.join(HERE, "libwd.so")
 
 HIPCC_FLAGS = [

@@ -1,0 +1,519 @@
+// wdc.hip — continuous Tag: the C ABI of include/wdc.h and its kernels (gfx950).
+//
+// One thread per agent.  A workgroup of `bd` threads holds floor(bd / N) envs (these envs are
+// small: the paper's own continuous-Tag runs have 5 to 45 agents per env); the moved positions
+// and velocities of the workgroup's envs are staged in LDS, where the runner-side tag test and the
+// brute-force K-nearest search read them.  Every float32 operation that feeds a comparison is
+// written as its own statement and the file is compiled without contraction, so that the state is
+// reproducible to the bit (arXiv 2108.13976, Sec. 5.1, continuous variant; the numbers are this
+// build's reading, stated in wdc.h).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <new>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "../../include/wdc.h"
+#include "wd_dev_common.h"
+
+namespace wdc {
+
+constexpr int kMaxThreads = 1024;      // one thread per agent, so also the largest env
+constexpr int kMaxK = 8;
+constexpr uint32_t kStreamActionC = 2;  // random streams of this variant (0 and 1 are the discrete variant's)
+constexpr uint32_t kStreamInitC = 3;
+enum Mode : int { kSample = 1, kStep = 2, kResetDone = 4, kResetAll = 8 };
+
+struct Params {
+  int32_t E, N, N_tag, H, T, K, D;
+  int32_t envs_per_wg, threads;
+  uint32_t env_offset, seed_lo, seed_hi;
+  wd::FastDiv div_N;
+  float L, inv_L, inv_T, accel, vmax_tagger, vmax_runner, tag_r2, tag_reward, tag_penalty;
+  float *x, *y, *v;
+  int32_t* h;
+  float *x0, *y0;
+  int32_t* h0;
+  int32_t* live;
+  int32_t* action;
+  float* reward;
+  float* obs;
+  int32_t *t, *done, *n_live_runners, *tags_step;
+  const float2* table;  // (cx, cy) per heading
+};
+
+namespace {
+
+using wd::dev::philox_block;
+using wd::dev::sample_action;
+
+// start state of every agent (once per reset of all envs)
+__global__ __launch_bounds__(256) void init_kernel(const Params p) {
+  const int64_t a = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  if (a >= int64_t(p.E) * p.N) return;
+  const uint32_t e = uint32_t(a / p.N), i = uint32_t(a - int64_t(e) * p.N);
+  const wd::dev::Block4 r = philox_block(p.env_offset + e, i, 0u, kStreamInitC, p.seed_lo, p.seed_hi);
+  const float u0 = static_cast<float>(r.w[0] >> 8) * (1.0f / 16777216.0f);
+  const float u1 = static_cast<float>(r.w[1] >> 8) * (1.0f / 16777216.0f);
+  p.x0[a] = u0 * p.L;
+  p.y0[a] = u1 * p.L;
+  p.h0[a] = int32_t(__umulhi(r.w[2], uint32_t(p.H)));
+}
+
+// heading index brought into [0, H): also keeps a caller's stray value from indexing outside the table
+__device__ __forceinline__ int wrap_heading(int h, int H) {
+  const int r = h % H;
+  return r < 0 ? r + H : r;
+}
+
+__device__ __forceinline__ float squared_distance(float xa, float ya, float xb, float yb) {
+  const float dx = xa - xb;
+  const float dy = ya - yb;
+  const float dx2 = dx * dx;
+  const float dy2 = dy * dy;
+  return dx2 + dy2;
+}
+
+__global__ __launch_bounds__(kMaxThreads) void env_kernel(const Params p, const int mode, const float* __restrict__ probs,
+                                                           const uint32_t g_lo, const uint32_t g_hi) {
+  // per local agent slot: moved position, velocity components, live flag, credits (taggers)
+  // (dynamic LDS: 26 bytes per thread of the workgroup, see lds_bytes)
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* const s_x = reinterpret_cast<float*>(smem);
+  float* const s_y = s_x + p.threads;
+  float* const s_vx = s_y + p.threads;
+  float* const s_vy = s_vx + p.threads;
+  int32_t* const s_live = reinterpret_cast<int32_t*>(s_vy + p.threads);
+  int32_t* const s_credits = s_live + p.threads;
+  int32_t* const s_tags = s_credits + p.threads;  // per env of the workgroup: at most threads / 2
+  const int tid = threadIdx.x;
+  const int el = int(wd::dev::fastdiv(uint32_t(tid), p.div_N));  // env of the workgroup
+  const int i = tid - el * p.N;                                  // agent
+  const int e = blockIdx.x * p.envs_per_wg + el;
+  const bool valid = el < p.envs_per_wg && e < p.E;
+  const int first = el * p.N;  // slot of the env's agent 0
+  const int64_t a = int64_t(valid ? e : 0) * p.N + i;
+  const bool tagger = i < p.N_tag;
+
+  // ---- sampler: two draws per agent from one random block ------------------------------------
+  int lvl_acc = 2, lvl_turn = 2;
+  if (mode & kSample) {
+    if (valid) {
+      const wd::dev::Block4 r = philox_block(p.env_offset + uint32_t(e), uint32_t(i), g_lo, kStreamActionC | (g_hi << 8),
+                                             p.seed_lo, p.seed_hi);
+      const float2* pr = reinterpret_cast<const float2*>(probs + a * 10);
+      const float2 q0 = pr[0], q1 = pr[1], q2 = pr[2], q3 = pr[3], q4 = pr[4];
+      lvl_acc = sample_action(q0.x, q0.y, q1.x, q1.y, r.w[0]);   // probabilities 0..3 of category 0
+      lvl_turn = sample_action(q2.y, q3.x, q3.y, q4.x, r.w[1]);  // probabilities 5..8 = 0..3 of category 1
+      *reinterpret_cast<int2*>(p.action + 2 * a) = make_int2(lvl_acc, lvl_turn);
+    }
+    if (mode == kSample) return;
+  } else if ((mode & kStep) && valid) {
+    const int2 act = *reinterpret_cast<const int2*>(p.action + 2 * a);
+    lvl_acc = act.x;
+    lvl_turn = act.y;
+  }
+
+  int done_in = 0, t_in = 0, nlr_in = 0;
+  if (valid) {
+    done_in = p.done[e];
+    t_in = p.t[e];
+    nlr_in = p.n_live_runners[e];
+  }
+  const bool step_act = (mode & kStep) && valid && !done_in;
+  bool new_rows = false;
+  int t_out = t_in;
+  bool done_now = done_in != 0;
+  float x = 0.0f, y = 0.0f, v = 0.0f;
+  int h = 0, live = 0;
+  float2 dir = make_float2(1.0f, 0.0f);
+
+  if (mode & kStep) {
+    if (step_act) {
+      x = p.x[a];
+      y = p.y[a];
+      v = p.v[a];
+      h = p.h[a];
+      live = p.live[a];
+      if (live == 1) {
+        h = wrap_heading(h + (lvl_turn - 2), p.H);
+        dir = p.table[h];
+        const float vmax = tagger ? p.vmax_tagger : p.vmax_runner;
+        const float dv = static_cast<float>(lvl_acc - 2) * p.accel;
+        v = v + dv;
+        if (v < 0.0f) v = 0.0f;
+        if (v > vmax) v = vmax;
+        const float step_x = v * dir.x;
+        const float step_y = v * dir.y;
+        x = x + step_x;
+        y = y + step_y;
+        bool clamped = false;
+        if (x < 0.0f) { x = 0.0f; clamped = true; }
+        if (x > p.L) { x = p.L; clamped = true; }
+        if (y < 0.0f) { y = 0.0f; clamped = true; }
+        if (y > p.L) { y = p.L; clamped = true; }
+        if (clamped) v = 0.0f;
+        p.x[a] = x;
+        p.y[a] = y;
+        p.v[a] = v;
+        p.h[a] = h;
+      } else {
+        dir = p.table[wrap_heading(h, p.H)];
+      }
+      s_x[tid] = x;
+      s_y[tid] = y;
+      s_vx[tid] = v * dir.x;
+      s_vy[tid] = v * dir.y;
+      s_live[tid] = live;
+      s_credits[tid] = 0;
+      if (i == 0) s_tags[el] = 0;
+    }
+    __syncthreads();
+    // ---- tag test from the runner's side: nearest tagger by (d2, index) ------------------------
+    bool tagged_now = false;
+    if (step_act && !tagger && live == 1 && p.tag_r2 >= 0.0f) {
+      int best_t = 0;
+      float best_d2 = squared_distance(x, y, s_x[first], s_y[first]);
+      for (int t = 1; t < p.N_tag; ++t) {
+        const float d2 = squared_distance(x, y, s_x[first + t], s_y[first + t]);
+        if (d2 < best_d2) {
+          best_d2 = d2;
+          best_t = t;
+        }
+      }
+      if (best_d2 <= p.tag_r2) {
+        tagged_now = true;
+        live = 0;
+        s_live[tid] = 0;  // (the loops above read taggers only, and taggers stay live)
+        p.live[a] = 0;
+        atomicAdd(&s_credits[first + best_t], 1);
+        atomicAdd(&s_tags[el], 1);
+      }
+    }
+    __syncthreads();
+    // ---- rewards, clock, end of episode ---------------------------------------------------------
+    if (step_act) {
+      float rew = 0.0f;
+      if (tagger)
+        rew = static_cast<float>(s_credits[tid]) * p.tag_reward;
+      else if (tagged_now)
+        rew = p.tag_penalty;
+      p.reward[a] = rew;
+      const int tags = s_tags[el];
+      const int nlr = nlr_in - tags;
+      t_out = t_in + 1;
+      done_now = nlr == 0 || t_out >= p.T;
+      if (i == 0) {
+        p.t[e] = t_out;
+        p.n_live_runners[e] = nlr;
+        p.tags_step[e] = tags;
+        p.done[e] = done_now ? 1 : 0;
+      }
+      new_rows = true;
+    }
+  }
+
+  // ---- reset: envs that are done (or all) go back to their start state ---------------------------
+  if (mode & (kResetDone | kResetAll)) {
+    if (valid && ((mode & kResetAll) || done_now)) {
+      x = p.x0[a];
+      y = p.y0[a];
+      h = wrap_heading(p.h0[a], p.H);
+      v = 0.0f;
+      live = 1;
+      dir = p.table[h];
+      p.x[a] = x;
+      p.y[a] = y;
+      p.h[a] = h;
+      p.v[a] = v;
+      p.live[a] = 1;
+      t_out = 0;
+      if (i == 0) {
+        p.t[e] = 0;
+        p.n_live_runners[e] = p.N - p.N_tag;
+        p.tags_step[e] = 0;
+        p.done[e] = 0;
+      }
+      s_x[tid] = x;
+      s_y[tid] = y;
+      s_vx[tid] = v * dir.x;
+      s_vy[tid] = v * dir.y;
+      s_live[tid] = 1;
+      new_rows = true;
+    }
+  }
+  __syncthreads();
+
+  // ---- observation rows ---------------------------------------------------------------------------
+  if (!new_rows) return;
+  const int K = p.K;
+  uint64_t keys[kMaxK];
+#pragma unroll
+  for (int k = 0; k < kMaxK; ++k) keys[k] = ~0ull;
+  if (live == 1 && K > 0) {
+    for (int j = 0; j < p.N; ++j) {
+      if (j == i || s_live[first + j] != 1) continue;
+      const float d2 = squared_distance(s_x[first + j], s_y[first + j], x, y);
+      uint64_t key = (uint64_t(__float_as_uint(d2)) << 32) | uint32_t(j);  // d2 >= +0: its bits order like its value
+#pragma unroll
+      for (int k = 0; k < kMaxK; ++k) {
+        if (k < K && key < keys[k]) {
+          const uint64_t tmp = keys[k];
+          keys[k] = key;
+          key = tmp;
+        }
+      }
+    }
+  }
+  float* row = p.obs + a * p.D;
+  float2* row2 = reinterpret_cast<float2*>(row);  // D is even and the buffer 256-byte aligned: 8-byte pieces
+  row2[0] = make_float2(x * p.inv_L, y * p.inv_L);
+  row2[1] = make_float2(v, dir.x);
+  row2[2] = make_float2(dir.y, tagger ? 1.0f : 0.0f);
+  row2[3] = make_float2(live == 1 ? 1.0f : 0.0f, static_cast<float>(t_out) * p.inv_T);
+#pragma unroll
+  for (int k = 0; k < kMaxK; ++k) {
+    if (k < K) {
+      float2 s0 = make_float2(0.0f, 0.0f), s1 = s0, s2 = s0;
+      if (keys[k] != ~0ull) {
+        const int j = int(uint32_t(keys[k]));
+        const float dx = s_x[first + j] - x;
+        const float dy = s_y[first + j] - y;
+        s0 = make_float2(dx * p.inv_L, dy * p.inv_L);
+        s1 = make_float2(s_vx[first + j], s_vy[first + j]);
+        s2 = make_float2(j < p.N_tag ? 1.0f : 0.0f, 1.0f);
+      }
+      row2[4 + 3 * k] = s0;
+      row2[5 + 3 * k] = s1;
+      row2[6 + 3 * k] = s2;
+    }
+  }
+}
+
+}  // namespace
+}  // namespace wdc
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+struct wdc_handle {
+  wdc_config cfg;
+  wdc_buffers bufs;
+  wdc::Params params;
+  hipStream_t stream;
+  uint64_t g;
+  bool started;
+  void* table;
+  std::string last_error;
+};
+
+namespace {
+
+int check_config(const wdc_config* c) {
+  if (!c) return WD_E_NULL;
+  if (c->struct_size != sizeof(wdc_config)) return WD_E_CONFIG;
+  if (c->num_envs < 1 || c->env_offset < 0) return WD_E_CONFIG;
+  if (c->num_agents < 2 || c->num_agents > wdc::kMaxThreads) return WD_E_CONFIG;
+  if (c->num_taggers < 1 || c->num_taggers > c->num_agents - 1) return WD_E_CONFIG;
+  if (c->num_headings < 4 || c->num_headings > 4096 || c->num_headings % 4 != 0) return WD_E_CONFIG;
+  if (c->episode_length < 1) return WD_E_CONFIG;
+  if (c->obs_k < 0 || c->obs_k > wdc::kMaxK || c->obs_k > c->num_agents - 1) return WD_E_CONFIG;
+  if (!(c->world_size > 0.0f) || std::isinf(c->world_size)) return WD_E_CONFIG;
+  const float fields[] = {c->accel, c->max_speed_tagger, c->max_speed_runner, c->tag_r2, c->tag_reward, c->tag_penalty};
+  for (float f : fields)
+    if (!(f == f) || std::isinf(f)) return WD_E_CONFIG;
+  if (c->accel < 0.0f || c->max_speed_tagger < 0.0f || c->max_speed_runner < 0.0f) return WD_E_CONFIG;
+  if (int64_t(c->num_envs) * c->num_agents > int64_t(INT32_MAX) / 2) return WD_E_CONFIG;
+  return WD_OK;
+}
+
+// The heading table: the first octant from double-precision cos / sin rounded to float32, the
+// rest by reflection about the diagonal and by quarter turns; zeros are +0.
+std::vector<float2> heading_table(int H) {
+  std::vector<float2> t(H);
+  const int quarter = H / 4;
+  const double pi = 3.14159265358979323846;
+  for (int h = 0; h < H; ++h) {
+    const int turns = h / quarter;
+    int r = h % quarter;
+    const bool reflect = 2 * r > quarter;
+    if (reflect) r = quarter - r;
+    const double angle = 2.0 * pi * double(r) / double(H);
+    float c = float(std::cos(angle)), s = float(std::sin(angle));
+    if (2 * r == quarter) s = c;
+    if (reflect) std::swap(c, s);
+    for (int k = 0; k < turns; ++k) {  // a quarter turn to the left
+      const float old_c = c;
+      c = -s;
+      s = old_c;
+    }
+    t[h] = make_float2(c + 0.0f, s + 0.0f);  // (-0) + 0 = +0
+  }
+  return t;
+}
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int fail_hip(wdc_handle* h, hipError_t err, const char* what) {
+  h->last_error = std::string(what) + ": " + hipGetErrorString(err);
+  return WD_E_HIP;
+}
+
+// four float and two int arrays of one element per thread, one int per env of the workgroup
+size_t lds_bytes(const wdc::Params& p) { return size_t(p.threads) * 24 + size_t(p.threads / 2) * 4; }
+
+int launch(wdc_handle* h, int mode, const float* probs) {
+  const wdc::Params& p = h->params;
+  const int groups = (p.E + p.envs_per_wg - 1) / p.envs_per_wg;
+  hipLaunchKernelGGL(wdc::env_kernel, dim3(groups), dim3(p.threads), lds_bytes(p), h->stream, p, mode, probs, uint32_t(h->g),
+                     uint32_t(h->g >> 32));
+  const hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return fail_hip(h, err, "env_kernel launch");
+  return WD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int wdc_query_layout(const wdc_config* cfg, wdc_layout* out) {
+  if (!cfg || !out) return WD_E_NULL;
+  const int rc = check_config(cfg);
+  if (rc != WD_OK) return rc;
+  const int64_t EN = int64_t(cfg->num_envs) * cfg->num_agents;
+  out->obs_dim = 8 + 6 * cfg->obs_k;
+  out->agent_elems = EN;
+  out->action_elems = 2 * EN;
+  out->obs_elems = EN * out->obs_dim;
+  out->env_elems = cfg->num_envs;
+  out->probs_elems = 10 * EN;
+  // 40 probabilities, 20 state read, 20 state written, 8 actions, 4 reward, 4 D row; 24 per env
+  out->bytes_per_iteration = EN * (40 + 20 + 20 + 8 + 4 + 4 * int64_t(out->obs_dim)) + 24 * int64_t(cfg->num_envs);
+  return WD_OK;
+}
+
+int wdc_create(const wdc_config* cfg, const wdc_buffers* bufs, wdc_handle** out) {
+  if (!cfg || !bufs || !out) return WD_E_NULL;
+  *out = nullptr;
+  const int rc = check_config(cfg);
+  if (rc != WD_OK) return rc;
+  const void* ptrs[] = {bufs->x, bufs->y, bufs->v, bufs->h, bufs->x0, bufs->y0, bufs->h0, bufs->live,
+                        bufs->action, bufs->reward, bufs->obs, bufs->t, bufs->done, bufs->n_live_runners,
+                        bufs->tags_step};
+  for (const void* q : ptrs) {
+    if (!q) return WD_E_NULL;
+    if (!aligned(q, 256)) return WD_E_ALIGN;
+  }
+  wdc_handle* h = new (std::nothrow) wdc_handle();
+  if (!h) return WD_E_HIP;
+  h->cfg = *cfg;
+  h->bufs = *bufs;
+  h->stream = static_cast<hipStream_t>(cfg->stream);
+  h->g = 0;
+  h->started = false;
+  h->table = nullptr;
+  wdc::Params& p = h->params;
+  p.E = cfg->num_envs;
+  p.N = cfg->num_agents;
+  p.N_tag = cfg->num_taggers;
+  p.H = cfg->num_headings;
+  p.T = cfg->episode_length;
+  p.K = cfg->obs_k;
+  p.D = 8 + 6 * cfg->obs_k;
+  p.threads = p.N <= 256 ? 256 : (p.N + 63) / 64 * 64;
+  p.envs_per_wg = p.threads / p.N;
+  p.env_offset = uint32_t(cfg->env_offset);
+  p.seed_lo = uint32_t(cfg->seed);
+  p.seed_hi = uint32_t(cfg->seed >> 32);
+  p.div_N = wd::make_fastdiv(uint32_t(p.N));
+  p.L = cfg->world_size;
+  p.inv_L = float(1.0 / double(cfg->world_size));
+  p.inv_T = float(1.0 / double(cfg->episode_length));
+  p.accel = cfg->accel;
+  p.vmax_tagger = cfg->max_speed_tagger;
+  p.vmax_runner = cfg->max_speed_runner;
+  p.tag_r2 = cfg->tag_r2;
+  p.tag_reward = cfg->tag_reward;
+  p.tag_penalty = cfg->tag_penalty;
+  p.x = bufs->x; p.y = bufs->y; p.v = bufs->v; p.h = bufs->h;
+  p.x0 = bufs->x0; p.y0 = bufs->y0; p.h0 = bufs->h0;
+  p.live = bufs->live; p.action = bufs->action; p.reward = bufs->reward; p.obs = bufs->obs;
+  p.t = bufs->t; p.done = bufs->done; p.n_live_runners = bufs->n_live_runners; p.tags_step = bufs->tags_step;
+  const std::vector<float2> table = heading_table(p.H);
+  hipError_t err = hipMalloc(&h->table, sizeof(float2) * table.size());
+  if (err == hipSuccess) err = hipMemcpy(h->table, table.data(), sizeof(float2) * table.size(), hipMemcpyHostToDevice);
+  if (err != hipSuccess) {
+    if (h->table) (void)hipFree(h->table);
+    delete h;
+    return WD_E_HIP;
+  }
+  p.table = static_cast<const float2*>(h->table);
+  *out = h;
+  return WD_OK;
+}
+
+int wdc_reset(wdc_handle* h, int mode) {
+  if (!h) return WD_E_NULL;
+  if (mode != WD_RESET_ALL && mode != WD_RESET_DONE) return WD_E_CONFIG;
+  if (mode == WD_RESET_DONE) {
+    if (!h->started) return WD_E_STATE;
+    return launch(h, wdc::kResetDone, nullptr);
+  }
+  const int64_t agents = int64_t(h->params.E) * h->params.N;
+  hipLaunchKernelGGL(wdc::init_kernel, dim3(uint32_t((agents + 255) / 256)), dim3(256), 0, h->stream, h->params);
+  const hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return fail_hip(h, err, "init_kernel launch");
+  h->g = 0;
+  const int rc = launch(h, wdc::kResetAll, nullptr);
+  if (rc == WD_OK) h->started = true;
+  return rc;
+}
+
+int wdc_sample(wdc_handle* h, const float* probs) {
+  if (!h || !probs) return WD_E_NULL;
+  if (!aligned(probs, 8)) return WD_E_ALIGN;
+  if (!h->started) return WD_E_STATE;
+  return launch(h, wdc::kSample, probs);
+}
+
+int wdc_step(wdc_handle* h) {
+  if (!h) return WD_E_NULL;
+  if (!h->started) return WD_E_STATE;
+  const int rc = launch(h, wdc::kStep, nullptr);
+  if (rc == WD_OK) ++h->g;
+  return rc;
+}
+
+int wdc_iterate(wdc_handle* h, const float* probs) {
+  if (!h || !probs) return WD_E_NULL;
+  if (!aligned(probs, 8)) return WD_E_ALIGN;
+  if (!h->started) return WD_E_STATE;
+  const int rc = launch(h, wdc::kSample | wdc::kStep | wdc::kResetDone, probs);
+  if (rc == WD_OK) ++h->g;
+  return rc;
+}
+
+int wdc_get_step(const wdc_handle* h, uint64_t* g) {
+  if (!h || !g) return WD_E_NULL;
+  *g = h->g;
+  return WD_OK;
+}
+
+int wdc_set_step(wdc_handle* h, uint64_t g) {
+  if (!h) return WD_E_NULL;
+  h->g = g;
+  return WD_OK;
+}
+
+int wdc_destroy(wdc_handle* h) {
+  if (!h) return WD_OK;
+  if (h->table) (void)hipFree(h->table);
+  delete h;
+  return WD_OK;
+}
+
+const char* wdc_last_error(const wdc_handle* h) { return h ? h->last_error.c_str() : ""; }
+
+}  // extern "C"

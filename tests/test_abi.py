@@ -168,3 +168,52 @@ def test_missing_library_fails_loudly(tmp_path, monkeypatch):
         binding.load_library(str(tmp_path / "libwd.so"))
     monkeypatch.undo()
     wd.load_library()
+
+
+# ---------------------------------------------------------------- continuous Tag (include/wdc.h)
+def declared_continuous_symbols():
+    text = open(os.path.join(ROOT, "include", "wdc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(wdc_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_continuous_symbol():
+    lib = wd.load_library()
+    names = declared_continuous_symbols()
+    assert {"wdc_create", "wdc_reset", "wdc_sample", "wdc_step", "wdc_iterate", "wdc_destroy",
+            "wdc_query_layout"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+        assert callable(getattr(binding, n)), n
+
+
+def test_continuous_layout_and_rejections():
+    lay = binding.wdc_query_layout(binding.make_cconfig(2000, 5, 1, 500))
+    assert lay.obs_dim == 32 and lay.agent_elems == 10_000 and lay.action_elems == 20_000
+    assert lay.obs_elems == 320_000 and lay.env_elems == 2000 and lay.probs_elems == 100_000
+    assert lay.bytes_per_iteration == 10_000 * (40 + 20 + 20 + 8 + 4 + 128) + 24 * 2000
+    good = dict(num_envs=4, num_agents=6, num_taggers=2, episode_length=20)
+    for over in (dict(num_envs=0), dict(num_agents=1), dict(num_agents=1025), dict(num_taggers=0),
+                 dict(num_taggers=6), dict(num_headings=6), dict(num_headings=0), dict(num_headings=8192),
+                 dict(episode_length=0), dict(obs_k=9), dict(obs_k=6), dict(obs_k=-1), dict(world_size=0.0),
+                 dict(world_size=float("nan")), dict(accel=-1.0), dict(tag_reward=float("inf")), dict(env_offset=-2)):
+        with pytest.raises(wd.WdError) as ei:
+            binding.wdc_query_layout(binding.make_cconfig(**{**good, **over}))
+        assert ei.value.status == binding.WD_E_CONFIG, over
+    cfg = binding.make_cconfig(**good)
+    cfg.struct_size = 12
+    with pytest.raises(wd.WdError) as ei:
+        binding.wdc_query_layout(cfg)
+    assert ei.value.status == binding.WD_E_CONFIG
+    bufs = binding.wdc_buffers(*[0x10000 + 0x1000 * i for i in range(len(binding.CBUFFER_NAMES))])
+    bufs.obs = 0
+    with pytest.raises(wd.WdError) as ei:
+        binding.wdc_create(binding.make_cconfig(**good), bufs)
+    assert ei.value.status == binding.WD_E_NULL
+    bufs.obs = 0x20010
+    with pytest.raises(wd.WdError) as ei:
+        binding.wdc_create(binding.make_cconfig(**good), bufs)
+    assert ei.value.status == binding.WD_E_ALIGN
+    lib = wd.load_library()
+    assert lib.wdc_reset(None, 0) == binding.WD_E_NULL and lib.wdc_step(None) == binding.WD_E_NULL
+    assert lib.wdc_iterate(None, None) == binding.WD_E_NULL and lib.wdc_destroy(None) == binding.WD_OK
