@@ -271,6 +271,109 @@ def time_oracle(cfg, ring, envs_per_thread, iterations, threads):
     return n_envs * iterations / dt, used, dt
 
 
+def continuous_ring(cfg, device="cuda:0"):
+    """A ring of RING steps of [E, N, 2, 5] probabilities (softmax of N(0,1) logits per category) on the device."""
+    import torch
+
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(cfg.seed))
+    logits = torch.randn((RING, cfg.num_envs, cfg.num_agents, 2, 5), generator=gen, device=device, dtype=torch.float32)
+    return torch.softmax(logits, dim=-1).contiguous()
+
+
+def time_continuous(cfg, ring, steps, warmup):
+    """Continuous Tag (paper Sec. 5.1, second variant; Sec. 5.3 quotes it at 2000 envs x 5 agents): `steps`
+    wdc_iterate launches after `warmup` from the reset state.  Returns (wall seconds, event seconds,
+    algorithmic bytes per iteration)."""
+    import torch
+    import paper_2108_13976_amd as wd
+
+    env = wd.CTagEnvs(device="cuda:0", **cfg.kwargs())
+    env.reset(wd.WD_RESET_ALL)
+    for k in range(warmup):
+        env.iterate(ring[k % RING])
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    s.record(env.torch_stream)
+    for k in range(steps):
+        env.iterate(ring[(warmup + k) % RING])
+    e.record(env.torch_stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    out = wall, s.elapsed_time(e) / 1e3, env.layout.bytes_per_iteration
+    env.close()
+    return out
+
+
+def continuous_figures(cfg, steps=None, warmup=50):
+    steps = steps or 2 * cfg.episode_length
+    ring = continuous_ring(cfg)
+    runs = sorted(time_continuous(cfg, ring, steps, warmup) for _ in range(3))
+    wall, ev, nbytes = runs[1]
+    return {"us_per_iteration": ev / steps * 1e6, "env_steps_per_s": steps / wall * cfg.num_envs,
+            "agent_steps_per_s": steps / wall * cfg.num_envs * cfg.num_agents, "iterations": steps, "warmup": warmup,
+            "algorithmic_bytes_per_iteration": nbytes, "hbm_frac": nbytes / (ev / steps) / 1e9 / HBM_PEAK_GBS}
+
+
+def time_continuous_oracle(cfg, envs, iterations, threads):
+    import numpy as np
+    from oracle import ctag_oracle, tag_oracle
+    from workloads import ctag_probs_for_step
+
+    kw = cfg.kwargs()
+    kw["num_envs"] = envs
+    orc = ctag_oracle.CTagOracle(**kw)
+    probs = [ctag_probs_for_step(cfg.seed, g, envs, cfg.num_agents) for g in range(RING)]
+
+    def work(shard):
+        lo = shard.cfg.env_offset
+        shard.reset()
+        for g in range(iterations):
+            shard.iterate(np.ascontiguousarray(probs[g % RING][lo:lo + shard.E]), g)
+
+    t0 = time.perf_counter()
+    used = tag_oracle.run_sharded(orc, work, threads)
+    dt = time.perf_counter() - t0
+    return envs * iterations / dt, used, dt
+
+
+def main_continuous(args):
+    """bench.py --workload ctag_*: the same JSON line for a continuous-Tag workload."""
+    from workloads import CTAG_CONFIGS
+
+    cfg = CTAG_CONFIGS[args.workload]
+    ring = continuous_ring(cfg)
+    time_continuous(cfg, ring, 400, 0)  # untimed: the device leaves its idle clocks
+    wall, ev, nbytes = time_continuous(cfg, ring, args.steps, args.warmup)
+    gbs = nbytes / (ev / args.steps) / 1e9
+    out = {
+        "metric": "env_steps_per_s", "value": args.steps / wall * cfg.num_envs, "unit": "env-steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * wall / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32 state, rewards and observations", "data": "synthetic",
+        "config": {"workload": args.workload, "num_envs": cfg.num_envs, "num_agents": cfg.num_agents,
+                   "num_taggers": cfg.num_taggers, "world_size": cfg.world_size, "num_headings": cfg.num_headings,
+                   "episode_length": cfg.episode_length, "obs": f"partial K={cfg.obs_k}", "seed": cfg.seed, "mode": "fused",
+                   "probs": f"softmax(N(0,1)) float32 per action category, ring of {RING} steps resident in HBM"},
+        "agent_steps_per_s": args.steps / wall * cfg.num_envs * cfg.num_agents,
+        "paper_env_steps_per_s_a100": 8.3e6 if args.workload == "ctag_2000x5" else None,
+        "roofline": {"bound": "hbm", "kernel": "wdc env_kernel (sample + step + reset fused)", "achieved": gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                     "algorithmic_bytes_per_launch": nbytes, "avg_launch_us": ev / args.steps * 1e6, "traffic": None,
+                     "window": f"{args.steps} iterations after {args.warmup} from the reset state"},
+    }
+    if not args.no_cpu_baseline:
+        threads = max(1, min(16, os.cpu_count() or 1))
+        envs = min(cfg.num_envs, 64 * threads)
+        probe, _, _ = time_continuous_oracle(cfg, envs, 20, threads)
+        iters = int(max(40, min(20000, 10.0 * probe / envs)))  # about 10 s of oracle work
+        value, used, dt = time_continuous_oracle(cfg, envs, iters, threads)
+        out["cpu_baseline"] = {"value": value, "unit": "env-steps/s", "cores": used, "kind": "oracle",
+                               "sample": f"first {envs} envs of {args.workload} x {iters} iterations from the reset state, "
+                                         f"one single-threaded oracle per core on disjoint envs ({dt:.1f} s wall)"}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -313,6 +416,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_mib": args.copy_probe_mib, "reads_kib": args.copy_probe_mib * 1024,
                           "writes_kib": args.copy_probe_mib * 1024}))
+        return
+    if args.workload.startswith("ctag_"):
+        main_continuous(args)
         return
     cfg = CONFIGS[args.workload]
     if args.obs == "full":
@@ -449,6 +555,9 @@ def main():
                                     "resets_per_iteration": w["resets_per_iteration"]}
                 del other_ring
             extras["configs"] = per_config
+            # continuous Tag (paper Sec. 5.1, second variant): its three workloads, 2 T iterations after 50
+            from workloads import CTAG_CONFIGS
+            extras["continuous_tag"] = {name: continuous_figures(c) for name, c in CTAG_CONFIGS.items()}
         out["extras"] = extras
 
     if not args.no_cpu_baseline:

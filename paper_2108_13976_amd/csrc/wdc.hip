@@ -76,6 +76,8 @@ __device__ __forceinline__ float squared_distance(float xa, float ya, float xb, 
   return dx2 + dy2;
 }
 
+// KT: length of the register list of nearest keys (4 or 8, at least K)
+template <int KT>
 __global__ __launch_bounds__(kMaxThreads) void env_kernel(const Params p, const int mode, const float* __restrict__ probs,
                                                            const uint32_t g_lo, const uint32_t g_hi) {
   // per local agent slot: moved position, velocity components, live flag, credits (taggers)
@@ -249,16 +251,16 @@ __global__ __launch_bounds__(kMaxThreads) void env_kernel(const Params p, const 
   // ---- observation rows ---------------------------------------------------------------------------
   if (!new_rows) return;
   const int K = p.K;
-  uint64_t keys[kMaxK];
+  uint64_t keys[KT];
 #pragma unroll
-  for (int k = 0; k < kMaxK; ++k) keys[k] = ~0ull;
+  for (int k = 0; k < KT; ++k) keys[k] = ~0ull;
   if (live == 1 && K > 0) {
     for (int j = 0; j < p.N; ++j) {
       if (j == i || s_live[first + j] != 1) continue;
       const float d2 = squared_distance(s_x[first + j], s_y[first + j], x, y);
       uint64_t key = (uint64_t(__float_as_uint(d2)) << 32) | uint32_t(j);  // d2 >= +0: its bits order like its value
 #pragma unroll
-      for (int k = 0; k < kMaxK; ++k) {
+      for (int k = 0; k < KT; ++k) {
         if (k < K && key < keys[k]) {
           const uint64_t tmp = keys[k];
           keys[k] = key;
@@ -274,7 +276,7 @@ __global__ __launch_bounds__(kMaxThreads) void env_kernel(const Params p, const 
   row2[2] = make_float2(dir.y, tagger ? 1.0f : 0.0f);
   row2[3] = make_float2(live == 1 ? 1.0f : 0.0f, static_cast<float>(t_out) * p.inv_T);
 #pragma unroll
-  for (int k = 0; k < kMaxK; ++k) {
+  for (int k = 0; k < KT; ++k) {
     if (k < K) {
       float2 s0 = make_float2(0.0f, 0.0f), s1 = s0, s2 = s0;
       if (keys[k] != ~0ull) {
@@ -367,8 +369,12 @@ size_t lds_bytes(const wdc::Params& p) { return size_t(p.threads) * 24 + size_t(
 int launch(wdc_handle* h, int mode, const float* probs) {
   const wdc::Params& p = h->params;
   const int groups = (p.E + p.envs_per_wg - 1) / p.envs_per_wg;
-  hipLaunchKernelGGL(wdc::env_kernel, dim3(groups), dim3(p.threads), lds_bytes(p), h->stream, p, mode, probs, uint32_t(h->g),
-                     uint32_t(h->g >> 32));
+  if (p.K <= 4)
+    hipLaunchKernelGGL(wdc::env_kernel<4>, dim3(groups), dim3(p.threads), lds_bytes(p), h->stream, p, mode, probs,
+                       uint32_t(h->g), uint32_t(h->g >> 32));
+  else
+    hipLaunchKernelGGL(wdc::env_kernel<wdc::kMaxK>, dim3(groups), dim3(p.threads), lds_bytes(p), h->stream, p, mode, probs,
+                       uint32_t(h->g), uint32_t(h->g >> 32));
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) return fail_hip(h, err, "env_kernel launch");
   return WD_OK;
