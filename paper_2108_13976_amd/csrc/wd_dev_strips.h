@@ -336,6 +336,20 @@ __device__ __forceinline__ bool strip_window_search(uint32_t (&keys)[K], uint32_
   return reach2 >= kFarSq || (!(kth & kDeadBit) && (kth >> ib) < reach2);
 }
 
+// A list of a few dozen agents: every entry is a candidate (exact without any bound; every lane
+// reads the same entry, and 8 instructions per entry undercut the fixed windows).
+template <int K>
+__device__ __forceinline__ void strip_scan_all(uint32_t (&keys)[K], uint32_t me, uint32_t q, uint32_t n_sorted, int ib,
+                                               const uint32_t* __restrict__ pos, const uint16_t* __restrict__ id) {
+  const short2v mev = __builtin_bit_cast(short2v, me);
+#pragma unroll
+  for (int k = 0; k < K; ++k) keys[k] = ~0u;
+  for (uint32_t s = 0; s < n_sorted; ++s) {
+    const uint32_t key = (squared_length(__builtin_bit_cast(short2v, pos[s]) - mev) << ib) | uint32_t(id[s]);
+    insert_key<K>(keys, s == q ? ~0u : key);
+  }
+}
+
 // Exact search for the agents that the windows did not settle: all bins within m strip heights
 // of the agent, m doubling until the K-th key is nearer than the nearest cell outside the block
 // (or the block covers the grid).

@@ -32,6 +32,7 @@ constexpr int strip_pad(int k) {
   const int a = strip_half_own(k) + 2 * strip_half_adj(k), b = 2 * strip_half_adj2(k), c = strip_half_own2(k);
   return a > b ? (a > c ? a : c) : (b > c ? b : c);
 }
+constexpr int kStripScanAll = 64;  // lists up to this length are scanned whole instead of through windows
 constexpr int kStripQueue2 = 32;  // agents per env that may wait for the third, exact block search
 constexpr uint32_t kStreamAction = 0;   // random streams (low byte of the fourth counter word)
 constexpr uint32_t kStreamInit = 1;

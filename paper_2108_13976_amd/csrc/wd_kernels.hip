@@ -484,15 +484,21 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
     if constexpr (STRIP) {
       // the fixed windows of the strip-sorted list; what they do not settle is queued
       for_each_wave_team([&](const TeamLds<WIDE, BIG>& Lt, const Strips st, int n_sorted) {
+        const bool few = n_sorted <= kStripScanAll;  // (uniform: an env's whole list is cheaper than its windows)
         for (int q = wave_lane; q < n_sorted; q += wave_stride) {
           const uint32_t me = Lt.sorted.pos[q];
           if (int(me >> 16) < p.dead_dx) {  // not tagged in this step
             Key keys[KT];
-            if (strip_window_search<KX, strip_half_own(KX), strip_half_adj(KX), 0, false>(
-                    keys, me, q, 0, st, p.idx_bits, n_sorted, p.pad_l, Lt.sorted.pos, Lt.sorted.id, Lt.starts, Lt.edges))
+            if (few) {
+              strip_scan_all<KX>(keys, me, uint32_t(q), uint32_t(n_sorted), p.idx_bits, Lt.sorted.pos, Lt.sorted.id);
               put_neighbours_of(Lt, Lt.sorted.id[q], keys);
-            else
+            } else if (strip_window_search<KX, strip_half_own(KX), strip_half_adj(KX), 0, false>(
+                           keys, me, q, 0, st, p.idx_bits, n_sorted, p.pad_l, Lt.sorted.pos, Lt.sorted.id, Lt.starts,
+                           Lt.edges)) {
+              put_neighbours_of(Lt, Lt.sorted.id[q], keys);
+            } else {
               Lt.retry[atomicAdd(&Lt.misc[3], 1)] = uint16_t(q);
+            }
           }
         }
       });
@@ -898,7 +904,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
 
 template <int WIDE, int KX, bool CN, bool BIG, bool ONE>
 __global__ __launch_bounds__(BIG ? kBigEnvWorkgroupSize : kMaxEnvWorkgroupSize)
-    __attribute__((amdgpu_waves_per_eu((WIDE || BIG || KX <= 0 || KX > 4) ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
+    __attribute__((amdgpu_waves_per_eu((WIDE || BIG || KX <= 1 || KX > 4) ? 4 : 8, 8))) void env_kernel(const Params p, const int mode,
                                                              const float* __restrict__ probs, uint32_t g_lo,
                                                              uint32_t g_hi) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -1001,7 +1007,7 @@ struct RollArgs {  // the one kernel argument of rollout_kernel
 
 template <int WIDE, int KX, bool CN, bool ONE>
 __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
-    __attribute__((amdgpu_waves_per_eu((WIDE || KX == 0 || KX > 4) ? 4 : 8, 8))) void rollout_kernel(const RollArgs args) {
+    __attribute__((amdgpu_waves_per_eu((WIDE || KX <= 1 || KX > 4) ? 4 : 8, 8))) void rollout_kernel(const RollArgs args) {
   extern __shared__ __align__(16) unsigned char smem[];
   // The loop reads its parameters from the kernel-argument segment (args is the only argument,
   // at offset 0) through a pointer that is opaque to the optimiser in every iteration: loads of
