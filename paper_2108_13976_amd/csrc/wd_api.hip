@@ -174,7 +174,8 @@ bool plan_strip_layout(const wd_config& c, wd::Params* p) {
 
 // Launch geometry and LDS map of the env-per-team kernels.  Returns false if an env does
 // not fit one workgroup's LDS.
-bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
+// (`big_tables_in_lds`: a large env also keeps slots, tag keys and credits in LDS when they fit)
+bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big, bool big_tables_in_lds = false) {
   const int N = c.num_agents, G = c.grid_size;
   p->NG = (N + 3) / 4;
   p->big = big ? 1 : 0;
@@ -295,7 +296,8 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big) {
   p->off_starts = take(2ll * (nb_cap + 4));
   p->x_stride = int32_t(off);
   off = 0;
-  if (!big) {
+  p->big_lds_tables = (big && big_tables_in_lds) ? 1 : 0;
+  if (!big || big_tables_in_lds) {
     p->off_slot = take(2 * NPAD);
     p->off_best = take(key_bytes * NPAD);
     p->off_credits = take(4ll * c.num_taggers);
@@ -394,14 +396,22 @@ int fill_params(const wd_config& c, const wd_buffers& b, wd::Params* p) {
   const int64_t pair_up_to = c.num_agents <= 1024 ? 3ll * c.num_agents / 10 : 450;  // envs
   const bool prefer_pair = pair_serves && c.num_agents >= 384 && c.num_envs <= pair_up_to;
   const wd::Params filled = *p;
-  bool planned = prefer_pair && plan_env_kernels(c, p, true);
+  bool planned = prefer_pair && plan_env_kernels(c, p, true, true);
+  if (!planned && prefer_pair) {
+    *p = filled;
+    planned = plan_env_kernels(c, p, true);
+  }
   if (!planned) {
     *p = filled;
     planned = plan_env_kernels(c, p, false);
   }
   if (!planned && !prefer_pair) {
     *p = filled;
-    planned = plan_env_kernels(c, p, true);
+    planned = plan_env_kernels(c, p, true, true);
+    if (!planned) {
+      *p = filled;
+      planned = plan_env_kernels(c, p, true);
+    }
   }
   if (!planned || !wd::env_kernel_available(*p)) return WD_E_UNSUPPORTED;
   return WD_OK;

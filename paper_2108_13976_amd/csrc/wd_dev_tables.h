@@ -178,7 +178,8 @@ __device__ __forceinline__ int bucket_of(int x, int y, const Buckets bk) {
 }
 
 // Views of one team's tables: in LDS, except that a large env (BIG) keeps slots, tag keys and
-// credits in device memory (and has no neighbour lists: its rows come from big_obs_kernel).
+// credits in device memory unless they fit LDS too (and has no neighbour lists: its rows come
+// from big_obs_kernel).
 template <int WIDE, bool BIG>
 struct TeamLds {
   using Key = typename SortedList<WIDE>::Key;
@@ -216,9 +217,15 @@ struct TeamLds {
       nbr = nullptr;  // no neighbour lists: big_obs_kernel writes rows straight from the search
       nbr_lo = nullptr;
       nbr_hi = nullptr;
-      slot = p.g_slot + env * p.g_stride_agents;
-      best = reinterpret_cast<Key*>(p.g_best) + env * p.g_stride_agents;
-      credits = p.g_credits + env * p.g_stride_credits;
+      if (p.big_lds_tables) {  // (the pointers are generic then: either address space)
+        slot = reinterpret_cast<uint16_t*>(yr + p.off_slot);
+        best = reinterpret_cast<Key*>(yr + p.off_best);
+        credits = reinterpret_cast<int32_t*>(yr + p.off_credits);
+      } else {
+        slot = p.g_slot + env * p.g_stride_agents;
+        best = reinterpret_cast<Key*>(p.g_best) + env * p.g_stride_agents;
+        credits = p.g_credits + env * p.g_stride_credits;
+      }
     } else {
       nbr = reinterpret_cast<uint16_t*>(yr + p.off_nbr);
       nbr_lo = reinterpret_cast<uint32_t*>(yr + p.off_nbr);

@@ -100,6 +100,7 @@ struct Params {
   // neighbour lists live in library-owned device memory instead of LDS (per-env strides in
   // elements of each array's type).
   int32_t big;
+  int32_t big_lds_tables;  // 1: slots, tag keys and credits of a large env are in LDS after all (they fit)
   uint16_t* g_slot;
   void* g_best;
   int32_t* g_credits;
