@@ -20,6 +20,12 @@ struct wd_handle {
   bool started;        // wd_reset(WD_RESET_ALL) has run
   bool rows_valid;     // bufs.obs holds the rows this library wrote for the current state
   void* scratch;       // device memory of the large-env tables (NULL for the small layout)
+  // roll-outs of the large-env layout: a second stream for the observation kernels, a second
+  // table image and two events per image (created by the first such roll-out, freed by wd_destroy)
+  hipStream_t obs_stream;
+  hipEvent_t tables_ready[2], rows_done[2];
+  void* second_image;
+  bool pipe_ready;
   std::string last_error;
 };
 
@@ -437,6 +443,22 @@ int64_t place_big_tables(wd::Params* p, int64_t E, unsigned char* base) {
   return slot_b + best_b + cred_b + image_b;
 }
 
+// What a roll-out of the large-env layout needs to run the observation kernel of one iteration
+// beside the step kernel of the next: a stream of default priority, events, a second table image.
+int ensure_pipe(wd_handle* h) {
+  if (h->pipe_ready) return WD_OK;
+  hipError_t err = hipStreamCreateWithFlags(&h->obs_stream, hipStreamNonBlocking);
+  if (err != hipSuccess) return hip_failed(h, err, "stream for the observation kernels");
+  for (int b = 0; b < 2 && err == hipSuccess; ++b) {
+    err = hipEventCreateWithFlags(&h->tables_ready[b], hipEventDisableTiming);
+    if (err == hipSuccess) err = hipEventCreateWithFlags(&h->rows_done[b], hipEventDisableTiming);
+  }
+  if (err == hipSuccess) err = hipMalloc(&h->second_image, size_t(h->params.g_stride_image) * size_t(h->params.E));
+  if (err != hipSuccess) return hip_failed(h, err, "events and second table image of a roll-out");
+  h->pipe_ready = true;
+  return WD_OK;
+}
+
 // The work tables of wd_iterate_static: one array per device, held until the process ends.
 constexpr size_t kStaticScratchBytes = size_t(WD_STATIC_SCRATCH_BYTES);
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
@@ -494,6 +516,9 @@ int wd_create(const wd_config* cfg, const wd_buffers* bufs, wd_handle** out) {
   h->g = 0;
   h->started = false;
   h->rows_valid = false;
+  h->obs_stream = nullptr;
+  h->second_image = nullptr;
+  h->pipe_ready = false;
   *out = h;
   return WD_OK;
 }
@@ -609,10 +634,30 @@ int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const
     // Configurations without a multi-step kernel (large-env layout, full observations,
     // K > 8): the same results from one launch of the iteration kernels per iteration,
     // outputs redirected to the slices, the last slice copied from the in-place buffers.
+    // In the large-env layout the observation kernel of iteration s runs on a second stream beside
+    // the step kernel of iteration s + 1 (which needs the state, not the rows): two table images
+    // in turn, an image rewritten only once the observation kernel that read it has finished.
+    const bool piped = h->params.big && k > 1;
+    if (piped) {
+      const int rc = ensure_pipe(h);
+      if (rc != WD_OK) return rc;
+    }
     const int64_t EN = int64_t(h->cfg.num_envs) * h->cfg.num_agents, D = h->params.D;
     for (int s = 0; s < k; ++s) {
       wd::Params q = h->params;
       q.rows_kept = rows_kept;
+      wd::ObsPipe pipe = {};
+      if (piped) {
+        const int b = s & 1;
+        if (b) q.g_image = static_cast<unsigned char*>(h->second_image);
+        if (s >= 2) {
+          const hipError_t werr = hipStreamWaitEvent(h->stream, h->rows_done[b], 0);
+          if (werr != hipSuccess) return hip_failed(h, werr, "wait for a table image");
+        }
+        pipe.stream = h->obs_stream;
+        pipe.tables_ready = h->tables_ready[b];
+        pipe.rows_done = h->rows_done[b];
+      }
       if (out && s + 1 < k) {
         if (out->action) q.action = out->action + int64_t(s) * EN;
         if (out->reward) q.reward = out->reward + int64_t(s) * EN;
@@ -620,8 +665,13 @@ int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const
       }
       q.done_log = (out && out->done) ? out->done + int64_t(s) * h->cfg.num_envs : nullptr;
       const float* probs = probs_ring + int64_t((h->g + uint64_t(s)) % uint64_t(ring_len)) * EN * wd::kNumActions;
-      const hipError_t err = wd::launch_env_kernel(q, wd::kModeIterate, probs, h->g + uint64_t(s), h->stream);
+      const hipError_t err = wd::launch_env_kernel(q, wd::kModeIterate, probs, h->g + uint64_t(s), h->stream,
+                                                   piped ? &pipe : nullptr);
       if (err != hipSuccess) return hip_failed(h, err, "iteration kernel of a roll-out");
+    }
+    if (piped) {  // what follows on the caller's stream sees every row
+      const hipError_t werr = hipStreamWaitEvent(h->stream, h->rows_done[(k - 1) & 1], 0);
+      if (werr != hipSuccess) return hip_failed(h, werr, "wait for the last observation kernel");
     }
     if (out) {
       const int64_t last = int64_t(k - 1) * EN;
@@ -680,6 +730,15 @@ int wd_invalidate_obs(wd_handle* h) {
 int wd_destroy(wd_handle* h) {
   if (!h) return WD_E_NULL;
   if (h->scratch) (void)hipFree(h->scratch);
+  if (h->pipe_ready) {
+    (void)hipStreamSynchronize(h->obs_stream);
+    (void)hipFree(h->second_image);
+    for (int b = 0; b < 2; ++b) {
+      (void)hipEventDestroy(h->tables_ready[b]);
+      (void)hipEventDestroy(h->rows_done[b]);
+    }
+    (void)hipStreamDestroy(h->obs_stream);
+  }
   delete h;
   return WD_OK;
 }

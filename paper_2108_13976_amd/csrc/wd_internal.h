@@ -134,7 +134,16 @@ enum EnvKernelMode { kModeStep = 0, kModeResetAll = 1, kModeResetDone = 2, kMode
 // Launchers (wd_kernels.hip).  Each enqueues on `stream` and returns the HIP status of the launch.
 hipError_t launch_sample(const Params& p, const float* probs, uint64_t g, hipStream_t stream);
 hipError_t launch_init_start_positions(const Params& p, hipStream_t stream);
-hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream);
+// Large-env layout only: where the observation kernel of a call runs when it is not to hold up the
+// caller's stream (roll-outs overlap it with the next iteration's step kernel).  The launcher
+// records `tables_ready` on the caller's stream behind the step kernel, makes `stream` wait for
+// it, launches the observation kernel there and records `rows_done` behind it.
+struct ObsPipe {
+  hipStream_t stream;
+  hipEvent_t tables_ready, rows_done;
+};
+hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream,
+                             const ObsPipe* pipe = nullptr);
 hipError_t launch_rollout(const Params& p, const Roll& roll, const float* ring, uint64_t g, hipStream_t stream);
 bool rollout_available(const Params& p);
 // True if the env-per-team kernels cover this configuration.

@@ -1073,9 +1073,10 @@ template <int WIDE, int KX, bool BIG>
 constexpr bool kHasOneTeamVariant = WIDE == 0 && !BIG && KX > 0;
 
 template <int WIDE, int KX, bool CN, bool BIG, bool ONE = false>
-hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream) {
+hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream,
+                              const ObsPipe* pipe) {
   if constexpr (!ONE && kHasOneTeamVariant<WIDE, KX, BIG>) {
-    if (p.teams_per_wg == 1) return launch_env_variant<WIDE, KX, CN, BIG, true>(p, mode, probs, g, stream);
+    if (p.teams_per_wg == 1) return launch_env_variant<WIDE, KX, CN, BIG, true>(p, mode, probs, g, stream, pipe);
   }
   const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
   hipError_t lds_err = ensure_dynamic_lds(&env_kernel<WIDE, KX, CN, BIG, ONE>, p.lds_bytes);
@@ -1085,12 +1086,21 @@ hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uin
   hipError_t err = hipGetLastError();
   if constexpr (BIG) {
     if (err != hipSuccess) return err;
-    // stream order puts the observation kernel behind the tables it reads
+    // stream order puts the observation kernel behind the tables it reads; with a pipe it runs on
+    // the pipe's stream behind an event, so that the caller's stream can go on with the next step
     err = ensure_dynamic_lds(&big_obs_kernel<WIDE, KX>, p.y_base);
     if (err != hipSuccess) return err;
+    hipStream_t obs_stream = stream;
+    if (pipe) {
+      err = hipEventRecord(pipe->tables_ready, stream);
+      if (err == hipSuccess) err = hipStreamWaitEvent(pipe->stream, pipe->tables_ready, 0);
+      if (err != hipSuccess) return err;
+      obs_stream = pipe->stream;
+    }
     hipLaunchKernelGGL((big_obs_kernel<WIDE, KX>), dim3(p.E * p.big_slices), dim3(kBigObsWorkgroupSize),
-                       size_t(p.y_base), stream, p);
+                       size_t(p.y_base), obs_stream, p);
     err = hipGetLastError();
+    if (pipe && err == hipSuccess) err = hipEventRecord(pipe->rows_done, pipe->stream);
   }
   return err;
 }
@@ -1163,8 +1173,9 @@ int variant_of(const Params& p) {
     return fn<true, -1, false, false>(p, ##__VA_ARGS__);                                   \
   } while (0)
 
-hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream) {
-  WD_DISPATCH(launch_env_variant, mode, probs, g, stream);
+hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream,
+                             const ObsPipe* pipe) {
+  WD_DISPATCH(launch_env_variant, mode, probs, g, stream, pipe);
 }
 
 bool rollout_available(const Params& p) { return !p.big && p.obs_mode == 0 && p.K <= kMaxRegisterK; }
