@@ -313,23 +313,25 @@ __device__ __forceinline__ uint32_t squared_length(short2v d) {
 }
 
 // The agents in slots [qb, qe) of the bucket-sorted list as candidates for the key list of the agent
-// at (x, y); one overload per key form.
-template <int KT>
+// at (x, y); one overload per key form.  ABOVE: only keys greater than `floor` count (the search
+// for neighbours beyond those already found).
+template <int KT, bool ABOVE = false>
 __device__ __forceinline__ void scan_range(unsigned long long (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y,
-                                           int ib, const SortedList<kKeys64>& sorted) {
+                                           int ib, const SortedList<kKeys64>& sorted, unsigned long long floor = 0) {
   for (uint32_t q = qb; q < qe; ++q) {
     const Ent ent = sorted.get(q);
     const int dx = SortedList<kKeys64>::x(ent) - x, dy = SortedList<kKeys64>::y(ent) - y;
     const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
     unsigned long long key = ((unsigned long long)(d2) << ib) | (unsigned long long)(ent.id);
     if (sorted.dead(ent)) key = key_none<unsigned long long>();
+    if (ABOVE && key <= floor) key = key_none<unsigned long long>();
     insert_key<KT>(keys, key);
   }
 }
 
-template <int KT>
+template <int KT, bool ABOVE = false>
 __device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y, int ib,
-                                           const SortedList<kKeys31>& sorted) {
+                                           const SortedList<kKeys31>& sorted, uint32_t floor = 0) {
   const short2v me = __builtin_bit_cast(short2v, uint32_t(x) | (uint32_t(y) << 16));
   // one running pointer per array, the loop ends on the first: three instructions of loop
   // overhead per candidate
@@ -338,13 +340,15 @@ __device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, ui
   const uint16_t* id = sorted.id + qb;
   for (; pos < pos_end; ++pos, ++id) {
     const short2v d = __builtin_bit_cast(short2v, *pos) - me;  // (dx, dy), one packed subtract
-    insert_key<KT>(keys, (squared_length(d) << ib) | uint32_t(*id));
+    uint32_t key = (squared_length(d) << ib) | uint32_t(*id);
+    if (ABOVE && key <= floor) key = ~0u;
+    insert_key<KT>(keys, key);
   }
 }
 
-template <int KT>
+template <int KT, bool ABOVE = false>
 __device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, uint32_t qe, int x, int y, int ib,
-                                           const SortedList<kKeys32>& sorted) {
+                                           const SortedList<kKeys32>& sorted, uint32_t floor = 0) {
   const short2v me = __builtin_bit_cast(short2v, uint32_t(x) | (uint32_t(y) << 16));
   for (uint32_t q = qb; q < qe; ++q) {
     const short2v d = __builtin_bit_cast(short2v, sorted.pos[q]) - me;
@@ -352,7 +356,9 @@ __device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, ui
     const uint32_t idv = sorted.id[q];
     // a marked entry becomes the empty key (all ones): sign-extend the flag bit over the key
     const uint32_t dead_mask = uint32_t(int32_t(idv << 16) >> 31);
-    insert_key<KT>(keys, ((d2 << ib) | idv) | dead_mask);
+    uint32_t key = ((d2 << ib) | idv) | dead_mask;
+    if (ABOVE && key <= floor) key = ~0u;
+    insert_key<KT>(keys, key);
   }
 }
 
@@ -363,11 +369,12 @@ __device__ __forceinline__ void scan_range(uint32_t (&keys)[KT], uint32_t qb, ui
 // and only the buckets that the wider block adds, and that are near enough to matter, are
 // scanned.  The agent's own entry is left out by splitting its bucket row at its slot.  FIRST: give
 // up (return false) when the first ring does not settle the list; the caller queues the agent.
-template <int WIDE, int KT, bool FIRST>
+// ABOVE: the K smallest keys greater than `floor` (the next K neighbours after those up to `floor`).
+template <int WIDE, int KT, bool FIRST, bool ABOVE = false>
 __device__ __forceinline__ bool nearest_keys(typename SortedList<WIDE>::Key (&keys)[KT], int K, int x, int y,
                                              uint32_t self_slot, const Buckets bk, int ib,
                                              const SortedList<WIDE>& sorted, const uint16_t* starts,
-                                             const uint16_t* edges) {
+                                             const uint16_t* edges, typename SortedList<WIDE>::Key floor = 0) {
   using Key = typename SortedList<WIDE>::Key;
   const int bx = bucket_coord(x, bk), by = bucket_coord(y, bk), last = bk.nbx - 1;
 #pragma unroll
@@ -387,17 +394,18 @@ __device__ __forceinline__ bool nearest_keys(typename SortedList<WIDE>::Key (&ke
         // the agent's own row (first ring only) is split at its slot so that it does not meet itself
         const uint32_t qb = rs[x0], qe = rs[x1 + 1];
         const uint32_t split = row == by ? self_slot : qe;
-        scan_range<KT>(keys, qb, split, x, y, ib, sorted);
-        scan_range<KT>(keys, split + 1, qe, x, y, ib, sorted);
+        scan_range<KT, ABOVE>(keys, qb, split, x, y, ib, sorted, floor);
+        scan_range<KT, ABOVE>(keys, split + 1, qe, x, y, ib, sorted, floor);
       } else {
         // only the buckets left and right of the earlier block are new
         if (x0 < px0) {
           const int gap = x - (int(edges[px0]) - 1);
-          if (uint32_t(gap * gap) <= kth_d2) scan_range<KT>(keys, rs[x0], rs[px0], x, y, ib, sorted);
+          if (uint32_t(gap * gap) <= kth_d2) scan_range<KT, ABOVE>(keys, rs[x0], rs[px0], x, y, ib, sorted, floor);
         }
         if (x1 > px1) {
           const int gap = int(edges[px1 + 1]) - x;
-          if (uint32_t(gap * gap) <= kth_d2) scan_range<KT>(keys, rs[px1 + 1], rs[x1 + 1], x, y, ib, sorted);
+          if (uint32_t(gap * gap) <= kth_d2)
+            scan_range<KT, ABOVE>(keys, rs[px1 + 1], rs[x1 + 1], x, y, ib, sorted, floor);
         }
       }
       if (!key_is_none<WIDE>(keys[K - 1])) kth_d2 = uint32_t(keys[K - 1] >> ib);

@@ -56,8 +56,8 @@ __global__ __launch_bounds__(kWorkgroupSize) void init_start_positions_kernel(co
 // The env-per-team kernel: step, reset, or a whole iteration (sample + step + reset).
 // KX > 0: K == KX known at compile time (1..8): the neighbour list and the row live in registers
 // and rows leave through the LDS transpose.  KX == 0: K <= 8 at run time, KX == -2: K <= 16 (the
-// list in registers, rows built in LDS).  KX == -1: any K, by repeated selection, rows written
-// directly (slow path).
+// list in registers, rows built in LDS).  KX == -1: any K, sixteen neighbours at a time, rows
+// written directly (slow path).
 // ----------------------------------------------------------------------------------
 // Where one iteration's outputs go: the in-place buffers, or a slice of a roll-out's arrays.
 struct StepOut {
@@ -844,9 +844,9 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
         }
       }
     } else if (out_act) {
-      // any K: the k-th neighbour is the smallest key above the (k-1)-th; rows written in place
+      // any K: sixteen neighbours at a time by the ring search, each further sixteen as the smallest
+      // keys above the last one found (keys are unique, so no agent comes twice); rows written in place
       const int D = p.D;
-      const int n_sorted = int(L.starts[p.nb_cap]);
       const float tf = static_cast<float>(t_out) * p.inv_T;
       for (int i = lt; i < N; i += ts) {
         float* row = out.obs + (abase + i) * D;
@@ -862,37 +862,42 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
         row[2] = i < N_tag ? 1.0f : 0.0f;
         row[3] = lv ? 1.0f : 0.0f;
         row[4] = tf;
-        bool have_prev = false, exhausted = !lv;
-        Key prev = 0;
-        for (int kk = 0; kk < K; ++kk) {
-          Key bestk = key_none<Key>();
+        bool exhausted = !lv;  // no further neighbour exists
+        Key floor = 0;
+        for (int k0 = 0; k0 < K; k0 += kMaxRegisterK2) {
+          const int kc = min(kMaxRegisterK2, K - k0);
+          Key keys[kMaxRegisterK2];
           if (!exhausted) {
-            for (int q = 0; q < n_sorted; ++q) {
-              const Ent ent = L.sorted.get(q);
-              if (int(ent.id) == i || L.sorted.dead(ent)) continue;
-              const int dx = SL::x(ent) - x, dy = SL::y(ent) - y;
-              const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
-              const Key key = (Key(d2) << p.idx_bits) | Key(ent.id);
-              if ((!have_prev || key > prev) && key < bestk) bestk = key;
+            const uint32_t self_slot = L.slot[i];
+            if (k0 == 0)
+              nearest_keys<WIDE, kMaxRegisterK2, false>(keys, kc, x, y, self_slot, bk, p.idx_bits, L.sorted, L.starts,
+                                                        L.edges);
+            else
+              nearest_keys<WIDE, kMaxRegisterK2, false, true>(keys, kc, x, y, self_slot, bk, p.idx_bits, L.sorted,
+                                                              L.starts, L.edges, floor);
+          }
+#pragma unroll
+          for (int kk = 0; kk < kMaxRegisterK2; ++kk) {
+            if (kk < kc) {
+              float f0 = 0.0f, f1 = 0.0f, f2 = 0.0f, f3 = 0.0f;
+              if (!exhausted && !key_is_none<WIDE>(keys[kk])) {
+                const int j = int(keys[kk] & idx_mask);
+                const uint32_t other = L.pl[j];
+                f0 = static_cast<float>(pos_x_of(other) - x) * p.inv_G;
+                f1 = static_cast<float>(pos_y_of(other) - y) * p.inv_G;
+                f2 = j < N_tag ? 1.0f : 0.0f;
+                f3 = 1.0f;
+                floor = keys[kk];
+              } else {
+                exhausted = true;
+              }
+              float* slot_out = row + 5 + 4 * (k0 + kk);
+              slot_out[0] = f0;
+              slot_out[1] = f1;
+              slot_out[2] = f2;
+              slot_out[3] = f3;
             }
           }
-          float f0 = 0.0f, f1 = 0.0f, f2 = 0.0f, f3 = 0.0f;
-          if (bestk != key_none<Key>()) {
-            const int j = int(bestk & idx_mask);
-            const uint32_t other = L.pl[j];
-            f0 = static_cast<float>(pos_x_of(other) - x) * p.inv_G;
-            f1 = static_cast<float>(pos_y_of(other) - y) * p.inv_G;
-            f2 = j < N_tag ? 1.0f : 0.0f;
-            f3 = 1.0f;
-            prev = bestk;
-            have_prev = true;
-          } else {
-            exhausted = true;
-          }
-          row[5 + 4 * kk + 0] = f0;
-          row[5 + 4 * kk + 1] = f1;
-          row[5 + 4 * kk + 2] = f2;
-          row[5 + 4 * kk + 3] = f3;
         }
       }
     }

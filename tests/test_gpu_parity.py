@@ -813,6 +813,11 @@ EDGE = {
     "k_sixteen_wide_keys": dict(num_envs=3, num_agents=200, num_taggers=15, grid_size=9000, episode_length=8, obs_k=16,
                                 tag_r2=10**7),
     "k_seventeen": dict(num_envs=4, num_agents=30, num_taggers=4, grid_size=10, episode_length=15, obs_k=17),
+    "k_thirty_three": dict(num_envs=3, num_agents=200, num_taggers=20, grid_size=25, episode_length=12, obs_k=33),
+    "k_forty_nine_wide_keys": dict(num_envs=2, num_agents=120, num_taggers=10, grid_size=9000, episode_length=8, obs_k=49,
+                                   tag_r2=10**7),
+    "k_all_others_seventy": dict(num_envs=3, num_agents=70, num_taggers=8, grid_size=12, episode_length=20, obs_k=69),
+    "k_thirty_two_one_cell": dict(num_envs=2, num_agents=50, num_taggers=5, grid_size=1, episode_length=4, obs_k=32),
     "large_env_k_ten": dict(num_envs=2, num_agents=4200, num_taggers=50, grid_size=150, episode_length=3, obs_k=10),
     "k_all_others": dict(num_envs=5, num_agents=14, num_taggers=4, grid_size=9, episode_length=25, obs_k=13),
     "one_cell_grid": dict(num_envs=4, num_agents=6, num_taggers=2, grid_size=1, episode_length=5, obs_k=4),
