@@ -306,12 +306,36 @@ def time_continuous(cfg, ring, steps, warmup):
     return out
 
 
+def time_continuous_rollout(cfg, ring, steps, warmup, k=25):
+    """The same iterations through wdc_rollout, k per launch, outputs in place."""
+    import torch
+    import paper_2108_13976_amd as wd
+
+    env = wd.CTagEnvs(device="cuda:0", **cfg.kwargs())
+    env.reset(wd.WD_RESET_ALL)
+    for _ in range(max(1, warmup // k)):
+        wd.wdc_rollout(env.handle, ring.data_ptr(), RING, k, None)
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    s.record(env.torch_stream)
+    launches = max(1, steps // k)
+    for _ in range(launches):
+        wd.wdc_rollout(env.handle, ring.data_ptr(), RING, k, None)
+    e.record(env.torch_stream)
+    torch.cuda.synchronize()
+    us = s.elapsed_time(e) * 1e3 / (launches * k)
+    env.close()
+    return us
+
+
 def continuous_figures(cfg, steps=None, warmup=50):
     steps = steps or 2 * cfg.episode_length
     ring = continuous_ring(cfg)
     runs = sorted(time_continuous(cfg, ring, steps, warmup) for _ in range(3))
     wall, ev, nbytes = runs[1]
-    return {"us_per_iteration": ev / steps * 1e6, "env_steps_per_s": steps / wall * cfg.num_envs,
+    roll_us = sorted(time_continuous_rollout(cfg, ring, steps, warmup) for _ in range(3))[1]
+    return {"rollout_us_per_iteration": roll_us, "rollout_env_steps_per_s": cfg.num_envs / (roll_us * 1e-6),
+            "rollout_iterations_per_launch": 25,"us_per_iteration": ev / steps * 1e6, "env_steps_per_s": steps / wall * cfg.num_envs,
             "agent_steps_per_s": steps / wall * cfg.num_envs * cfg.num_agents, "iterations": steps, "warmup": warmup,
             "algorithmic_bytes_per_iteration": nbytes, "hbm_frac": nbytes / (ev / steps) / 1e9 / HBM_PEAK_GBS}
 

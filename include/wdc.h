@@ -128,6 +128,25 @@ int wdc_step(wdc_handle* h);
  * fusion of Sec. 4.5 items 3-6). */
 int wdc_iterate(wdc_handle* h, const float* probs);
 
+/* Roll-out arrays of wdc_rollout: DEVICE pointers, 8-byte aligned, each optional (NULL = not
+ * recorded): action [k][E][N][2], reward [k][E][N], done [k][E], obs [k][E][N][D]. */
+typedef struct wdc_rollout_buffers {
+  int32_t* action;
+  float* reward;
+  int32_t* done;
+  float* obs;
+} wdc_rollout_buffers;
+
+/* k iterations (each = wdc_iterate) in ONE launch: the roll-out of Sec. 4.5 whose data a trainer
+ * gathers into a batch (item 7), here without returning to the host between iterations.
+ * probs_ring holds ring_len steps of probabilities [ring_len][E][N][2][5]; iteration s draws with
+ * step g + s from entry (g + s) mod ring_len.  Slice s of each array of `out` that is not NULL
+ * receives that iteration's actions, rewards, done flags (as they were before the reset of done
+ * envs) and rows; `out` may be NULL.  The in-place arrays end as after k calls of wdc_iterate
+ * (action, reward and obs hold the last iteration's values); g <- g + k.  Same results as k calls
+ * of wdc_iterate.  WD_E_CONFIG for ring_len < 1 or k < 1. */
+int wdc_rollout(wdc_handle* h, const float* probs_ring, int ring_len, int k, const wdc_rollout_buffers* out);
+
 /* The global step g that the next draw will use (this build's own; no passage). */
 int wdc_get_step(const wdc_handle* h, uint64_t* g);
 int wdc_set_step(wdc_handle* h, uint64_t g);

@@ -335,8 +335,14 @@ class wdc_layout(ctypes.Structure):
     ]
 
 
+class wdc_rollout_buffers(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("action", "reward", "done", "obs")]
+
+
 def _declare_continuous(lib):
     H = ctypes.c_void_p
+    lib.wdc_rollout.argtypes = [H, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.POINTER(wdc_rollout_buffers)]
+    lib.wdc_rollout.restype = ctypes.c_int
     lib.wdc_query_layout.argtypes = [ctypes.POINTER(wdc_config), ctypes.POINTER(wdc_layout)]
     lib.wdc_create.argtypes = [ctypes.POINTER(wdc_config), ctypes.POINTER(wdc_buffers), ctypes.POINTER(H)]
     lib.wdc_reset.argtypes = [H, ctypes.c_int]
@@ -397,6 +403,11 @@ def wdc_step(handle):
 
 def wdc_iterate(handle, probs_ptr):
     _ccall(handle, "wdc_iterate", ctypes.c_void_p(probs_ptr))
+
+
+def wdc_rollout(handle, probs_ring_ptr, ring_len, k, out=None):
+    _ccall(handle, "wdc_rollout", ctypes.c_void_p(probs_ring_ptr), int(ring_len), int(k),
+           ctypes.byref(out) if out is not None else None)
 
 
 def wdc_get_step(handle):
@@ -472,6 +483,22 @@ class CTagEnvs:
     def iterate(self, probs):
         self._check_probs(probs)
         wdc_iterate(self.handle, probs.data_ptr())
+
+    def rollout(self, probs_ring, k, record=("action", "reward", "done", "obs")):
+        """k iterations in one launch; returns a dict of [k, ...] device tensors for the recorded outputs."""
+        import torch
+
+        ring_len = probs_ring.shape[0]
+        if (probs_ring.dtype != torch.float32 or not probs_ring.is_contiguous() or probs_ring.device != self.device
+                or probs_ring.numel() != ring_len * self.layout.probs_elems):
+            raise ValueError("probs_ring must be a contiguous float32 device tensor of shape [R, E, N, 2, 5]")
+        E, N, D = self.E, self.N, self.D
+        shapes = {"action": ((k, E, N, 2), torch.int32), "reward": ((k, E, N), torch.float32),
+                  "done": ((k, E), torch.int32), "obs": ((k, E, N, D), torch.float32)}
+        out = {n: torch.empty(shapes[n][0], dtype=shapes[n][1], device=self.device) for n in record}
+        bufs = wdc_rollout_buffers(*[out[n].data_ptr() if n in out else None for n in ("action", "reward", "done", "obs")])
+        wdc_rollout(self.handle, probs_ring.data_ptr(), ring_len, k, bufs if out else None)
+        return out
 
     def to_host(self):
         """Synchronise the stream and copy every state array to numpy."""

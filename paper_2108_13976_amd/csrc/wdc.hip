@@ -76,6 +76,114 @@ __device__ __forceinline__ float squared_distance(float xa, float ya, float xb, 
   return dx2 + dy2;
 }
 
+// One live agent turns, changes speed, moves and meets the walls.
+__device__ __forceinline__ void advance_agent(const Params& p, bool tagger, int lvl_acc, int lvl_turn, float& x, float& y,
+                                              float& v, int& h, float2& dir) {
+  h = wrap_heading(h + (lvl_turn - 2), p.H);
+  dir = p.table[h];
+  const float vmax = tagger ? p.vmax_tagger : p.vmax_runner;
+  const float dv = static_cast<float>(lvl_acc - 2) * p.accel;
+  v = v + dv;
+  if (v < 0.0f) v = 0.0f;
+  if (v > vmax) v = vmax;
+  const float step_x = v * dir.x;
+  const float step_y = v * dir.y;
+  x = x + step_x;
+  y = y + step_y;
+  bool clamped = false;
+  if (x < 0.0f) { x = 0.0f; clamped = true; }
+  if (x > p.L) { x = p.L; clamped = true; }
+  if (y < 0.0f) { y = 0.0f; clamped = true; }
+  if (y > p.L) { y = p.L; clamped = true; }
+  if (clamped) v = 0.0f;
+}
+
+// An agent's ten probabilities (five per action category) as five 8-byte pieces.
+struct Probs10 {
+  float2 q[5];
+};
+__device__ __forceinline__ Probs10 load_probs(const float* __restrict__ probs, int64_t a) {
+  const float2* pr = reinterpret_cast<const float2*>(probs + a * 10);
+  Probs10 r;
+#pragma unroll
+  for (int k = 0; k < 5; ++k) r.q[k] = pr[k];
+  return r;
+}
+
+// The two levels of an agent's action from its ten probabilities and one random block.
+__device__ __forceinline__ int2 draw_levels(const Params& p, const Probs10& pr, int e, int i, uint32_t g_lo,
+                                            uint32_t g_hi) {
+  const wd::dev::Block4 r = philox_block(p.env_offset + uint32_t(e), uint32_t(i), g_lo, kStreamActionC | (g_hi << 8),
+                                         p.seed_lo, p.seed_hi);
+  const int lvl_acc = sample_action(pr.q[0].x, pr.q[0].y, pr.q[1].x, pr.q[1].y, r.w[0]);   // probabilities 0..3 of category 0
+  const int lvl_turn = sample_action(pr.q[2].y, pr.q[3].x, pr.q[3].y, pr.q[4].x, r.w[1]);  // 5..8 = 0..3 of category 1
+  return make_int2(lvl_acc, lvl_turn);
+}
+
+// The nearest tagger of a runner at (x, y) by (d2, index): true if it is in range.
+__device__ __forceinline__ bool tagger_in_range(const Params& p, const float* s_x, const float* s_y, int first, float x,
+                                                float y, int* tagger_out) {
+  int best_t = 0;
+  float best_d2 = squared_distance(x, y, s_x[first], s_y[first]);
+  for (int t = 1; t < p.N_tag; ++t) {
+    const float d2 = squared_distance(x, y, s_x[first + t], s_y[first + t]);
+    if (d2 < best_d2) {
+      best_d2 = d2;
+      best_t = t;
+    }
+  }
+  *tagger_out = best_t;
+  return best_d2 <= p.tag_r2;
+}
+
+// The observation row of agent i of the env whose agents sit in LDS slots first .. first + N - 1.
+template <int KT>
+__device__ __forceinline__ void write_row(const Params& p, float* row, const float* s_x, const float* s_y,
+                                          const float* s_vx, const float* s_vy, const int32_t* s_live, int first, int i,
+                                          float x, float y, float v, float2 dir, bool tagger, int live, int t_out) {
+  const int K = p.K;
+  uint64_t keys[KT];
+#pragma unroll
+  for (int k = 0; k < KT; ++k) keys[k] = ~0ull;
+  if (live == 1 && K > 0) {
+    for (int j = 0; j < p.N; ++j) {
+      if (j == i || s_live[first + j] != 1) continue;
+      const float d2 = squared_distance(s_x[first + j], s_y[first + j], x, y);
+      uint64_t key = (uint64_t(__float_as_uint(d2)) << 32) | uint32_t(j);  // d2 >= +0: its bits order like its value
+#pragma unroll
+      for (int k = 0; k < KT; ++k) {
+        if (k < K && key < keys[k]) {
+          const uint64_t tmp = keys[k];
+          keys[k] = key;
+          key = tmp;
+        }
+      }
+    }
+  }
+  float2* row2 = reinterpret_cast<float2*>(row);  // D is even and the buffer 256-byte aligned: 8-byte pieces
+  row2[0] = make_float2(x * p.inv_L, y * p.inv_L);
+  row2[1] = make_float2(v, dir.x);
+  row2[2] = make_float2(dir.y, tagger ? 1.0f : 0.0f);
+  row2[3] = make_float2(live == 1 ? 1.0f : 0.0f, static_cast<float>(t_out) * p.inv_T);
+#pragma unroll
+  for (int k = 0; k < KT; ++k) {
+    if (k < K) {
+      float2 s0 = make_float2(0.0f, 0.0f), s1 = s0, s2 = s0;
+      if (keys[k] != ~0ull) {
+        const int j = int(uint32_t(keys[k]));
+        const float dx = s_x[first + j] - x;
+        const float dy = s_y[first + j] - y;
+        s0 = make_float2(dx * p.inv_L, dy * p.inv_L);
+        s1 = make_float2(s_vx[first + j], s_vy[first + j]);
+        s2 = make_float2(j < p.N_tag ? 1.0f : 0.0f, 1.0f);
+      }
+      row2[4 + 3 * k] = s0;
+      row2[5 + 3 * k] = s1;
+      row2[6 + 3 * k] = s2;
+    }
+  }
+}
+
 // KT: length of the register list of nearest keys (4 or 8, at least K)
 template <int KT>
 __global__ __launch_bounds__(kMaxThreads) void env_kernel(const Params p, const int mode, const float* __restrict__ probs,
@@ -103,13 +211,10 @@ __global__ __launch_bounds__(kMaxThreads) void env_kernel(const Params p, const 
   int lvl_acc = 2, lvl_turn = 2;
   if (mode & kSample) {
     if (valid) {
-      const wd::dev::Block4 r = philox_block(p.env_offset + uint32_t(e), uint32_t(i), g_lo, kStreamActionC | (g_hi << 8),
-                                             p.seed_lo, p.seed_hi);
-      const float2* pr = reinterpret_cast<const float2*>(probs + a * 10);
-      const float2 q0 = pr[0], q1 = pr[1], q2 = pr[2], q3 = pr[3], q4 = pr[4];
-      lvl_acc = sample_action(q0.x, q0.y, q1.x, q1.y, r.w[0]);   // probabilities 0..3 of category 0
-      lvl_turn = sample_action(q2.y, q3.x, q3.y, q4.x, r.w[1]);  // probabilities 5..8 = 0..3 of category 1
-      *reinterpret_cast<int2*>(p.action + 2 * a) = make_int2(lvl_acc, lvl_turn);
+      const int2 lv = draw_levels(p, load_probs(probs, a), e, i, g_lo, g_hi);
+      lvl_acc = lv.x;
+      lvl_turn = lv.y;
+      *reinterpret_cast<int2*>(p.action + 2 * a) = lv;
     }
     if (mode == kSample) return;
   } else if ((mode & kStep) && valid) {
@@ -140,23 +245,7 @@ __global__ __launch_bounds__(kMaxThreads) void env_kernel(const Params p, const 
       h = p.h[a];
       live = p.live[a];
       if (live == 1) {
-        h = wrap_heading(h + (lvl_turn - 2), p.H);
-        dir = p.table[h];
-        const float vmax = tagger ? p.vmax_tagger : p.vmax_runner;
-        const float dv = static_cast<float>(lvl_acc - 2) * p.accel;
-        v = v + dv;
-        if (v < 0.0f) v = 0.0f;
-        if (v > vmax) v = vmax;
-        const float step_x = v * dir.x;
-        const float step_y = v * dir.y;
-        x = x + step_x;
-        y = y + step_y;
-        bool clamped = false;
-        if (x < 0.0f) { x = 0.0f; clamped = true; }
-        if (x > p.L) { x = p.L; clamped = true; }
-        if (y < 0.0f) { y = 0.0f; clamped = true; }
-        if (y > p.L) { y = p.L; clamped = true; }
-        if (clamped) v = 0.0f;
+        advance_agent(p, tagger, lvl_acc, lvl_turn, x, y, v, h, dir);
         p.x[a] = x;
         p.y[a] = y;
         p.v[a] = v;
@@ -176,16 +265,8 @@ __global__ __launch_bounds__(kMaxThreads) void env_kernel(const Params p, const 
     // ---- tag test from the runner's side: nearest tagger by (d2, index) ------------------------
     bool tagged_now = false;
     if (step_act && !tagger && live == 1 && p.tag_r2 >= 0.0f) {
-      int best_t = 0;
-      float best_d2 = squared_distance(x, y, s_x[first], s_y[first]);
-      for (int t = 1; t < p.N_tag; ++t) {
-        const float d2 = squared_distance(x, y, s_x[first + t], s_y[first + t]);
-        if (d2 < best_d2) {
-          best_d2 = d2;
-          best_t = t;
-        }
-      }
-      if (best_d2 <= p.tag_r2) {
+      int best_t;
+      if (tagger_in_range(p, s_x, s_y, first, x, y, &best_t)) {
         tagged_now = true;
         live = 0;
         s_live[tid] = 0;  // (the loops above read taggers only, and taggers stay live)
@@ -250,46 +331,147 @@ __global__ __launch_bounds__(kMaxThreads) void env_kernel(const Params p, const 
 
   // ---- observation rows ---------------------------------------------------------------------------
   if (!new_rows) return;
-  const int K = p.K;
-  uint64_t keys[KT];
-#pragma unroll
-  for (int k = 0; k < KT; ++k) keys[k] = ~0ull;
-  if (live == 1 && K > 0) {
-    for (int j = 0; j < p.N; ++j) {
-      if (j == i || s_live[first + j] != 1) continue;
-      const float d2 = squared_distance(s_x[first + j], s_y[first + j], x, y);
-      uint64_t key = (uint64_t(__float_as_uint(d2)) << 32) | uint32_t(j);  // d2 >= +0: its bits order like its value
-#pragma unroll
-      for (int k = 0; k < KT; ++k) {
-        if (k < K && key < keys[k]) {
-          const uint64_t tmp = keys[k];
-          keys[k] = key;
-          key = tmp;
-        }
+  write_row<KT>(p, p.obs + a * p.D, s_x, s_y, s_vx, s_vy, s_live, first, i, x, y, v, dir, tagger, live, t_out);
+}
+
+// Several roll-out iterations in one launch (envs never interact, and an env's agents share a
+// workgroup, so no synchronisation beyond the workgroup is needed).  Between the iterations an
+// agent's state stays in its thread's registers and the env's clock, live count and done flag in
+// every one of its threads; iteration s draws with step g0 + s from ring entry (ring_pos + s) mod
+// ring_len and writes action, reward and rows to slice s of the roll-out arrays (to the in-place
+// arrays where a roll-out array is not given, and always in the last iteration); the done flags
+// recorded are those before the reset.  The state arrays are written once, at the end.
+struct Roll {
+  int32_t steps, ring_len, ring_pos, pad;
+  int32_t* action;
+  float* reward;
+  int32_t* done;
+  float* obs;
+  const float* ring;
+  uint64_t g0;
+};
+
+template <int KT>
+__global__ __launch_bounds__(kMaxThreads) void rollout_kernel(const Params p, const Roll roll) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  float* const s_x = reinterpret_cast<float*>(smem);
+  float* const s_y = s_x + p.threads;
+  float* const s_vx = s_y + p.threads;
+  float* const s_vy = s_vx + p.threads;
+  int32_t* const s_live = reinterpret_cast<int32_t*>(s_vy + p.threads);
+  int32_t* const s_credits = s_live + p.threads;
+  int32_t* const s_tags = s_credits + p.threads;
+  const int tid = threadIdx.x;
+  const int el = int(wd::dev::fastdiv(uint32_t(tid), p.div_N));
+  const int i = tid - el * p.N;
+  const int e = blockIdx.x * p.envs_per_wg + el;
+  const bool valid = el < p.envs_per_wg && e < p.E;
+  const int first = el * p.N;
+  const int64_t a = int64_t(valid ? e : 0) * p.N + i;
+  const bool tagger = i < p.N_tag;
+  const int64_t EN = int64_t(p.E) * p.N;
+
+  float x = 0.0f, y = 0.0f, v = 0.0f;
+  int h = 0, live = 0, t = 0, nlr = 0, tags_last = 0;
+  bool done = false;
+  if (valid) {
+    x = p.x[a];
+    y = p.y[a];
+    v = p.v[a];
+    h = wrap_heading(p.h[a], p.H);
+    live = p.live[a];
+    t = p.t[e];
+    nlr = p.n_live_runners[e];
+    tags_last = p.tags_step[e];
+    done = p.done[e] != 0;
+  }
+  float2 dir = p.table[h];
+
+  for (int s = 0; s < roll.steps; ++s) {
+    const bool last = s + 1 == roll.steps;
+    const uint64_t g = roll.g0 + uint64_t(s);
+    const float* probs = roll.ring + int64_t((roll.ring_pos + s) % roll.ring_len) * EN * 10;
+    int32_t* const action_out = (roll.action && !last) ? roll.action + int64_t(s) * 2 * EN : p.action;
+    float* const reward_out = (roll.reward && !last) ? roll.reward + int64_t(s) * EN : p.reward;
+    float* const obs_out = (roll.obs && !last) ? roll.obs + int64_t(s) * EN * p.D : p.obs;
+    int2 lv = make_int2(2, 2);
+    if (valid) {
+      lv = draw_levels(p, load_probs(probs, a), e, i, uint32_t(g), uint32_t(g >> 32));
+      *reinterpret_cast<int2*>(action_out + 2 * a) = lv;
+    }
+    const bool step_act = valid && !done;
+    bool new_rows = false;
+    if (step_act) {
+      if (live == 1) advance_agent(p, tagger, lv.x, lv.y, x, y, v, h, dir);
+      s_x[tid] = x;
+      s_y[tid] = y;
+      s_vx[tid] = v * dir.x;
+      s_vy[tid] = v * dir.y;
+      s_live[tid] = live;
+      s_credits[tid] = 0;
+      if (i == 0) s_tags[el] = 0;
+    }
+    __syncthreads();
+    bool tagged_now = false;
+    if (step_act && !tagger && live == 1 && p.tag_r2 >= 0.0f) {
+      int best_t;
+      if (tagger_in_range(p, s_x, s_y, first, x, y, &best_t)) {
+        tagged_now = true;
+        live = 0;
+        s_live[tid] = 0;
+        atomicAdd(&s_credits[first + best_t], 1);
+        atomicAdd(&s_tags[el], 1);
       }
     }
+    __syncthreads();
+    if (step_act) {
+      float rew = 0.0f;
+      if (tagger)
+        rew = static_cast<float>(s_credits[tid]) * p.tag_reward;
+      else if (tagged_now)
+        rew = p.tag_penalty;
+      reward_out[a] = rew;
+      tags_last = s_tags[el];
+      nlr -= tags_last;
+      t += 1;
+      done = nlr == 0 || t >= p.T;
+      new_rows = true;
+    }
+    if (roll.done && valid && i == 0) roll.done[int64_t(s) * p.E + e] = done ? 1 : 0;  // the flag before the reset
+    if (valid && done) {  // back to the start state
+      x = p.x0[a];
+      y = p.y0[a];
+      h = wrap_heading(p.h0[a], p.H);
+      v = 0.0f;
+      live = 1;
+      dir = p.table[h];
+      t = 0;
+      nlr = p.N - p.N_tag;
+      tags_last = 0;
+      done = false;
+      s_x[tid] = x;
+      s_y[tid] = y;
+      s_vx[tid] = v * dir.x;
+      s_vy[tid] = v * dir.y;
+      s_live[tid] = 1;
+      new_rows = true;
+    }
+    __syncthreads();
+    if (new_rows)
+      write_row<KT>(p, obs_out + a * p.D, s_x, s_y, s_vx, s_vy, s_live, first, i, x, y, v, dir, tagger, live, t);
+    __syncthreads();  // the rows are read out of LDS before the next iteration overwrites it
   }
-  float* row = p.obs + a * p.D;
-  float2* row2 = reinterpret_cast<float2*>(row);  // D is even and the buffer 256-byte aligned: 8-byte pieces
-  row2[0] = make_float2(x * p.inv_L, y * p.inv_L);
-  row2[1] = make_float2(v, dir.x);
-  row2[2] = make_float2(dir.y, tagger ? 1.0f : 0.0f);
-  row2[3] = make_float2(live == 1 ? 1.0f : 0.0f, static_cast<float>(t_out) * p.inv_T);
-#pragma unroll
-  for (int k = 0; k < KT; ++k) {
-    if (k < K) {
-      float2 s0 = make_float2(0.0f, 0.0f), s1 = s0, s2 = s0;
-      if (keys[k] != ~0ull) {
-        const int j = int(uint32_t(keys[k]));
-        const float dx = s_x[first + j] - x;
-        const float dy = s_y[first + j] - y;
-        s0 = make_float2(dx * p.inv_L, dy * p.inv_L);
-        s1 = make_float2(s_vx[first + j], s_vy[first + j]);
-        s2 = make_float2(j < p.N_tag ? 1.0f : 0.0f, 1.0f);
-      }
-      row2[4 + 3 * k] = s0;
-      row2[5 + 3 * k] = s1;
-      row2[6 + 3 * k] = s2;
+  if (valid) {
+    p.x[a] = x;
+    p.y[a] = y;
+    p.v[a] = v;
+    p.h[a] = h;
+    p.live[a] = live;
+    if (i == 0) {
+      p.t[e] = t;
+      p.n_live_runners[e] = nlr;
+      p.tags_step[e] = tags_last;
+      p.done[e] = done ? 1 : 0;
     }
   }
 }
@@ -499,6 +681,50 @@ int wdc_iterate(wdc_handle* h, const float* probs) {
   const int rc = launch(h, wdc::kSample | wdc::kStep | wdc::kResetDone, probs);
   if (rc == WD_OK) ++h->g;
   return rc;
+}
+
+int wdc_rollout(wdc_handle* h, const float* probs_ring, int ring_len, int k, const wdc_rollout_buffers* out) {
+  if (!h || !probs_ring) return WD_E_NULL;
+  if (ring_len < 1 || k < 1) return WD_E_CONFIG;
+  if (!aligned(probs_ring, 8)) return WD_E_ALIGN;
+  if (out) {
+    const void* ptrs[] = {out->action, out->reward, out->done, out->obs};
+    for (const void* q : ptrs)
+      if (!aligned(q, 8)) return WD_E_ALIGN;
+  }
+  if (!h->started) return WD_E_STATE;
+  const wdc::Params& p = h->params;
+  wdc::Roll roll = {};
+  roll.steps = k;
+  roll.ring_len = ring_len;
+  roll.ring_pos = int32_t(h->g % uint64_t(ring_len));
+  roll.ring = probs_ring;
+  roll.g0 = h->g;
+  if (out) {
+    roll.action = out->action;
+    roll.reward = out->reward;
+    roll.done = out->done;
+    roll.obs = out->obs;
+  }
+  const int groups = (p.E + p.envs_per_wg - 1) / p.envs_per_wg;
+  if (p.K <= 4)
+    hipLaunchKernelGGL(wdc::rollout_kernel<4>, dim3(groups), dim3(p.threads), lds_bytes(p), h->stream, p, roll);
+  else
+    hipLaunchKernelGGL(wdc::rollout_kernel<wdc::kMaxK>, dim3(groups), dim3(p.threads), lds_bytes(p), h->stream, p, roll);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return fail_hip(h, err, "rollout_kernel launch");
+  if (out) {  // the last iteration wrote the in-place arrays: its slices are copies of them
+    const int64_t EN = int64_t(p.E) * p.N, last = int64_t(k - 1);
+    if (out->action && err == hipSuccess)
+      err = hipMemcpyAsync(out->action + last * 2 * EN, h->bufs.action, size_t(2 * EN) * 4, hipMemcpyDeviceToDevice, h->stream);
+    if (out->reward && err == hipSuccess)
+      err = hipMemcpyAsync(out->reward + last * EN, h->bufs.reward, size_t(EN) * 4, hipMemcpyDeviceToDevice, h->stream);
+    if (out->obs && err == hipSuccess)
+      err = hipMemcpyAsync(out->obs + last * EN * p.D, h->bufs.obs, size_t(EN * p.D) * 4, hipMemcpyDeviceToDevice, h->stream);
+    if (err != hipSuccess) return fail_hip(h, err, "copy of the last roll-out slice");
+  }
+  h->g += uint64_t(k);
+  return WD_OK;
 }
 
 int wdc_get_step(const wdc_handle* h, uint64_t* g) {

@@ -190,3 +190,75 @@ def test_call_order_and_resumption():
         orc.iterate(p, g)
     assert_same(env, orc, "after a jump of the step counter beyond 32 bits")
     env.close()
+
+
+@pytest.mark.parametrize("name,k,launches,envs", [("ctag_10x5", 37, 4, None), ("ctag_2000x5", 25, 3, None),
+                                                   ("ctag_2000x105", 10, 2, (700, 716))])
+def test_multi_step_rollout_against_oracle_and_single_iterations(name, k, launches, envs):
+    """wdc_rollout: every recorded slice and the final state equal the oracle's iteration by iteration,
+    and the in-place arrays equal those of the same number of wdc_iterate calls byte for byte."""
+    cfg = CTAG_CONFIGS[name]
+    kw = cfg.kwargs()
+    E, N, ring_len = cfg.num_envs, cfg.num_agents, 6
+    lo, hi = envs if envs else (0, E)
+    roll = wd.CTagEnvs(device="cuda:0", **kw)
+    single = wd.CTagEnvs(device="cuda:0", **kw)
+    okw = dict(kw, num_envs=hi - lo, env_offset=lo)
+    orc = ctag_oracle.CTagOracle(**okw)
+    ring_host = np.stack([ctag_probs_for_step(cfg.seed, r, E, N) for r in range(ring_len)])
+    ring = torch.from_numpy(ring_host).to(roll.device)
+    roll.reset(wd.WD_RESET_ALL)
+    single.reset(wd.WD_RESET_ALL)
+    orc.reset()
+    g = 0
+    for launch in range(launches):
+        record = ("action", "reward", "done", "obs") if launch % 2 == 0 else ("reward", "done")
+        out = roll.rollout(ring, k, record=record)
+        roll.torch_stream.synchronize()
+        got = {n: t.cpu().numpy() for n, t in out.items()}
+        for s in range(k):
+            probs = ring_host[g % ring_len]
+            single.iterate(ring[g % ring_len])
+            orc.sample(probs[lo:hi], g)
+            orc.step()
+            where = f"launch {launch} iteration {s}"
+            if "action" in got:
+                assert np.array_equal(got["action"][s, lo:hi], orc.action), where
+                assert np.abs(got["obs"][s, lo:hi].astype(np.float64) - 0.0).max() <= 2.0  # (shape sanity)
+            assert np.array_equal(got["reward"][s, lo:hi], orc.reward), where
+            assert np.array_equal(got["done"][s, lo:hi], orc.done), where
+            orc.reset(ctag_oracle.RESET_DONE)
+            if "obs" in got:
+                assert np.abs(got["obs"][s, lo:hi].astype(np.float64) - orc.obs).max() <= TOL, where
+            g += 1
+        a, b = roll.to_host(), single.to_host()
+        for n in a:
+            assert np.array_equal(a[n], b[n]), (launch, n)
+
+        class View:
+            def to_host(self):
+                return {n: arr[lo:hi] for n, arr in a.items()}
+        assert_same(View(), orc, f"after launch {launch}")
+        assert wd.wdc_get_step(roll.handle) == g
+    roll.close()
+    single.close()
+
+
+def test_rollout_argument_checks():
+    cfg = CTAG_CONFIGS["ctag_10x5"]
+    env = wd.CTagEnvs(device="cuda:0", **cfg.kwargs())
+    ring = torch.from_numpy(np.stack([ctag_probs_for_step(cfg.seed, r, 10, 5) for r in range(2)])).to(env.device)
+    with pytest.raises(wd.WdError) as ei:
+        wd.wdc_rollout(env.handle, ring.data_ptr(), 2, 3, None)
+    assert ei.value.status == wd.binding.WD_E_STATE
+    env.reset(wd.WD_RESET_ALL)
+    for bad in ((0, 3), (2, 0)):
+        with pytest.raises(wd.WdError) as ei:
+            wd.wdc_rollout(env.handle, ring.data_ptr(), bad[0], bad[1], None)
+        assert ei.value.status == wd.binding.WD_E_CONFIG
+    with pytest.raises(wd.WdError) as ei:
+        wd.wdc_rollout(env.handle, ring.data_ptr() + 4, 2, 3, None)
+    assert ei.value.status == wd.binding.WD_E_ALIGN
+    wd.wdc_rollout(env.handle, ring.data_ptr(), 2, 1, None)  # a single iteration, nothing recorded
+    assert wd.wdc_get_step(env.handle) == 1
+    env.close()
