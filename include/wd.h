@@ -24,7 +24,9 @@
  *   - All state lives in the caller's buffers.  The library allocates no device
  *     memory, with one exception: for envs too large for a workgroup's LDS
  *     (thousands of agents) wd_create allocates per-env work tables once on the
- *     current device (about 20 bytes per agent) and wd_destroy frees them.
+ *     current device (about 20 bytes per agent) and wd_destroy frees them (and
+ *     wd_rollout, on its first call for such a configuration, a second copy of part
+ *     of them: see there).
  *   - The observations are part of that in-place state (one data store, modified
  *     in place: Sec. 4.2).  The row of an agent that was already out of play
  *     before a step differs from the row the previous call left in `obs` in its
@@ -198,7 +200,13 @@ typedef struct wd_rollout_buffers {
  * receives every iteration's outputs, g advances by k.  Configurations that use the
  * large-env layout, full observations or K > 8 have no multi-step kernel: for them the
  * call enqueues one launch per iteration (and device-to-device copies of the last slice),
- * with the same results.  On WD_E_HIP part of the iterations may have been enqueued. */
+ * with the same results.  In the large-env layout the observation kernel of an iteration
+ * then runs on a second stream that the handle owns (default priority), beside the step
+ * kernel of the next iteration, ordered by events; cfg.stream waits for the last of them
+ * before the call's work on it ends, so the caller sees one stream as before.  The first
+ * such call creates that stream, four events and a second copy of the env tables (device
+ * memory, about 11 bytes per agent); wd_destroy releases them.
+ * On WD_E_HIP part of the iterations may have been enqueued. */
 int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const wd_rollout_buffers* out);
 
 /* The global step counter g used as the RNG step index (checkpoint / resume; no passage

@@ -148,8 +148,10 @@ def test_edge_shapes(n):
 
 
 def test_random_configurations():
+    """24 seeded random configurations (WDC_EXTRA_TRIALS runs more of them)."""
+    import os
     rng = np.random.default_rng(2024)
-    for trial in range(24):
+    for trial in range(int(os.environ.get("WDC_EXTRA_TRIALS", "24"))):
         N = int(rng.choice([2, 3, 5, 8, 17, 45, 64, 100, 255, 300]))
         kw = dict(num_envs=int(rng.integers(1, 40)), num_agents=N, num_taggers=int(rng.integers(1, max(2, N // 3 + 1))),
                   episode_length=int(rng.integers(3, 40)), world_size=float(rng.choice([2.0, 7.5, 20.0, 33.0])),
@@ -159,6 +161,8 @@ def test_random_configurations():
                   seed=int(rng.integers(0, 2**40)), env_offset=int(rng.integers(0, 1000)))
         kw["num_taggers"] = min(kw["num_taggers"], N - 1)
         lockstep(kw, int(2.5 * kw["episode_length"]) + 3, kw["seed"], check_every=3)
+        if trial % 25 == 24:
+            print(f"{trial + 1} configurations", flush=True)
 
 
 def test_call_order_and_resumption():
