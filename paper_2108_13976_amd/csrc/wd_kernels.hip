@@ -481,6 +481,17 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
         }
       }
     };
+    // One team per workgroup whose list is scanned whole (or that gets no new rows): nothing is ever
+    // queued, so the two later tries and their barriers are left out; the whole workgroup agrees on it.
+    bool no_retries = false;
+    if constexpr (STRIP && ONE) {
+      const TeamLds<WIDE, BIG> L0(smem, 0, p, e0);
+      no_retries = __builtin_amdgcn_readfirstlane(L0.misc[2]) == 0;
+      if (!no_retries) {
+        const int rows = __builtin_amdgcn_readfirstlane(L0.misc[kMiscStripRows]);
+        no_retries = __builtin_amdgcn_readfirstlane(int(L0.starts[rows * p.strip_C])) <= kStripScanAll;
+      }
+    }
     if constexpr (STRIP) {
       // the fixed windows of the strip-sorted list; what they do not settle is queued
       for_each_wave_team([&](const TeamLds<WIDE, BIG>& Lt, const Strips st, int n_sorted) {
@@ -506,6 +517,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
       // after that (hardly ever anything) waits in a short queue of its own for the block search
       // (two lanes per agent: an even lane takes what lies below the agent's slot, its odd neighbour
       // what lies above)
+      if (!no_retries) {
       __syncthreads();
       const auto second_try = [&](const TeamLds<WIDE, BIG>& Lt, const Strips st, int n_sorted, int j, int side) {
         const int q = Lt.retry[j];
@@ -556,6 +568,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
           }
         }
       }
+      }  // (!no_retries)
     } else if (search) {
       const int n_sorted = int(L.starts[p.nb_cap]);
       for (int q = lt; q < n_sorted; q += ts) {
@@ -570,8 +583,9 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
         }
       }
     }
-    __syncthreads();
+    if (!no_retries) __syncthreads();
     if constexpr (STRIP) {
+      if (!no_retries)
       for_each_wave_team([&](const TeamLds<WIDE, BIG>& Lt, const Strips st, int) {
         const int n_wait = min(__builtin_amdgcn_readfirstlane(Lt.misc[kMiscQueue2]), kStripQueue2);
         const uint16_t* const queue2 = reinterpret_cast<const uint16_t*>(Lt.misc + 4);
