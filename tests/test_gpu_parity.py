@@ -629,6 +629,10 @@ def random_configuration(seed):
         kw["obs_mode"] = 1
     else:
         kw["obs_k"] = int(min(N - 1, rng.choice([0, 1, 2, 3, 4, 4, 4, 5, 8, 9, 16, 17, 40])))
+    # batches of at most 256 envs run one env per workgroup: every other small-env configuration gets
+    # more envs than that, so that the workgroups that hold several envs are exercised as well
+    if seed % 2 == 1 and N <= 129 and kw.get("obs_mode", 0) == 0:
+        kw["num_envs"] = 257 + int(rng.integers(0, 300))
     return kw
 
 
