@@ -572,7 +572,10 @@ def main():
                 other_ring = ring if name == args.workload else device_probs_ring(other.seed, RING, other.num_envs,
                                                                                    other.num_agents, "cuda:0")
                 w = contract_window(other, other_ring, repetitions=3)
+                # the same window through wd_rollout, 25 iterations per call, outputs in place
+                _, ev_roll, _, _, _ = time_gpu(other, other_ring, w["iterations"], 50, "rollout", 25)
                 per_config[name] = {"us_per_iteration": w["avg_launch_us"], "env_steps_per_s": w["env_steps_per_s"],
+                                    "rollout_us_per_iteration": ev_roll / w["iterations"] * 1e6,
                                     "agent_steps_per_s": w["env_steps_per_s"] * other.num_agents,
                                     "hbm_frac": w["frac"], "iterations": w["iterations"],
                                     "mean_live_fraction": w["mean_live_fraction"],
