@@ -492,6 +492,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
         no_retries = __builtin_amdgcn_readfirstlane(int(L0.starts[rows * p.strip_C])) <= kStripScanAll;
       }
     }
+    bool queued = false;  // this lane has put an agent into a retry queue
     if constexpr (STRIP) {
       // the fixed windows of the strip-sorted list; what they do not settle is queued
       for_each_wave_team([&](const TeamLds<WIDE, BIG>& Lt, const Strips st, int n_sorted) {
@@ -509,6 +510,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
               put_neighbours_of(Lt, Lt.sorted.id[q], keys);
             } else {
               Lt.retry[atomicAdd(&Lt.misc[3], 1)] = uint16_t(q);
+              queued = true;
             }
           }
         }
@@ -517,8 +519,16 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
       // after that (hardly ever anything) waits in a short queue of its own for the block search
       // (two lanes per agent: an even lane takes what lies below the agent's slot, its odd neighbour
       // what lies above)
+      // (no lane of the workgroup has queued anything: as good as no retries at all)
+      // (workgroups of several small envs only: the roll-out loop and the one-env workgroups, which
+      // nearly always have something queued, keep the plain barrier; the vote costs them more than it saves)
       if (!no_retries) {
-      __syncthreads();
+        if constexpr (LOOPED || ONE)
+          __syncthreads();
+        else
+          no_retries = __syncthreads_or(queued ? 1 : 0) == 0;
+      }
+      if (!no_retries) {
       const auto second_try = [&](const TeamLds<WIDE, BIG>& Lt, const Strips st, int n_sorted, int j, int side) {
         const int q = Lt.retry[j];
         const uint32_t me = Lt.sorted.pos[q];
