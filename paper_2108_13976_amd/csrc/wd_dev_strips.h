@@ -337,29 +337,40 @@ __device__ __forceinline__ bool strip_window_search(uint32_t (&keys)[K], uint32_
 }
 
 // A list of a few dozen agents: every entry is a candidate (exact without any bound; every lane
-// reads the same entries, and 9 instructions per entry undercut the fixed windows).  Eight entries
+// reads the same entries, and 8 instructions per entry undercut the fixed windows).  Eight entries
 // per round at constant offsets; the last round may run into the pad behind the list, whose
-// entries are as far away as agents out of play.  `self`: the agent's own slot minus the round's first.
-template <int K, int... J>
-__device__ __forceinline__ void scan_all_chunk(uint32_t (&keys)[K], const uint32_t* __restrict__ wp, const uint16_t* wi,
-                                               short2v mev, int ib, int self, std::integer_sequence<int, J...>) {
+// entries are as far away as agents out of play.  The agent meets itself too: the list holds one
+// key more than wanted, and the agent's own key (distance 0, its index) is taken out at the end,
+// which is cheaper than a test per entry.
+template <int K1, int... J>
+__device__ __forceinline__ void scan_all_chunk(uint32_t (&keys)[K1], const uint32_t* __restrict__ wp,
+                                               const uint16_t* wi, short2v mev, int ib,
+                                               std::integer_sequence<int, J...>) {
   constexpr int kN = sizeof...(J);
   uint32_t pv[kN], iv[kN];
   ((pv[J] = wp[J]), ...);
   ((iv[J] = lds_read_u16<2 * J>(wi)), ...);
   lds_wait();
   (lds_loaded(iv[J]), ...);
-  (insert_key<K>(keys, self == J ? ~0u : ((squared_length(__builtin_bit_cast(short2v, pv[J]) - mev) << ib) | iv[J])), ...);
+  (insert_key<K1>(keys, (squared_length(__builtin_bit_cast(short2v, pv[J]) - mev) << ib) | iv[J]), ...);
 }
 
 template <int K>
 __device__ __forceinline__ void strip_scan_all(uint32_t (&keys)[K], uint32_t me, uint32_t q, uint32_t n_sorted, int ib,
                                                const uint32_t* __restrict__ pos, const uint16_t* __restrict__ id) {
   const short2v mev = __builtin_bit_cast(short2v, me);
+  uint32_t all[K + 1];
 #pragma unroll
-  for (int k = 0; k < K; ++k) keys[k] = ~0u;
+  for (int k = 0; k <= K; ++k) all[k] = ~0u;
   for (uint32_t s0 = 0; s0 < n_sorted; s0 += 8)
-    scan_all_chunk<K>(keys, pos + s0, id + s0, mev, ib, int(q) - int(s0), std::make_integer_sequence<int, 8>{});
+    scan_all_chunk<K + 1>(all, pos + s0, id + s0, mev, ib, std::make_integer_sequence<int, 8>{});
+  const uint32_t own = id[q];  // squared distance 0
+  bool passed = false;
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    passed |= all[k] == own;
+    keys[k] = passed ? all[k + 1] : all[k];
+  }
 }
 
 // Exact search for the agents that the windows did not settle: all bins within m strip heights
