@@ -20,6 +20,7 @@ struct wd_handle {
   bool started;        // wd_reset(WD_RESET_ALL) has run
   bool rows_valid;     // bufs.obs holds the rows this library wrote for the current state
   void* scratch;       // device memory of the large-env tables (NULL for the small layout)
+  int spread_parity;   // spread form of the large-env pair: the set of accumulators the next stepping call uses
   // roll-outs of the large-env layout: a second stream for the observation kernels, a second
   // table image and two events per image (created by the first such roll-out, freed by wd_destroy)
   hipStream_t obs_stream;
@@ -36,6 +37,7 @@ namespace {
 constexpr int64_t kLdsLimitBytes = 160 * 1024 - 256;
 constexpr int kMaxAgents = 32768;
 constexpr int kMaxGrid = 32767;
+constexpr int kSpreadMaxEnvs = 64;  // spread form of the large-env pair: batches up to this many envs
 
 int bits_for(uint32_t v) {  // bits needed to hold values 0..v
   int b = 1;
@@ -362,6 +364,28 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big, bool big_tabl
   return total <= kLdsLimitBytes;
 }
 
+// Spread form of the large-env pair.  The pair's first kernel runs one workgroup per env, so a
+// batch of a few envs leaves most of the chip idle through seven phases of one workgroup's
+// latency; the spread form gives every 512 agents a workgroup for the move and the tag check
+// and lets every slice of the second kernel build the env's tables itself.  It pays while the
+// batch has far fewer envs than the chip has compute units.
+void plan_spread(const wd_config& c, wd::Params* p) {
+  p->big_spread = 0;
+  if (!p->big || c.num_taggers > wd::kSpreadMaxTaggers || c.num_envs > kSpreadMaxEnvs) return;
+  p->big_spread = 1;
+  p->spread_slices = (p->NG + wd::kSpreadMoveThreads - 1) / wd::kSpreadMoveThreads;
+  p->big_slices = std::max(1, std::min(64, (c.num_agents + 511) / 512));
+  // coarse cells of the taggers' table: at least a tag radius wide, so that a runner looks at no
+  // more than three per axis, and at most kSpreadTagSide per grid side
+  const int64_t width = std::max<int64_t>(std::max<int64_t>(p->tag_rad, 1),
+                                          (c.grid_size + wd::kSpreadTagSide - 1) / wd::kSpreadTagSide);
+  p->tag_mul = uint32_t(std::max<int64_t>(1, 65536 / width));
+  p->tag_nbx = int32_t((uint64_t(c.grid_size - 1) * p->tag_mul) >> 16) + 1;
+  p->acc_credits = p->nb_cap;
+  p->acc_tags = p->nb_cap + int32_t(p->g_stride_credits);
+  p->g_stride_acc = (p->acc_tags + 1 + 3) / 4 * 4;
+}
+
 int fill_params(const wd_config& c, const wd_buffers& b, wd::Params* p) {
   std::memset(p, 0, sizeof(*p));
   p->E = c.num_envs;
@@ -424,6 +448,7 @@ int fill_params(const wd_config& c, const wd_buffers& b, wd::Params* p) {
     }
   }
   if (!planned || !wd::env_kernel_available(*p)) return WD_E_UNSUPPORTED;
+  plan_spread(c, p);
   return WD_OK;
 }
 
@@ -437,14 +462,24 @@ int hip_failed(wd_handle* h, hipError_t err, const char* what) {
 int64_t place_big_tables(wd::Params* p, int64_t E, unsigned char* base) {
   const int64_t key_bytes = p->wide == 1 ? 8 : 4;
   const int64_t slot_b = align16(2 * p->g_stride_agents * E), best_b = align16(key_bytes * p->g_stride_agents * E);
-  const int64_t cred_b = align16(4 * p->g_stride_credits * E), image_b = p->g_stride_image * E;
+  const int64_t cred_b = align16(4 * p->g_stride_credits * E), image_b = p->big_spread ? 0 : p->g_stride_image * E;
+  // spread form: packed positions, ranks, the envs' scalars and the two sets of accumulators
+  const int64_t pl_b = p->big_spread ? align16(4 * p->g_stride_agents * E) : 0;
+  const int64_t rank_b = p->big_spread ? align16(2 * p->g_stride_agents * E) : 0;
+  const int64_t env_b = p->big_spread ? 16 * E : 0;
+  const int64_t acc_b = p->big_spread ? 2 * 4 * p->g_stride_acc * E : 0;
   if (base) {
     p->g_best = base;
     p->g_credits = reinterpret_cast<int32_t*>(base + best_b);
     p->g_slot = reinterpret_cast<uint16_t*>(base + best_b + cred_b);
     p->g_image = base + best_b + cred_b + slot_b;
+    unsigned char* at = p->g_image + image_b;
+    p->g_pl = reinterpret_cast<uint32_t*>(at);
+    p->g_rank = reinterpret_cast<uint16_t*>(at + pl_b);
+    p->g_env = reinterpret_cast<int32_t*>(at + pl_b + rank_b);
+    p->g_acc = reinterpret_cast<uint32_t*>(at + pl_b + rank_b + env_b);
   }
-  return slot_b + best_b + cred_b + image_b;
+  return slot_b + best_b + cred_b + image_b + pl_b + rank_b + env_b + acc_b;
 }
 
 // What a roll-out of the large-env layout needs to run the observation kernel of one iteration
@@ -512,7 +547,15 @@ int wd_create(const wd_config* cfg, const wd_buffers* bufs, wd_handle** out) {
       return WD_E_HIP;
     }
     place_big_tables(&params, cfg->num_envs, static_cast<unsigned char*>(h->scratch));
+    if (params.big_spread &&  // both sets of accumulators start clear
+        hipMemset(params.g_acc, 0, size_t(2 * 4 * params.g_stride_acc) * size_t(cfg->num_envs)) != hipSuccess) {
+      (void)hipGetLastError();
+      (void)hipFree(h->scratch);
+      delete h;
+      return WD_E_HIP;
+    }
   }
+  h->spread_parity = 0;
   h->cfg = *cfg;
   h->bufs = *bufs;
   h->params = params;
@@ -561,8 +604,10 @@ int wd_step(wd_handle* h) {
   if (!h->started) return WD_E_STATE;
   wd::Params q = h->params;
   q.rows_kept = h->rows_valid ? 1 : 0;
+  q.spread_parity = h->spread_parity;
   const hipError_t err = wd::launch_env_kernel(q, wd::kModeStep, nullptr, h->g, h->stream);
   if (err != hipSuccess) return hip_failed(h, err, "step kernel");
+  h->spread_parity ^= 1;
   h->rows_valid = true;
   h->g += 1;
   return WD_OK;
@@ -574,8 +619,10 @@ int wd_iterate(wd_handle* h, const float* probs) {
   if (!h->started) return WD_E_STATE;
   wd::Params q = h->params;
   q.rows_kept = h->rows_valid ? 1 : 0;
+  q.spread_parity = h->spread_parity;
   const hipError_t err = wd::launch_env_kernel(q, wd::kModeIterate, probs, h->g, h->stream);
   if (err != hipSuccess) return hip_failed(h, err, "iterate kernel");
+  h->spread_parity ^= 1;
   h->rows_valid = true;
   h->g += 1;
   return WD_OK;
@@ -595,6 +642,7 @@ int wd_iterate_static(const wd_config* cfg, const wd_buffers* bufs, const float*
   rc = fill_params(*cfg, *bufs, &params);
   if (rc != WD_OK) return rc;
   if (!probs_aligned(params, probs)) return WD_E_ALIGN;
+  params.big_spread = 0;  // (its accumulators have to start clear; the pair with one workgroup per env needs nothing of the kind)
   if (params.big) {
     if (size_t(place_big_tables(&params, cfg->num_envs, nullptr)) > kStaticScratchBytes) return WD_E_SCRATCH;
     int dev = -1;
@@ -641,7 +689,7 @@ int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const
     // In the large-env layout the observation kernel of iteration s runs on a second stream beside
     // the step kernel of iteration s + 1 (which needs the state, not the rows): two table images
     // in turn, an image rewritten only once the observation kernel that read it has finished.
-    const bool piped = h->params.big && k > 1;
+    const bool piped = h->params.big && !h->params.big_spread && k > 1;
     if (piped) {
       const int rc = ensure_pipe(h);
       if (rc != WD_OK) return rc;
@@ -650,6 +698,7 @@ int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const
     for (int s = 0; s < k; ++s) {
       wd::Params q = h->params;
       q.rows_kept = rows_kept;
+      q.spread_parity = h->spread_parity;
       wd::ObsPipe pipe = {};
       if (piped) {
         const int b = s & 1;
@@ -672,6 +721,7 @@ int wd_rollout(wd_handle* h, const float* probs_ring, int ring_len, int k, const
       const hipError_t err = wd::launch_env_kernel(q, wd::kModeIterate, probs, h->g + uint64_t(s), h->stream,
                                                    piped ? &pipe : nullptr);
       if (err != hipSuccess) return hip_failed(h, err, "iteration kernel of a roll-out");
+      h->spread_parity ^= 1;
     }
     if (piped) {  // what follows on the caller's stream sees every row
       const hipError_t werr = hipStreamWaitEvent(h->stream, h->rows_done[(k - 1) & 1], 0);

@@ -12,6 +12,13 @@ constexpr int kWorkgroupSize = 256;     // flat per-agent kernels: four wave64s
 constexpr int kMaxEnvWorkgroupSize = 1024; // env-per-team kernels run 256, 512 or 1024 threads (by agent count);
 constexpr int kBigEnvWorkgroupSize = 1024; // 1024 in the step kernel of the large-env layout
 constexpr int kBigObsWorkgroupSize = 512;  // observation kernel of the large-env layout
+// Large envs of a small batch, step spread over many workgroups: the move kernel gives a lane a
+// group of four agents, the table kernel runs 1024 threads per slice of an env
+constexpr int kSpreadMoveThreads = 128;
+constexpr int kSpreadMoveAgents = 4 * kSpreadMoveThreads;
+constexpr int kSpreadObsThreads = 1024;
+constexpr int kSpreadMaxTaggers = 2048;  // every workgroup of the move kernel moves all taggers of its env
+constexpr int kSpreadTagSide = 64;       // its table of taggers: at most this many coarse cells per grid side
 constexpr int kWaveSize = 64;
 constexpr int kNumActions = 5;
 constexpr int kMaxRegisterK = 8;        // K up to this keeps the candidate list in 8 registers,
@@ -107,6 +114,22 @@ struct Params {
   unsigned char* g_image;  // per env: the kept and sorted parts of LDS as the env kernel left them
   int64_t g_stride_agents, g_stride_credits, g_stride_image;
   int32_t big_slices;      // workgroups per env in the observation kernel
+  // Spread form of the large-env pair (big_spread != 0): spread_move_kernel (sample, move, tag check
+  // by slices of 512 agents) leaves packed positions, ranks inside the buckets and, in the
+  // accumulators, bucket counts, credits and the number of tags; spread_obs_kernel finishes the step
+  // and builds the tables per slice.  Two sets of accumulators take turns: the kernels of one call
+  // use set `spread_parity`, and the second kernel clears the other set for the next call.
+  int32_t big_spread;
+  int32_t spread_slices;   // workgroups per env in spread_move_kernel
+  int32_t spread_parity;
+  uint32_t tag_mul;        // coarse cell of a tagger: (x * tag_mul) >> 16 per axis, tag_nbx cells per side
+  int32_t tag_nbx;
+  uint32_t* g_pl;          // [E][NPAD] packed positions after the move and the tag check
+  uint16_t* g_rank;        // [E][NPAD] rank of a live agent among those of its bucket
+  int32_t* g_env;          // [E][4] done, t, n_live_runners as the call found them
+  uint32_t* g_acc;         // [2][E][g_stride_acc]: nb_cap bucket counts, credits, number of tags
+  int64_t g_stride_acc;
+  int32_t acc_credits, acc_tags;  // word offsets inside one env's accumulators
   // device buffers (borrowed from the caller)
   int32_t *pos_x, *pos_y, *pos_x0, *pos_y0, *live, *action;
   float* reward;

@@ -1010,6 +1010,354 @@ __global__ __launch_bounds__(kBigObsWorkgroupSize) void big_obs_kernel(const Par
   }
 }
 
+// ----------------------------------------------------------------------------------
+// Large envs of a small batch: the step spread over many workgroups (Sec. 4.5 item 4 holds the step
+// at constant time only while an env has a thread per agent; this is the layout past that point).
+//
+// spread_move_kernel, workgroup (e, s): lane l owns group 128 s + l of env e: samples (iterate
+// mode), moves, checks its live runners against the taggers and counts its live agents into the
+// env's buckets.  The tag check needs every tagger's position after the move, and a tagger's
+// position is written in place by nobody in this kernel (a workgroup reading it could otherwise meet
+// the new value): every workgroup moves all taggers of its env itself, into a table in LDS (taggers
+// chained by coarse cell), and the second kernel writes their positions.  A runner then takes the
+// smallest (distance, tagger) pair in range, which is what the tagger-side scan with a minimum per
+// runner gives.  Global atomics collect credits, the number of tags and the bucket counts; the
+// value an agent's count returns is its rank inside its bucket.
+// ----------------------------------------------------------------------------------
+struct MovedGroup {
+  int act[4], x[4], y[4], lv[4];
+  int n;
+  bool moved;
+};
+
+__device__ __forceinline__ void move_group(const Params& p, int mode, const float* __restrict__ probs, int e, int grp,
+                                           uint32_t g_lo, uint32_t g_hi, bool step_act, MovedGroup& m) {
+  const int i0 = 4 * grp;
+  const bool vec = p.vec4 != 0;
+  m.n = min(4, p.N - i0);
+  m.moved = false;
+  const int64_t a0 = int64_t(e) * p.N + i0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) m.act[j] = m.x[j] = m.y[j] = m.lv[j] = 0;
+  if (mode == kModeIterate) {
+    const Block4 r = random_block(p, uint32_t(e), uint32_t(grp), g_lo, g_hi, kStreamAction);
+    sample_group(probs, a0, m.n, vec, r, m.act);
+  } else if (step_act) {
+    load4(p.action, a0, m.n, vec, m.act);
+  }
+  if (!step_act) return;
+  load4(p.pos_x, a0, m.n, vec, m.x);
+  load4(p.pos_y, a0, m.n, vec, m.y);
+  load4(p.live, a0, m.n, vec, m.lv);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const bool is_live = j < m.n && m.lv[j] != 0;
+    const int dxm = is_live ? (m.act[j] == 4) - (m.act[j] == 3) : 0;
+    const int dym = is_live ? (m.act[j] == 1) - (m.act[j] == 2) : 0;
+    const int nx = min(max(m.x[j] + dxm, 0), p.G - 1);
+    const int ny = min(max(m.y[j] + dym, 0), p.G - 1);
+    m.moved |= (nx != m.x[j]) | (ny != m.y[j]);
+    m.x[j] = nx;
+    m.y[j] = ny;
+    m.lv[j] = is_live ? 1 : 0;
+  }
+}
+
+__global__ __launch_bounds__(kSpreadMoveThreads) void spread_move_kernel(const Params p, const int mode,
+                                                                         const float* __restrict__ probs, uint32_t g_lo,
+                                                                         uint32_t g_hi) {
+  __shared__ int32_t head[kSpreadTagSide * kSpreadTagSide];  // last tagger put into each coarse cell, -1: none
+  __shared__ uint32_t tagger_pos[kSpreadMaxTaggers];         // x | y << 16 after the move
+  __shared__ int16_t next_in_cell[kSpreadMaxTaggers];
+  const int tid = threadIdx.x;
+  const int e = blockIdx.x / p.spread_slices, s = blockIdx.x - e * p.spread_slices;
+  const int done_in = p.done[e], t_in = p.t[e], nlr_in = p.n_live_runners[e];
+  if (s == 0 && tid == 0) {  // the second kernel overwrites these while its other workgroups still need them
+    p.g_env[4 * e + 0] = done_in;
+    p.g_env[4 * e + 1] = t_in;
+    p.g_env[4 * e + 2] = nlr_in;
+  }
+  if (mode != kModeStep && mode != kModeIterate) return;
+  const bool step_act = !done_in;
+  const bool tagging = step_act && p.tag_r2 >= 0;
+  const int N = p.N, N_tag = p.N_tag;
+  Buckets tb;
+  tb.mul = p.tag_mul;
+  tb.nbx = p.tag_nbx;
+  tb.bmin = 0;
+  if (tagging)
+    for (int j = tid; j < tb.nbx * tb.nbx; j += kSpreadMoveThreads) head[j] = -1;
+  // this lane's group
+  const int grp = s * kSpreadMoveThreads + tid;
+  const bool have = grp < p.NG;
+  MovedGroup mine;
+  mine.n = 0;
+  if (have) move_group(p, mode, probs, e, grp, g_lo, g_hi, step_act, mine);
+  __syncthreads();
+  if (tagging) {
+    for (int tg = tid; 4 * tg < N_tag; tg += kSpreadMoveThreads) {
+      MovedGroup m;
+      move_group(p, mode, probs, e, tg, g_lo, g_hi, true, m);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int i = 4 * tg + j;
+        if (i < N_tag) {
+          tagger_pos[i] = uint32_t(m.x[j]) | (uint32_t(m.y[j]) << 16);
+          next_in_cell[i] = int16_t(atomicExch(&head[bucket_of(m.x[j], m.y[j], tb)], i));
+        }
+      }
+    }
+  }
+  __syncthreads();
+  if (!have) return;
+  const int i0 = 4 * grp;
+  const int64_t a0 = int64_t(e) * N + i0;
+  const bool vec = p.vec4 != 0;
+  if (mode == kModeIterate) store4(p.action, a0, mine.n, vec, mine.act);
+  if (!step_act) return;
+  uint32_t* const acc = p.g_acc + (int64_t(p.spread_parity) * p.E + e) * p.g_stride_acc;
+  const Buckets bk = choose_buckets(p, nlr_in + N_tag);
+  uint32_t packed[4];
+  uint32_t rank[4] = {0, 0, 0, 0};
+  int my_tags = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int i = i0 + j;
+    const int x = mine.x[j], y = mine.y[j];
+    bool live_after = mine.lv[j] != 0;
+    if (tagging && live_after && i >= N_tag) {
+      const int bx0 = bucket_coord(max(x - p.tag_rad, 0), tb), bx1 = bucket_coord(min(x + p.tag_rad, p.G - 1), tb);
+      const int by0 = bucket_coord(max(y - p.tag_rad, 0), tb), by1 = bucket_coord(min(y + p.tag_rad, p.G - 1), tb);
+      uint32_t best_d2 = ~0u;
+      int best_i = -1;
+      for (int row = by0; row <= by1; ++row)
+        for (int col = bx0; col <= bx1; ++col)
+          for (int c = head[row * tb.nbx + col]; c >= 0; c = next_in_cell[c]) {
+            const uint32_t tp = tagger_pos[c];
+            const int dx = int(tp & 0xFFFFu) - x, dy = int(tp >> 16) - y;
+            const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
+            if (d2 <= uint32_t(p.tag_r2) && (d2 < best_d2 || (d2 == best_d2 && c < best_i))) {
+              best_d2 = d2;
+              best_i = c;
+            }
+          }
+      if (best_i >= 0) {
+        live_after = false;
+        atomicAdd(&acc[p.acc_credits + best_i], 1u);
+        ++my_tags;
+      }
+    }
+    // (dead bit alone: tagged in this step; with the stale bit: out of play before it)
+    packed[j] = pack_pos(x, y, live_after) | (mine.lv[j] ? 0u : kStaleBit);
+    if (live_after) rank[j] = atomicAdd(&acc[bucket_of(x, y, bk)], 1u);
+    mine.lv[j] = live_after ? 1 : 0;
+  }
+  if (my_tags) atomicAdd(&acc[p.acc_tags], uint32_t(my_tags));
+  *reinterpret_cast<uint4*>(p.g_pl + int64_t(e) * p.NPAD + i0) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+  *reinterpret_cast<uint2*>(p.g_rank + int64_t(e) * p.NPAD + i0) =
+      make_uint2(rank[0] | (rank[1] << 16), rank[2] | (rank[3] << 16));
+  if (mine.moved && i0 >= N_tag) {
+    store4(p.pos_x, a0, mine.n, vec, mine.x);
+    store4(p.pos_y, a0, mine.n, vec, mine.y);
+  }
+  if (my_tags) store4(p.live, a0, mine.n, vec, mine.lv);
+}
+
+// spread_obs_kernel, workgroup (e, s): finishes the step of env e for index slice s (rewards, the
+// taggers' positions, and in slice 0 the env's clock, counts and done flag, from the complete
+// accumulators), resets the env if it is done (iterate and reset modes), then builds the env's
+// tables in LDS: after a step from the packed positions, the bucket counts and the ranks that
+// spread_move_kernel left (scan of the counts, then every live agent goes to start of its bucket +
+// its rank: no counting pass), after a reset by a counting sort of the start positions.  Every
+// workgroup of an env builds the same tables; then it serves its slice as big_obs_kernel does.
+template <int WIDE, int KX>
+__global__ __launch_bounds__(kSpreadObsThreads) void spread_obs_kernel(const Params p, const int mode) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  using SL = SortedList<WIDE>;
+  using Key = typename SL::Key;
+  constexpr int KT = register_list_size(KX);
+  constexpr int ts = kSpreadObsThreads;
+  const int tid = threadIdx.x;
+  const int e = blockIdx.x / p.big_slices, s = blockIdx.x - e * p.big_slices;
+  const int N = p.N, N_tag = p.N_tag, G = p.G, K = KX > 0 ? KX : p.K;
+  const bool vec = p.vec4 != 0;
+  const int64_t abase = int64_t(e) * N;
+  const TeamLds<WIDE, true> L(smem, 0, p, e);
+  const int done_in = p.g_env[4 * e + 0], t_in = p.g_env[4 * e + 1], nlr_in = p.g_env[4 * e + 2];
+  const bool stepping = mode == kModeStep || mode == kModeIterate;
+  const bool stepped = stepping && !done_in;
+  const uint32_t* const acc = p.g_acc + (int64_t(p.spread_parity) * p.E + e) * p.g_stride_acc;
+  if (stepping) {  // the other set of accumulators is clear when the next call's first kernel starts
+    uint32_t* const other = p.g_acc + (int64_t(p.spread_parity ^ 1) * p.E + e) * p.g_stride_acc;
+    for (int64_t j = int64_t(s) * ts + tid; j < p.g_stride_acc; j += int64_t(p.big_slices) * ts) other[j] = 0u;
+  }
+  int t_out = t_in, tags = 0;
+  bool done_now = done_in != 0;
+  if (stepped) {
+    tags = int(acc[p.acc_tags]);
+    t_out = t_in + 1;
+    done_now = (nlr_in - tags == 0) || (t_out >= p.T);
+  }
+  const bool reset_act = mode != kModeStep && (mode == kModeResetAll || done_now);
+  if (mode != kModeStep && p.done_log && s == 0 && tid == 0) p.done_log[e] = done_now ? 1 : 0;
+  if (!stepped && !reset_act) return;  // this env keeps its state and its rows
+  const int i_chunk = (N + p.big_slices - 1) / p.big_slices;
+  const int i_begin = s * i_chunk, i_end = min(N, i_begin + i_chunk);
+  const uint32_t* const env_pl = p.g_pl + int64_t(e) * p.NPAD;
+  if (stepped) {
+    const int tag_groups_end = 4 * ((N_tag + 3) / 4);  // agents of the groups that hold a tagger
+    for (int i = i_begin + tid; i < i_end; i += ts) {
+      const uint32_t me = env_pl[i];
+      float rew = 0.0f;
+      if (i < N_tag)
+        rew = static_cast<float>(int(acc[p.acc_credits + i])) * p.tag_reward;
+      else if ((me & kDeadBit) && !(me & kStaleBit))
+        rew = p.tag_penalty;
+      p.reward[abase + i] = rew;
+      if (i < tag_groups_end) {
+        p.pos_x[abase + i] = pos_x_of(me);
+        p.pos_y[abase + i] = pos_y_of(me);
+      }
+    }
+    if (s == 0 && tid == 0) {
+      p.t[e] = t_out;
+      p.n_live_runners[e] = nlr_in - tags;
+      p.tags_step[e] = tags;
+      p.done[e] = done_now ? 1 : 0;
+    }
+  }
+  Buckets bk;
+  if (reset_act) {
+    bk = choose_buckets(p, N);
+    for (int j = tid; j < p.nb_cap; j += ts) L.counts[j] = 0u;
+    for (int j = tid; j <= bk.nbx; j += ts) L.edges[j] = uint16_t(min(bucket_first_cell(j, bk), G));
+    __syncthreads();
+    for (int k = 0; k < p.gpt; ++k) {
+      const int grp = tid + k * ts;
+      if (grp < p.NG) {
+        const int i0 = 4 * grp, n = min(4, N - i0);
+        int x[4], y[4];
+        load4(p.pos_x0, abase + i0, n, vec, x);
+        load4(p.pos_y0, abase + i0, n, vec, y);
+        uint32_t packed[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          x[j] = min(max(x[j], 0), G - 1);
+          y[j] = min(max(y[j], 0), G - 1);
+          packed[j] = pack_pos(x[j], y[j], j < n);
+          if (j < n) {
+            atomicAdd(&L.counts[bucket_of(x[j], y[j], bk)], 1u);
+            const int i = i0 + j;
+            if (i >= i_begin && i < i_end) {  // this slice's part of the state
+              p.pos_x[abase + i] = x[j];
+              p.pos_y[abase + i] = y[j];
+              p.live[abase + i] = 1;
+            }
+          }
+        }
+        *reinterpret_cast<uint4*>(L.pl + i0) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+      }
+    }
+    t_out = 0;
+    if (s == 0 && tid == 0) {
+      p.t[e] = 0;
+      p.n_live_runners[e] = N - N_tag;
+      p.tags_step[e] = 0;
+      p.done[e] = 0;
+    }
+    __syncthreads();
+    scan_and_scatter<WIDE>(p, L, true, tid, ts, bk);
+  } else {
+    bk = choose_buckets(p, nlr_in + N_tag);
+    for (int j = tid; j <= bk.nbx; j += ts) L.edges[j] = uint16_t(min(bucket_first_cell(j, bk), G));
+    {
+      const uint4* src = reinterpret_cast<const uint4*>(env_pl);
+      uint4* dst = reinterpret_cast<uint4*>(L.pl);
+      for (int j = tid; j < p.NPAD / 4; j += ts) dst[j] = src[j];
+    }
+    int part = 0;
+    const int j0 = tid * p.scan_chunk;
+    for (int c = 0; c < p.scan_chunk; ++c) part += int(acc[j0 + c]);
+    int total = 0;
+    int run = team_exclusive_scan(part, tid, p.ts_log2, L.misc + 4, &total);
+    for (int c = 0; c < p.scan_chunk; ++c) {
+      L.starts[j0 + c] = uint16_t(run);
+      run += int(acc[j0 + c]);
+    }
+    if (tid == ts - 1) L.starts[p.nb_cap] = uint16_t(total);
+    __syncthreads();
+    const uint16_t* const env_rank = p.g_rank + int64_t(e) * p.NPAD;
+    for (int k = 0; k < p.gpt; ++k) {
+      const int i0 = 4 * (tid + k * ts);
+      if (i0 < N) {
+        const uint4 v4 = *reinterpret_cast<const uint4*>(L.pl + i0);
+        const uint2 r2 = *reinterpret_cast<const uint2*>(env_rank + i0);
+        const uint32_t v[4] = {v4.x, v4.y, v4.z, v4.w};
+        const uint32_t rk[4] = {r2.x & 0xFFFFu, r2.x >> 16, r2.y & 0xFFFFu, r2.y >> 16};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (!(v[j] & kDeadBit)) {
+            const int x = pos_x_of(v[j]), y = pos_y_of(v[j]);
+            L.sorted.put(uint32_t(L.starts[bucket_of(x, y, bk)]) + rk[j], x, y, i0 + j);
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  const int64_t D = KX > 0 ? 5 + 4 * KX : p.D;
+  float* const env_obs = p.obs + abase * D;
+  const float t_frac = static_cast<float>(t_out) * p.inv_T;
+  // live agents, in bucket order
+  const int n_sorted = int(L.starts[p.nb_cap]);
+  const int q_chunk = (n_sorted + p.big_slices - 1) / p.big_slices;
+  int q_begin = min(n_sorted, s * q_chunk), q_end = min(n_sorted, (s + 1) * q_chunk);
+  if (reset_act) {
+    // The counting sort leaves the order inside a bucket to chance, so the lists of an env's workgroups
+    // agree on the buckets only: the slices end on bucket boundaries (after a step the ranks are
+    // shared and the lists are the same everywhere).
+    const auto next_bucket_start = [&](int q) {  // the first bucket start that is >= q
+      int lo = 0, hi = p.nb_cap;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (int(L.starts[mid]) >= q)
+          hi = mid;
+        else
+          lo = mid + 1;
+      }
+      return int(L.starts[lo]);
+    };
+    q_begin = next_bucket_start(q_begin);
+    q_end = next_bucket_start(q_end);
+  }
+  for (int q = q_begin + tid; q < q_end; q += ts) {
+    const Ent ent = L.sorted.get(q);
+    Key keys[KT];
+    if (K > 0) {
+      nearest_keys<WIDE, KT, false>(keys, K, SL::x(ent), SL::y(ent), uint32_t(q), bk, p.idx_bits, L.sorted, L.starts,
+                                    L.edges);
+    } else {
+#pragma unroll
+      for (int kk = 0; kk < KT; ++kk) keys[kk] = key_none<Key>();
+    }
+    store_row<WIDE, KT>(env_obs + int64_t(ent.id) * D, p, L.pl, int(ent.id), K, t_frac, keys, true);
+  }
+  // agents out of the game, in index order
+  for (int i = i_begin + tid; i < i_end; i += ts) {
+    const uint32_t me = L.pl[i];
+    if (!(me & kDeadBit)) continue;
+    if (p.rows_kept && (me & kStaleBit)) {  // out of play before this step: only the time feature changes
+      env_obs[int64_t(i) * D + 4] = t_frac;
+      continue;
+    }
+    Key keys[KT];
+#pragma unroll
+    for (int kk = 0; kk < KT; ++kk) keys[kk] = key_none<Key>();
+    store_row<WIDE, KT>(env_obs + int64_t(i) * D, p, L.pl, i, K, t_frac, keys, false);
+  }
+}
+
 // Workgroup-wide copy of `count` 4-byte words: 16-byte pieces when both ends are aligned.
 template <typename T>
 __device__ __forceinline__ void copy_words(T* __restrict__ dst, const T* __restrict__ src, int64_t count) {
@@ -1106,6 +1454,19 @@ hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uin
                               const ObsPipe* pipe) {
   if constexpr (!ONE && kHasOneTeamVariant<WIDE, KX, BIG>) {
     if (p.teams_per_wg == 1) return launch_env_variant<WIDE, KX, CN, BIG, true>(p, mode, probs, g, stream, pipe);
+  }
+  if constexpr (BIG) {
+    if (p.big_spread) {  // both kernels on the caller's stream: the next call's first kernel needs what the second leaves
+      hipError_t err = ensure_dynamic_lds(&spread_obs_kernel<WIDE, KX>, p.lds_bytes);
+      if (err != hipSuccess) return err;
+      hipLaunchKernelGGL(spread_move_kernel, dim3(p.E * p.spread_slices), dim3(kSpreadMoveThreads), 0, stream, p, mode,
+                         probs, uint32_t(g), uint32_t(g >> 32));
+      err = hipGetLastError();
+      if (err != hipSuccess) return err;
+      hipLaunchKernelGGL((spread_obs_kernel<WIDE, KX>), dim3(p.E * p.big_slices), dim3(kSpreadObsThreads),
+                         size_t(p.lds_bytes), stream, p, mode);
+      return hipGetLastError();
+    }
   }
   const int groups = (p.E + p.teams_per_wg - 1) / p.teams_per_wg;
   hipError_t lds_err = ensure_dynamic_lds(&env_kernel<WIDE, KX, CN, BIG, ONE>, p.lds_bytes);
