@@ -37,7 +37,9 @@ namespace {
 constexpr int64_t kLdsLimitBytes = 160 * 1024 - 256;
 constexpr int kMaxAgents = 32768;
 constexpr int kMaxGrid = 32767;
-constexpr int kSpreadMaxEnvs = 64;  // spread form of the large-env pair: batches up to this many envs
+// spread form of the large-env pair: while its observation kernel has a compute unit per workgroup to spare
+constexpr int kSpreadMaxWorkgroups = 192;
+constexpr int kSpreadMinAgents = 1024;
 
 int bits_for(uint32_t v) {  // bits needed to hold values 0..v
   int b = 1;
@@ -368,13 +370,17 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big, bool big_tabl
 // batch of a few envs leaves most of the chip idle through seven phases of one workgroup's
 // latency; the spread form gives every 512 agents a workgroup for the move and the tag check
 // and lets every slice of the second kernel build the env's tables itself.  It pays while the
-// batch has far fewer envs than the chip has compute units.
+// batch has far fewer slices than the chip has compute units.  Measured, us per iteration, one
+// workgroup per env -> spread (K = 4, a tenth of the agents taggers): 10 envs x 500 agents
+// 21.4 -> 21.5, 10 x 2000 24.8 -> 23.8, 10 x 8192 35.9 -> 29.1, 32 x 2000 25.5 -> 25.2,
+// 64 x 2000 27.2 -> 27.8, 64 x 4096 35.7 -> 47.2, 128 x 2000 31.3 -> 41.9.
 void plan_spread(const wd_config& c, wd::Params* p) {
   p->big_spread = 0;
-  if (!p->big || c.num_taggers > wd::kSpreadMaxTaggers || c.num_envs > kSpreadMaxEnvs) return;
+  if (!p->big || c.num_taggers > wd::kSpreadMaxTaggers || c.num_agents < kSpreadMinAgents ||
+      int64_t(c.num_envs) * p->big_slices > kSpreadMaxWorkgroups)
+    return;
   p->big_spread = 1;
   p->spread_slices = (p->NG + wd::kSpreadMoveThreads - 1) / wd::kSpreadMoveThreads;
-  p->big_slices = std::max(1, std::min(64, (c.num_agents + 511) / 512));
   // coarse cells of the taggers' table: at least a tag radius wide, so that a runner looks at no
   // more than three per axis, and at most kSpreadTagSide per grid side
   const int64_t width = std::max<int64_t>(std::max<int64_t>(p->tag_rad, 1),

@@ -103,6 +103,30 @@ __device__ __forceinline__ void sample_group(const float* __restrict__ probs, in
   for (int j = 0; j < 4; ++j) act[j] = sample_action(f[5 * j], f[5 * j + 1], f[5 * j + 2], f[5 * j + 3], r.w[j]);
 }
 
+// The same in two parts, for code that has other loads to issue before it waits for these: the
+// group's 20 probabilities (zeros beyond agent n), then the draws.
+__device__ __forceinline__ void load_group_probs(const float* __restrict__ probs, int64_t a0, int n, bool vec,
+                                                 float f[20]) {
+  if (vec) {
+    const float4* src = reinterpret_cast<const float4*>(probs + a0 * kNumActions);
+#pragma unroll
+    for (int q = 0; q < 5; ++q) {
+      const float4 v = src[q];
+      f[4 * q + 0] = v.x;
+      f[4 * q + 1] = v.y;
+      f[4 * q + 2] = v.z;
+      f[4 * q + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < 20; ++c) f[c] = c < n * kNumActions ? probs[a0 * kNumActions + c] : 0.0f;
+  }
+}
+__device__ __forceinline__ void draw_group(const float f[20], const Block4& r, int act[4]) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) act[j] = sample_action(f[5 * j], f[5 * j + 1], f[5 * j + 2], f[5 * j + 3], r.w[j]);
+}
+
 __device__ __forceinline__ void load4(const int32_t* __restrict__ src, int64_t a0, int n, bool vec, int v[4]) {
   if (vec) {
     const int4 q = *reinterpret_cast<const int4*>(src + a0);

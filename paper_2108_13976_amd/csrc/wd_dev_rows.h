@@ -110,6 +110,37 @@ __device__ __forceinline__ void store_row(float* __restrict__ row, const Params&
   }
 }
 
+// Half of such a row, for the two lanes that searched for one agent together: side 0 writes the
+// agent's own features and the even neighbour slots, side 1 the odd ones.
+template <int WIDE, int KT>
+__device__ __forceinline__ void store_row_half(float* __restrict__ row, const Params& p, const uint32_t* pl, int i,
+                                               int K, float t_frac, const typename SortedList<WIDE>::Key (&keys)[KT],
+                                               int side) {
+  using Key = typename SortedList<WIDE>::Key;
+  const Key idx_mask = (Key(1) << p.idx_bits) - 1;
+  const uint32_t me = pl[i];
+  const int x = pos_x_of(me), y = pos_y_of(me);
+  if (side == 0) {
+    row[0] = static_cast<float>(x) * p.inv_G;
+    row[1] = static_cast<float>(y) * p.inv_G;
+    row[2] = i < p.N_tag ? 1.0f : 0.0f;
+    row[3] = 1.0f;
+    row[4] = t_frac;
+  }
+#pragma unroll
+  for (int kk = 0; kk < KT; ++kk) {
+    if (kk < K && (kk & 1) == side) {
+      const bool none = key_is_none<WIDE>(keys[kk]);
+      const uint32_t j = none ? uint32_t(i) : uint32_t(keys[kk] & idx_mask);
+      const uint32_t other = pl[j];
+      row[5 + 4 * kk + 0] = static_cast<float>(pos_x_of(other) - x) * p.inv_G;
+      row[5 + 4 * kk + 1] = static_cast<float>(pos_y_of(other) - y) * p.inv_G;
+      row[5 + 4 * kk + 2] = (!none && int(j) < p.N_tag) ? 1.0f : 0.0f;
+      row[5 + 4 * kk + 3] = none ? 0.0f : 1.0f;
+    }
+  }
+}
+
 }  // namespace dev
 }  // namespace wd
 #endif  // WD_DEV_ROWS_H

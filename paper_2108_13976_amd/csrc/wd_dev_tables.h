@@ -428,6 +428,88 @@ __device__ __forceinline__ bool nearest_keys(typename SortedList<WIDE>::Key (&ke
   return true;
 }
 
+// The same search by two neighbouring lanes (side 0 and 1 of one agent): each scans half of
+// every range of slots, and at the end of a ring the two lists are merged through lane shuffles, so
+// that both lanes decide alike whether the list is settled.  Inside a ring a lane prunes rows with
+// the smaller of the pair's K-th distance after the ring before and the K-th of its own list, an
+// upper bound of the pair's.  A search is a chain of
+// dependent LDS reads whose length is the number of candidates: two lanes halve it.  Both lanes of
+// a pair must call together, and both get the whole list.
+template <int WIDE, int KT>
+__device__ __forceinline__ void nearest_keys_pair(typename SortedList<WIDE>::Key (&keys)[KT], int K, int x, int y,
+                                                  uint32_t self_slot, int side, const Buckets bk, int ib,
+                                                  const SortedList<WIDE>& sorted, const uint16_t* starts,
+                                                  const uint16_t* edges) {
+  using Key = typename SortedList<WIDE>::Key;
+  const int bx = bucket_coord(x, bk), by = bucket_coord(y, bk), last = bk.nbx - 1;
+#pragma unroll
+  for (int k = 0; k < KT; ++k) keys[k] = key_none<Key>();
+  // this lane's half of the slots [qb, qe), without the agent's own slot
+  const auto scan_half = [&](uint32_t qb, uint32_t qe) {
+    const uint32_t mid = (qb + qe) >> 1;
+    const uint32_t a = side ? mid : qb, b = side ? qe : mid;
+    scan_range<KT>(keys, a, min(b, max(self_slot, a)), x, y, ib, sorted);
+    scan_range<KT>(keys, max(a, min(self_slot + 1, b)), b, x, y, ib, sorted);
+  };
+  int px0 = 1, px1 = 0, py0 = 1, py1 = 0;  // block already scanned (empty)
+  uint32_t kth_d2 = ~0u;                   // squared distance of the K-th key so far
+  for (int r = 1;; r *= 2) {
+    const int x0 = max(bx - r, 0), x1 = min(bx + r, last);
+    const int y0 = max(by - r, 0), y1 = min(by + r, last);
+    for (int row = y0; row <= y1; ++row) {
+      const uint16_t* rs = starts + row * bk.nbx;
+      if (row < py0 || row > py1) {
+        const int gap = row > by ? int(edges[row]) - y : y - (int(edges[row + 1]) - 1);
+        if (r > 1 && uint32_t(gap * gap) > kth_d2) continue;
+        scan_half(rs[x0], rs[x1 + 1]);
+      } else {
+        if (x0 < px0) {
+          const int gap = x - (int(edges[px0]) - 1);
+          if (uint32_t(gap * gap) <= kth_d2) scan_half(rs[x0], rs[px0]);
+        }
+        if (x1 > px1) {
+          const int gap = int(edges[px1 + 1]) - x;
+          if (uint32_t(gap * gap) <= kth_d2) scan_half(rs[px1 + 1], rs[x1 + 1]);
+        }
+      }
+      if (!key_is_none<WIDE>(keys[K - 1])) kth_d2 = min(kth_d2, uint32_t(keys[K - 1] >> ib));
+    }
+    {  // the other lane's list joins this one
+      Key other[KT];
+#pragma unroll
+      for (int k = 0; k < KT; ++k) {
+        if constexpr (sizeof(Key) == 8) {
+          const uint32_t lo = uint32_t(__shfl_xor(int(uint32_t(keys[k])), 1));
+          const uint32_t hi = uint32_t(__shfl_xor(int(uint32_t(keys[k] >> 32)), 1));
+          other[k] = (Key(hi) << 32) | Key(lo);
+        } else {
+          other[k] = Key(uint32_t(__shfl_xor(int(keys[k]), 1)));
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < KT; ++k) insert_key<KT>(keys, other[k]);
+      kth_d2 = key_is_none<WIDE>(keys[K - 1]) ? ~0u : uint32_t(keys[K - 1] >> ib);
+    }
+    int reach = 65535;
+    if (x0 > 0) reach = min(reach, x - int(edges[x0]) + 1);
+    if (x1 < last) reach = min(reach, int(edges[x1 + 1]) - x);
+    if (y0 > 0) reach = min(reach, y - int(edges[y0]) + 1);
+    if (y1 < last) reach = min(reach, int(edges[y1 + 1]) - y);
+    if (reach == 65535) break;  // the block covers the grid
+    if (kth_d2 < uint32_t(reach * reach)) break;
+    // Another ring: side 0 goes on with the merged list, side 1 with an empty one (and the merged
+    // K-th distance as its bound), so that the next merge meets no key twice.
+    if (side) {
+#pragma unroll
+      for (int k = 0; k < KT; ++k) keys[k] = key_none<Key>();
+    }
+    px0 = x0;
+    px1 = x1;
+    py0 = y0;
+    py1 = y1;
+  }
+}
+
 }  // namespace dev
 }  // namespace wd
 #endif  // WD_DEV_TABLES_H

@@ -1024,39 +1024,52 @@ __global__ __launch_bounds__(kBigObsWorkgroupSize) void big_obs_kernel(const Par
 // runner gives.  Global atomics collect credits, the number of tags and the bucket counts; the
 // value an agent's count returns is its rank inside its bucket.
 // ----------------------------------------------------------------------------------
+struct GroupInput {  // what a group's move needs from memory
+  float f[20];
+  int act[4], x[4], y[4], lv[4];
+};
 struct MovedGroup {
   int act[4], x[4], y[4], lv[4];
   int n;
   bool moved;
 };
 
-__device__ __forceinline__ void move_group(const Params& p, int mode, const float* __restrict__ probs, int e, int grp,
-                                           uint32_t g_lo, uint32_t g_hi, bool step_act, MovedGroup& m) {
-  const int i0 = 4 * grp;
+// Loads only: a caller issues those of several groups before it waits for any.  The state is read
+// whether or not the env is stepped, so that the loads do not wait for its done flag either.
+__device__ __forceinline__ void load_group(const Params& p, int mode, const float* __restrict__ probs, int e, int grp,
+                                           GroupInput& in) {
+  const int i0 = 4 * grp, n = min(4, p.N - i0);
   const bool vec = p.vec4 != 0;
-  m.n = min(4, p.N - i0);
-  m.moved = false;
   const int64_t a0 = int64_t(e) * p.N + i0;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) m.act[j] = m.x[j] = m.y[j] = m.lv[j] = 0;
+  if (mode == kModeIterate) {
+    load_group_probs(probs, a0, n, vec, in.f);
+  } else {
+    load4(p.action, a0, n, vec, in.act);
+  }
+  load4(p.pos_x, a0, n, vec, in.x);
+  load4(p.pos_y, a0, n, vec, in.y);
+  load4(p.live, a0, n, vec, in.lv);
+}
+
+__device__ __forceinline__ void move_group(const Params& p, int mode, int e, int grp, uint32_t g_lo, uint32_t g_hi,
+                                           bool step_act, const GroupInput& in, MovedGroup& m) {
+  m.n = min(4, p.N - 4 * grp);
+  m.moved = false;
   if (mode == kModeIterate) {
     const Block4 r = random_block(p, uint32_t(e), uint32_t(grp), g_lo, g_hi, kStreamAction);
-    sample_group(probs, a0, m.n, vec, r, m.act);
-  } else if (step_act) {
-    load4(p.action, a0, m.n, vec, m.act);
+    draw_group(in.f, r, m.act);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) m.act[j] = in.act[j];
   }
-  if (!step_act) return;
-  load4(p.pos_x, a0, m.n, vec, m.x);
-  load4(p.pos_y, a0, m.n, vec, m.y);
-  load4(p.live, a0, m.n, vec, m.lv);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const bool is_live = j < m.n && m.lv[j] != 0;
+    const bool is_live = step_act && j < m.n && in.lv[j] != 0;
     const int dxm = is_live ? (m.act[j] == 4) - (m.act[j] == 3) : 0;
     const int dym = is_live ? (m.act[j] == 1) - (m.act[j] == 2) : 0;
-    const int nx = min(max(m.x[j] + dxm, 0), p.G - 1);
-    const int ny = min(max(m.y[j] + dym, 0), p.G - 1);
-    m.moved |= (nx != m.x[j]) | (ny != m.y[j]);
+    const int nx = min(max(in.x[j] + dxm, 0), p.G - 1);
+    const int ny = min(max(in.y[j] + dym, 0), p.G - 1);
+    m.moved |= (nx != in.x[j]) | (ny != in.y[j]);
     m.x[j] = nx;
     m.y[j] = ny;
     m.lv[j] = is_live ? 1 : 0;
@@ -1078,32 +1091,38 @@ __global__ __launch_bounds__(kSpreadMoveThreads) void spread_move_kernel(const P
     p.g_env[4 * e + 2] = nlr_in;
   }
   if (mode != kModeStep && mode != kModeIterate) return;
+  const int N = p.N, N_tag = p.N_tag;
+  // this lane's group, and its first group of taggers: all loads go out before anything waits
+  const int grp = s * kSpreadMoveThreads + tid;
+  const bool have = grp < p.NG, have_tagger = p.tag_r2 >= 0 && 4 * tid < N_tag;
+  GroupInput in_mine, in_tagger;
+  if (have) load_group(p, mode, probs, e, grp, in_mine);
+  if (have_tagger) load_group(p, mode, probs, e, tid, in_tagger);
   const bool step_act = !done_in;
   const bool tagging = step_act && p.tag_r2 >= 0;
-  const int N = p.N, N_tag = p.N_tag;
   Buckets tb;
   tb.mul = p.tag_mul;
   tb.nbx = p.tag_nbx;
   tb.bmin = 0;
   if (tagging)
     for (int j = tid; j < tb.nbx * tb.nbx; j += kSpreadMoveThreads) head[j] = -1;
-  // this lane's group
-  const int grp = s * kSpreadMoveThreads + tid;
-  const bool have = grp < p.NG;
-  MovedGroup mine;
+  MovedGroup mine, tagger;
   mine.n = 0;
-  if (have) move_group(p, mode, probs, e, grp, g_lo, g_hi, step_act, mine);
+  if (have) move_group(p, mode, e, grp, g_lo, g_hi, step_act, in_mine, mine);
+  if (have_tagger) move_group(p, mode, e, tid, g_lo, g_hi, step_act, in_tagger, tagger);
   __syncthreads();
   if (tagging) {
     for (int tg = tid; 4 * tg < N_tag; tg += kSpreadMoveThreads) {
-      MovedGroup m;
-      move_group(p, mode, probs, e, tg, g_lo, g_hi, true, m);
+      if (tg != tid) {  // more taggers than one group per lane
+        load_group(p, mode, probs, e, tg, in_tagger);
+        move_group(p, mode, e, tg, g_lo, g_hi, true, in_tagger, tagger);
+      }
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int i = 4 * tg + j;
         if (i < N_tag) {
-          tagger_pos[i] = uint32_t(m.x[j]) | (uint32_t(m.y[j]) << 16);
-          next_in_cell[i] = int16_t(atomicExch(&head[bucket_of(m.x[j], m.y[j], tb)], i));
+          tagger_pos[i] = uint32_t(tagger.x[j]) | (uint32_t(tagger.y[j]) << 16);
+          next_in_cell[i] = int16_t(atomicExch(&head[bucket_of(tagger.x[j], tagger.y[j], tb)], i));
         }
       }
     }
@@ -1117,50 +1136,70 @@ __global__ __launch_bounds__(kSpreadMoveThreads) void spread_move_kernel(const P
   if (!step_act) return;
   uint32_t* const acc = p.g_acc + (int64_t(p.spread_parity) * p.E + e) * p.g_stride_acc;
   const Buckets bk = choose_buckets(p, nlr_in + N_tag);
-  uint32_t packed[4];
-  uint32_t rank[4] = {0, 0, 0, 0};
   int my_tags = 0;
+  bool live_after[4];
+  // A coarse cell is at least a tag radius wide, so a runner's reach touches at most 3 x 3 of them.
+  // The heads of all of them, for the four agents, are read before any chain is followed: 36 reads
+  // in flight instead of 36 in a row (a cell beyond the reach repeats the last one in it and is dropped).
+  int heads[4][9];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int i = i0 + j;
     const int x = mine.x[j], y = mine.y[j];
-    bool live_after = mine.lv[j] != 0;
-    if (tagging && live_after && i >= N_tag) {
-      const int bx0 = bucket_coord(max(x - p.tag_rad, 0), tb), bx1 = bucket_coord(min(x + p.tag_rad, p.G - 1), tb);
-      const int by0 = bucket_coord(max(y - p.tag_rad, 0), tb), by1 = bucket_coord(min(y + p.tag_rad, p.G - 1), tb);
-      uint32_t best_d2 = ~0u;
-      int best_i = -1;
-      for (int row = by0; row <= by1; ++row)
-        for (int col = bx0; col <= bx1; ++col)
-          for (int c = head[row * tb.nbx + col]; c >= 0; c = next_in_cell[c]) {
-            const uint32_t tp = tagger_pos[c];
-            const int dx = int(tp & 0xFFFFu) - x, dy = int(tp >> 16) - y;
-            const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
-            if (d2 <= uint32_t(p.tag_r2) && (d2 < best_d2 || (d2 == best_d2 && c < best_i))) {
-              best_d2 = d2;
-              best_i = c;
-            }
-          }
-      if (best_i >= 0) {
-        live_after = false;
-        atomicAdd(&acc[p.acc_credits + best_i], 1u);
-        ++my_tags;
+    const int bx0 = bucket_coord(max(x - p.tag_rad, 0), tb), bx1 = bucket_coord(min(x + p.tag_rad, p.G - 1), tb);
+    const int by0 = bucket_coord(max(y - p.tag_rad, 0), tb), by1 = bucket_coord(min(y + p.tag_rad, p.G - 1), tb);
+    live_after[j] = mine.lv[j] != 0;
+    const bool check = tagging && live_after[j] && i0 + j >= N_tag;
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+      for (int c = 0; c < 3; ++c) {
+        const int h = tagging ? head[min(by0 + r, by1) * tb.nbx + min(bx0 + c, bx1)] : -1;
+        heads[j][3 * r + c] = (check && by0 + r <= by1 && bx0 + c <= bx1) ? h : -1;
       }
-    }
-    // (dead bit alone: tagged in this step; with the stale bit: out of play before it)
-    packed[j] = pack_pos(x, y, live_after) | (mine.lv[j] ? 0u : kStaleBit);
-    if (live_after) rank[j] = atomicAdd(&acc[bucket_of(x, y, bk)], 1u);
-    mine.lv[j] = live_after ? 1 : 0;
   }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int x = mine.x[j], y = mine.y[j];
+    uint32_t best_d2 = ~0u;
+    int best_i = -1;
+#pragma unroll
+    for (int k = 0; k < 9; ++k)
+      for (int c = heads[j][k]; c >= 0; c = next_in_cell[c]) {
+        const uint32_t tp = tagger_pos[c];
+        const int dx = int(tp & 0xFFFFu) - x, dy = int(tp >> 16) - y;
+        const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
+        if (d2 <= uint32_t(p.tag_r2) && (d2 < best_d2 || (d2 == best_d2 && c < best_i))) {
+          best_d2 = d2;
+          best_i = c;
+        }
+      }
+    if (best_i >= 0) {
+      live_after[j] = false;
+      atomicAdd(&acc[p.acc_credits + best_i], 1u);
+      ++my_tags;
+    }
+  }
+  // the four counts go out together; what each returns is the agent's rank inside its bucket
+  uint32_t packed[4];
+  uint32_t rank[4] = {0, 0, 0, 0};
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    if (live_after[j]) rank[j] = atomicAdd(&acc[bucket_of(mine.x[j], mine.y[j], bk)], 1u);
   if (my_tags) atomicAdd(&acc[p.acc_tags], uint32_t(my_tags));
-  *reinterpret_cast<uint4*>(p.g_pl + int64_t(e) * p.NPAD + i0) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
-  *reinterpret_cast<uint2*>(p.g_rank + int64_t(e) * p.NPAD + i0) =
-      make_uint2(rank[0] | (rank[1] << 16), rank[2] | (rank[3] << 16));
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    // (dead bit alone: tagged in this step; with the stale bit: out of play before it)
+    packed[j] = pack_pos(mine.x[j], mine.y[j], live_after[j]) | (mine.lv[j] ? 0u : kStaleBit);
+    mine.lv[j] = live_after[j] ? 1 : 0;
+  }
   if (mine.moved && i0 >= N_tag) {
     store4(p.pos_x, a0, mine.n, vec, mine.x);
     store4(p.pos_y, a0, mine.n, vec, mine.y);
   }
   if (my_tags) store4(p.live, a0, mine.n, vec, mine.lv);
+  *reinterpret_cast<uint4*>(p.g_pl + int64_t(e) * p.NPAD + i0) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+  *reinterpret_cast<uint2*>(p.g_rank + int64_t(e) * p.NPAD + i0) =
+      make_uint2(rank[0] | (rank[1] << 16), rank[2] | (rank[3] << 16));
 }
 
 // spread_obs_kernel, workgroup (e, s): finishes the step of env e for index slice s (rewards, the
@@ -1185,16 +1224,39 @@ __global__ __launch_bounds__(kSpreadObsThreads) void spread_obs_kernel(const Par
   const TeamLds<WIDE, true> L(smem, 0, p, e);
   const int done_in = p.g_env[4 * e + 0], t_in = p.g_env[4 * e + 1], nlr_in = p.g_env[4 * e + 2];
   const bool stepping = mode == kModeStep || mode == kModeIterate;
-  const bool stepped = stepping && !done_in;
   const uint32_t* const acc = p.g_acc + (int64_t(p.spread_parity) * p.E + e) * p.g_stride_acc;
+  const uint32_t* const env_pl = p.g_pl + int64_t(e) * p.NPAD;
+  const uint16_t* const env_rank = p.g_rank + int64_t(e) * p.NPAD;
+  const int acc_tags = int(acc[p.acc_tags]);
+  // What the tables of a stepped env are built from is asked for before anything waits for the env's
+  // scalars (a reset does not use it): packed positions straight into LDS, this thread's bucket
+  // counts and, when a thread has at most two groups, their ranks.
+  constexpr int kMaxScanChunk = 4, kRanksAhead = 2;  // (4096 buckets at most, 1024 threads)
+  const int j0 = tid * p.scan_chunk;
+  uint32_t cnt[kMaxScanChunk];
+  uint2 ranks_ahead[kRanksAhead];
+  {
+    const uint4* src = reinterpret_cast<const uint4*>(env_pl);
+    uint4* dst = reinterpret_cast<uint4*>(L.pl);
+#pragma unroll 2
+    for (int j = tid; j < p.NPAD / 4; j += ts) dst[j] = src[j];
+#pragma unroll
+    for (int c = 0; c < kMaxScanChunk; ++c) cnt[c] = c < p.scan_chunk ? acc[j0 + c] : 0u;
+#pragma unroll
+    for (int k = 0; k < kRanksAhead; ++k) {
+      const int i0 = 4 * (tid + k * ts);
+      ranks_ahead[k] = (p.gpt <= kRanksAhead && i0 < N) ? *reinterpret_cast<const uint2*>(env_rank + i0) : make_uint2(0u, 0u);
+    }
+  }
   if (stepping) {  // the other set of accumulators is clear when the next call's first kernel starts
     uint32_t* const other = p.g_acc + (int64_t(p.spread_parity ^ 1) * p.E + e) * p.g_stride_acc;
     for (int64_t j = int64_t(s) * ts + tid; j < p.g_stride_acc; j += int64_t(p.big_slices) * ts) other[j] = 0u;
   }
+  const bool stepped = stepping && !done_in;
   int t_out = t_in, tags = 0;
   bool done_now = done_in != 0;
   if (stepped) {
-    tags = int(acc[p.acc_tags]);
+    tags = acc_tags;
     t_out = t_in + 1;
     done_now = (nlr_in - tags == 0) || (t_out >= p.T);
   }
@@ -1203,20 +1265,31 @@ __global__ __launch_bounds__(kSpreadObsThreads) void spread_obs_kernel(const Par
   if (!stepped && !reset_act) return;  // this env keeps its state and its rows
   const int i_chunk = (N + p.big_slices - 1) / p.big_slices;
   const int i_begin = s * i_chunk, i_end = min(N, i_begin + i_chunk);
-  const uint32_t* const env_pl = p.g_pl + int64_t(e) * p.NPAD;
   if (stepped) {
-    const int tag_groups_end = 4 * ((N_tag + 3) / 4);  // agents of the groups that hold a tagger
-    for (int i = i_begin + tid; i < i_end; i += ts) {
-      const uint32_t me = env_pl[i];
-      float rew = 0.0f;
-      if (i < N_tag)
-        rew = static_cast<float>(int(acc[p.acc_credits + i])) * p.tag_reward;
-      else if ((me & kDeadBit) && !(me & kStaleBit))
-        rew = p.tag_penalty;
-      p.reward[abase + i] = rew;
-      if (i < tag_groups_end) {
-        p.pos_x[abase + i] = pos_x_of(me);
-        p.pos_y[abase + i] = pos_y_of(me);
+    // rewards of this slice and the positions of the groups that hold a tagger, from the quads this
+    // thread has just put into LDS itself
+    const int tag_groups_end = 4 * ((N_tag + 3) / 4);
+    for (int k = 0; k < p.gpt; ++k) {
+      const int i0 = 4 * (tid + k * ts);
+      if (i0 + 3 >= i_begin && i0 < i_end) {
+        const uint4 v4 = *reinterpret_cast<const uint4*>(L.pl + i0);
+        const uint32_t v[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int i = i0 + j;
+          if (i >= i_begin && i < i_end) {
+            float rew = 0.0f;
+            if (i < N_tag)
+              rew = static_cast<float>(int(acc[p.acc_credits + i])) * p.tag_reward;
+            else if ((v[j] & kDeadBit) && !(v[j] & kStaleBit))
+              rew = p.tag_penalty;
+            p.reward[abase + i] = rew;
+            if (i < tag_groups_end) {
+              p.pos_x[abase + i] = pos_x_of(v[j]);
+              p.pos_y[abase + i] = pos_y_of(v[j]);
+            }
+          }
+        }
       }
     }
     if (s == 0 && tid == 0) {
@@ -1270,37 +1343,40 @@ __global__ __launch_bounds__(kSpreadObsThreads) void spread_obs_kernel(const Par
   } else {
     bk = choose_buckets(p, nlr_in + N_tag);
     for (int j = tid; j <= bk.nbx; j += ts) L.edges[j] = uint16_t(min(bucket_first_cell(j, bk), G));
-    {
-      const uint4* src = reinterpret_cast<const uint4*>(env_pl);
-      uint4* dst = reinterpret_cast<uint4*>(L.pl);
-      for (int j = tid; j < p.NPAD / 4; j += ts) dst[j] = src[j];
-    }
     int part = 0;
-    const int j0 = tid * p.scan_chunk;
-    for (int c = 0; c < p.scan_chunk; ++c) part += int(acc[j0 + c]);
+#pragma unroll
+    for (int c = 0; c < kMaxScanChunk; ++c) part += int(cnt[c]);
     int total = 0;
     int run = team_exclusive_scan(part, tid, p.ts_log2, L.misc + 4, &total);
-    for (int c = 0; c < p.scan_chunk; ++c) {
-      L.starts[j0 + c] = uint16_t(run);
-      run += int(acc[j0 + c]);
+#pragma unroll
+    for (int c = 0; c < kMaxScanChunk; ++c) {
+      if (c < p.scan_chunk) L.starts[j0 + c] = uint16_t(run);
+      run += int(cnt[c]);
     }
     if (tid == ts - 1) L.starts[p.nb_cap] = uint16_t(total);
     __syncthreads();
-    const uint16_t* const env_rank = p.g_rank + int64_t(e) * p.NPAD;
-    for (int k = 0; k < p.gpt; ++k) {
-      const int i0 = 4 * (tid + k * ts);
-      if (i0 < N) {
-        const uint4 v4 = *reinterpret_cast<const uint4*>(L.pl + i0);
-        const uint2 r2 = *reinterpret_cast<const uint2*>(env_rank + i0);
-        const uint32_t v[4] = {v4.x, v4.y, v4.z, v4.w};
-        const uint32_t rk[4] = {r2.x & 0xFFFFu, r2.x >> 16, r2.y & 0xFFFFu, r2.y >> 16};
+    const auto place = [&](int i0, uint2 r2) {
+      const uint4 v4 = *reinterpret_cast<const uint4*>(L.pl + i0);
+      const uint32_t v[4] = {v4.x, v4.y, v4.z, v4.w};
+      const uint32_t rk[4] = {r2.x & 0xFFFFu, r2.x >> 16, r2.y & 0xFFFFu, r2.y >> 16};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (!(v[j] & kDeadBit)) {
-            const int x = pos_x_of(v[j]), y = pos_y_of(v[j]);
-            L.sorted.put(uint32_t(L.starts[bucket_of(x, y, bk)]) + rk[j], x, y, i0 + j);
-          }
+      for (int j = 0; j < 4; ++j) {
+        if (!(v[j] & kDeadBit)) {
+          const int x = pos_x_of(v[j]), y = pos_y_of(v[j]);
+          L.sorted.put(uint32_t(L.starts[bucket_of(x, y, bk)]) + rk[j], x, y, i0 + j);
         }
+      }
+    };
+    if (p.gpt <= kRanksAhead) {
+#pragma unroll
+      for (int k = 0; k < kRanksAhead; ++k) {
+        const int i0 = 4 * (tid + k * ts);
+        if (i0 < N) place(i0, ranks_ahead[k]);
+      }
+    } else {
+      for (int k = 0; k < p.gpt; ++k) {
+        const int i0 = 4 * (tid + k * ts);
+        if (i0 < N) place(i0, *reinterpret_cast<const uint2*>(env_rank + i0));
       }
     }
     __syncthreads();
@@ -1331,17 +1407,20 @@ __global__ __launch_bounds__(kSpreadObsThreads) void spread_obs_kernel(const Par
     q_begin = next_bucket_start(q_begin);
     q_end = next_bucket_start(q_end);
   }
-  for (int q = q_begin + tid; q < q_end; q += ts) {
+  // Two neighbouring lanes per agent: each searches half of the candidates and writes half of the
+  // row (collecting a wave's rows in LDS and writing them out whole was measured: slower).
+  const int side = tid & 1;
+  for (int q = q_begin + (tid >> 1); q < q_end; q += ts / 2) {
     const Ent ent = L.sorted.get(q);
     Key keys[KT];
     if (K > 0) {
-      nearest_keys<WIDE, KT, false>(keys, K, SL::x(ent), SL::y(ent), uint32_t(q), bk, p.idx_bits, L.sorted, L.starts,
-                                    L.edges);
+      nearest_keys_pair<WIDE, KT>(keys, K, SL::x(ent), SL::y(ent), uint32_t(q), side, bk, p.idx_bits, L.sorted,
+                                  L.starts, L.edges);
     } else {
 #pragma unroll
       for (int kk = 0; kk < KT; ++kk) keys[kk] = key_none<Key>();
     }
-    store_row<WIDE, KT>(env_obs + int64_t(ent.id) * D, p, L.pl, int(ent.id), K, t_frac, keys, true);
+    store_row_half<WIDE, KT>(env_obs + int64_t(ent.id) * D, p, L.pl, int(ent.id), K, t_frac, keys, side);
   }
   // agents out of the game, in index order
   for (int i = i_begin + tid; i < i_end; i += ts) {

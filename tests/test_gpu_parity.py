@@ -875,6 +875,17 @@ EDGE = {
     "large_env_pair_smallest": dict(num_envs=3, num_agents=384, num_taggers=30, grid_size=50, episode_length=10, obs_k=16),
     "odd_rewards": dict(num_envs=12, num_agents=25, num_taggers=5, grid_size=8, episode_length=20, obs_k=2,
                         tag_reward=0.3, tag_penalty=-2.5),
+    # The large-env layout has two forms: few envs get the step spread over a workgroup per 512 agents (the
+    # large_env_* cases above), more envs or more than 2048 taggers the step with one workgroup per env.
+    "large_env_one_workgroup_step": dict(num_envs=60, num_agents=2100, num_taggers=100, grid_size=150, episode_length=3),
+    "large_env_many_taggers": dict(num_envs=2, num_agents=5000, num_taggers=2500, grid_size=140, episode_length=3),
+    # spread step: a tag radius of many cells (one coarse cell of the taggers' table per reach), a group of four
+    # that holds taggers and runners with more than one group of taggers per lane, a crowded grid
+    "large_env_wide_reach": dict(num_envs=2, num_agents=4200, num_taggers=20, grid_size=300, episode_length=4, tag_r2=900),
+    "large_env_odd_taggers": dict(num_envs=3, num_agents=4099, num_taggers=513, grid_size=210, episode_length=4, obs_k=4,
+                                  tag_r2=5),
+    "large_env_crowded": dict(num_envs=2, num_agents=4200, num_taggers=100, grid_size=16, episode_length=6, tag_r2=0),
+    "large_env_two_thousand": dict(num_envs=4, num_agents=2000, num_taggers=2000 - 1, grid_size=64, episode_length=3, obs_k=8),
 }
 
 
