@@ -387,8 +387,8 @@ void plan_spread(const wd_config& c, wd::Params* p) {
                                           (c.grid_size + wd::kSpreadTagSide - 1) / wd::kSpreadTagSide);
   p->tag_mul = uint32_t(std::max<int64_t>(1, 65536 / width));
   p->tag_nbx = int32_t((uint64_t(c.grid_size - 1) * p->tag_mul) >> 16) + 1;
-  p->acc_credits = p->nb_cap;
-  p->acc_tags = p->nb_cap + int32_t(p->g_stride_credits);
+  p->acc_credits = 0;
+  p->acc_tags = int32_t(p->g_stride_credits);
   p->g_stride_acc = (p->acc_tags + 1 + 3) / 4 * 4;
 }
 
@@ -469,9 +469,8 @@ int64_t place_big_tables(wd::Params* p, int64_t E, unsigned char* base) {
   const int64_t key_bytes = p->wide == 1 ? 8 : 4;
   const int64_t slot_b = align16(2 * p->g_stride_agents * E), best_b = align16(key_bytes * p->g_stride_agents * E);
   const int64_t cred_b = align16(4 * p->g_stride_credits * E), image_b = p->big_spread ? 0 : p->g_stride_image * E;
-  // spread form: packed positions, ranks, the envs' scalars and the two sets of accumulators
+  // spread form: packed positions, the envs' scalars and the two sets of accumulators
   const int64_t pl_b = p->big_spread ? align16(4 * p->g_stride_agents * E) : 0;
-  const int64_t rank_b = p->big_spread ? align16(2 * p->g_stride_agents * E) : 0;
   const int64_t env_b = p->big_spread ? 16 * E : 0;
   const int64_t acc_b = p->big_spread ? 2 * 4 * p->g_stride_acc * E : 0;
   if (base) {
@@ -481,11 +480,10 @@ int64_t place_big_tables(wd::Params* p, int64_t E, unsigned char* base) {
     p->g_image = base + best_b + cred_b + slot_b;
     unsigned char* at = p->g_image + image_b;
     p->g_pl = reinterpret_cast<uint32_t*>(at);
-    p->g_rank = reinterpret_cast<uint16_t*>(at + pl_b);
-    p->g_env = reinterpret_cast<int32_t*>(at + pl_b + rank_b);
-    p->g_acc = reinterpret_cast<uint32_t*>(at + pl_b + rank_b + env_b);
+    p->g_env = reinterpret_cast<int32_t*>(at + pl_b);
+    p->g_acc = reinterpret_cast<uint32_t*>(at + pl_b + env_b);
   }
-  return slot_b + best_b + cred_b + image_b + pl_b + rank_b + env_b + acc_b;
+  return slot_b + best_b + cred_b + image_b + pl_b + env_b + acc_b;
 }
 
 // What a roll-out of the large-env layout needs to run the observation kernel of one iteration

@@ -125,9 +125,8 @@ struct Params {
   uint32_t tag_mul;        // coarse cell of a tagger: (x * tag_mul) >> 16 per axis, tag_nbx cells per side
   int32_t tag_nbx;
   uint32_t* g_pl;          // [E][NPAD] packed positions after the move and the tag check
-  uint16_t* g_rank;        // [E][NPAD] rank of a live agent among those of its bucket
   int32_t* g_env;          // [E][4] done, t, n_live_runners as the call found them
-  uint32_t* g_acc;         // [2][E][g_stride_acc]: nb_cap bucket counts, credits, number of tags
+  uint32_t* g_acc;         // [2][E][g_stride_acc]: credits per tagger, number of tags
   int64_t g_stride_acc;
   int32_t acc_credits, acc_tags;  // word offsets inside one env's accumulators
   // device buffers (borrowed from the caller)

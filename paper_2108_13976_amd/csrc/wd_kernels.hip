@@ -1135,7 +1135,6 @@ __global__ __launch_bounds__(kSpreadMoveThreads) void spread_move_kernel(const P
   if (mode == kModeIterate) store4(p.action, a0, mine.n, vec, mine.act);
   if (!step_act) return;
   uint32_t* const acc = p.g_acc + (int64_t(p.spread_parity) * p.E + e) * p.g_stride_acc;
-  const Buckets bk = choose_buckets(p, nlr_in + N_tag);
   int my_tags = 0;
   bool live_after[4];
   // A coarse cell is at least a tag radius wide, so a runner's reach touches at most 3 x 3 of them.
@@ -1179,27 +1178,20 @@ __global__ __launch_bounds__(kSpreadMoveThreads) void spread_move_kernel(const P
       ++my_tags;
     }
   }
-  // the four counts go out together; what each returns is the agent's rank inside its bucket
-  uint32_t packed[4];
-  uint32_t rank[4] = {0, 0, 0, 0};
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-    if (live_after[j]) rank[j] = atomicAdd(&acc[bucket_of(mine.x[j], mine.y[j], bk)], 1u);
   if (my_tags) atomicAdd(&acc[p.acc_tags], uint32_t(my_tags));
+  uint32_t packed[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     // (dead bit alone: tagged in this step; with the stale bit: out of play before it)
     packed[j] = pack_pos(mine.x[j], mine.y[j], live_after[j]) | (mine.lv[j] ? 0u : kStaleBit);
     mine.lv[j] = live_after[j] ? 1 : 0;
   }
+  *reinterpret_cast<uint4*>(p.g_pl + int64_t(e) * p.NPAD + i0) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
   if (mine.moved && i0 >= N_tag) {
     store4(p.pos_x, a0, mine.n, vec, mine.x);
     store4(p.pos_y, a0, mine.n, vec, mine.y);
   }
   if (my_tags) store4(p.live, a0, mine.n, vec, mine.lv);
-  *reinterpret_cast<uint4*>(p.g_pl + int64_t(e) * p.NPAD + i0) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
-  *reinterpret_cast<uint2*>(p.g_rank + int64_t(e) * p.NPAD + i0) =
-      make_uint2(rank[0] | (rank[1] << 16), rank[2] | (rank[3] << 16));
 }
 
 // spread_obs_kernel, workgroup (e, s): finishes the step of env e for index slice s (rewards, the
@@ -1226,27 +1218,15 @@ __global__ __launch_bounds__(kSpreadObsThreads) void spread_obs_kernel(const Par
   const bool stepping = mode == kModeStep || mode == kModeIterate;
   const uint32_t* const acc = p.g_acc + (int64_t(p.spread_parity) * p.E + e) * p.g_stride_acc;
   const uint32_t* const env_pl = p.g_pl + int64_t(e) * p.NPAD;
-  const uint16_t* const env_rank = p.g_rank + int64_t(e) * p.NPAD;
   const int acc_tags = int(acc[p.acc_tags]);
-  // What the tables of a stepped env are built from is asked for before anything waits for the env's
-  // scalars (a reset does not use it): packed positions straight into LDS, this thread's bucket
-  // counts and, when a thread has at most two groups, their ranks.
-  constexpr int kMaxScanChunk = 4, kRanksAhead = 2;  // (4096 buckets at most, 1024 threads)
-  const int j0 = tid * p.scan_chunk;
-  uint32_t cnt[kMaxScanChunk];
-  uint2 ranks_ahead[kRanksAhead];
+  // The packed positions of a stepped env go straight into LDS, and the bucket counters are cleared,
+  // before anything waits for the env's scalars (a reset does not use the positions).
   {
     const uint4* src = reinterpret_cast<const uint4*>(env_pl);
     uint4* dst = reinterpret_cast<uint4*>(L.pl);
 #pragma unroll 2
     for (int j = tid; j < p.NPAD / 4; j += ts) dst[j] = src[j];
-#pragma unroll
-    for (int c = 0; c < kMaxScanChunk; ++c) cnt[c] = c < p.scan_chunk ? acc[j0 + c] : 0u;
-#pragma unroll
-    for (int k = 0; k < kRanksAhead; ++k) {
-      const int i0 = 4 * (tid + k * ts);
-      ranks_ahead[k] = (p.gpt <= kRanksAhead && i0 < N) ? *reinterpret_cast<const uint2*>(env_rank + i0) : make_uint2(0u, 0u);
-    }
+    for (int j = tid; j < p.nb_cap; j += ts) L.counts[j] = 0u;
   }
   if (stepping) {  // the other set of accumulators is clear when the next call's first kernel starts
     uint32_t* const other = p.g_acc + (int64_t(p.spread_parity ^ 1) * p.E + e) * p.g_stride_acc;
@@ -1299,38 +1279,48 @@ __global__ __launch_bounds__(kSpreadObsThreads) void spread_obs_kernel(const Par
       p.done[e] = done_now ? 1 : 0;
     }
   }
-  Buckets bk;
-  if (reset_act) {
-    bk = choose_buckets(p, N);
-    for (int j = tid; j < p.nb_cap; j += ts) L.counts[j] = 0u;
-    for (int j = tid; j <= bk.nbx; j += ts) L.edges[j] = uint16_t(min(bucket_first_cell(j, bk), G));
-    __syncthreads();
-    for (int k = 0; k < p.gpt; ++k) {
-      const int grp = tid + k * ts;
-      if (grp < p.NG) {
-        const int i0 = 4 * grp, n = min(4, N - i0);
+  // The tables: a counting sort of the live agents by bucket, from the start positions after a reset,
+  // else from the packed positions in LDS (a thread counts the groups it put there itself).  Counting
+  // in the first kernel instead, with global atomics, was measured: they cost it two microseconds
+  // whether or not anything waits for what they return.
+  const Buckets bk = choose_buckets(p, reset_act ? N : nlr_in + N_tag);
+  for (int j = tid; j <= bk.nbx; j += ts) L.edges[j] = uint16_t(min(bucket_first_cell(j, bk), G));
+  __syncthreads();  // the counters are clear
+  for (int k = 0; k < p.gpt; ++k) {
+    const int grp = tid + k * ts;
+    if (grp < p.NG) {
+      const int i0 = 4 * grp, n = min(4, N - i0);
+      uint32_t packed[4];
+      if (reset_act) {
         int x[4], y[4];
         load4(p.pos_x0, abase + i0, n, vec, x);
         load4(p.pos_y0, abase + i0, n, vec, y);
-        uint32_t packed[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           x[j] = min(max(x[j], 0), G - 1);
           y[j] = min(max(y[j], 0), G - 1);
           packed[j] = pack_pos(x[j], y[j], j < n);
-          if (j < n) {
-            atomicAdd(&L.counts[bucket_of(x[j], y[j], bk)], 1u);
-            const int i = i0 + j;
-            if (i >= i_begin && i < i_end) {  // this slice's part of the state
-              p.pos_x[abase + i] = x[j];
-              p.pos_y[abase + i] = y[j];
-              p.live[abase + i] = 1;
-            }
+          const int i = i0 + j;
+          if (j < n && i >= i_begin && i < i_end) {  // this slice's part of the state
+            p.pos_x[abase + i] = x[j];
+            p.pos_y[abase + i] = y[j];
+            p.live[abase + i] = 1;
           }
         }
         *reinterpret_cast<uint4*>(L.pl + i0) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+      } else {
+        const uint4 v4 = *reinterpret_cast<const uint4*>(L.pl + i0);
+        packed[0] = v4.x;
+        packed[1] = v4.y;
+        packed[2] = v4.z;
+        packed[3] = v4.w;
       }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (!(packed[j] & kDeadBit)) atomicAdd(&L.counts[bucket_of(pos_x_of(packed[j]), pos_y_of(packed[j]), bk)], 1u);
     }
+  }
+  if (reset_act) {
     t_out = 0;
     if (s == 0 && tid == 0) {
       p.t[e] = 0;
@@ -1338,49 +1328,9 @@ __global__ __launch_bounds__(kSpreadObsThreads) void spread_obs_kernel(const Par
       p.tags_step[e] = 0;
       p.done[e] = 0;
     }
-    __syncthreads();
-    scan_and_scatter<WIDE>(p, L, true, tid, ts, bk);
-  } else {
-    bk = choose_buckets(p, nlr_in + N_tag);
-    for (int j = tid; j <= bk.nbx; j += ts) L.edges[j] = uint16_t(min(bucket_first_cell(j, bk), G));
-    int part = 0;
-#pragma unroll
-    for (int c = 0; c < kMaxScanChunk; ++c) part += int(cnt[c]);
-    int total = 0;
-    int run = team_exclusive_scan(part, tid, p.ts_log2, L.misc + 4, &total);
-#pragma unroll
-    for (int c = 0; c < kMaxScanChunk; ++c) {
-      if (c < p.scan_chunk) L.starts[j0 + c] = uint16_t(run);
-      run += int(cnt[c]);
-    }
-    if (tid == ts - 1) L.starts[p.nb_cap] = uint16_t(total);
-    __syncthreads();
-    const auto place = [&](int i0, uint2 r2) {
-      const uint4 v4 = *reinterpret_cast<const uint4*>(L.pl + i0);
-      const uint32_t v[4] = {v4.x, v4.y, v4.z, v4.w};
-      const uint32_t rk[4] = {r2.x & 0xFFFFu, r2.x >> 16, r2.y & 0xFFFFu, r2.y >> 16};
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (!(v[j] & kDeadBit)) {
-          const int x = pos_x_of(v[j]), y = pos_y_of(v[j]);
-          L.sorted.put(uint32_t(L.starts[bucket_of(x, y, bk)]) + rk[j], x, y, i0 + j);
-        }
-      }
-    };
-    if (p.gpt <= kRanksAhead) {
-#pragma unroll
-      for (int k = 0; k < kRanksAhead; ++k) {
-        const int i0 = 4 * (tid + k * ts);
-        if (i0 < N) place(i0, ranks_ahead[k]);
-      }
-    } else {
-      for (int k = 0; k < p.gpt; ++k) {
-        const int i0 = 4 * (tid + k * ts);
-        if (i0 < N) place(i0, *reinterpret_cast<const uint2*>(env_rank + i0));
-      }
-    }
-    __syncthreads();
   }
+  __syncthreads();
+  scan_and_scatter<WIDE>(p, L, true, tid, ts, bk);
 
   const int64_t D = KX > 0 ? 5 + 4 * KX : p.D;
   float* const env_obs = p.obs + abase * D;
@@ -1389,23 +1339,25 @@ __global__ __launch_bounds__(kSpreadObsThreads) void spread_obs_kernel(const Par
   const int n_sorted = int(L.starts[p.nb_cap]);
   const int q_chunk = (n_sorted + p.big_slices - 1) / p.big_slices;
   int q_begin = min(n_sorted, s * q_chunk), q_end = min(n_sorted, (s + 1) * q_chunk);
-  if (reset_act) {
+  {
     // The counting sort leaves the order inside a bucket to chance, so the lists of an env's workgroups
-    // agree on the buckets only: the slices end on bucket boundaries (after a step the ranks are
-    // shared and the lists are the same everywhere).
-    const auto next_bucket_start = [&](int q) {  // the first bucket start that is >= q
-      int lo = 0, hi = p.nb_cap;
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (int(L.starts[mid]) >= q)
-          hi = mid;
-        else
-          lo = mid + 1;
-      }
-      return int(L.starts[lo]);
-    };
-    q_begin = next_bucket_start(q_begin);
-    q_end = next_bucket_start(q_end);
+    // agree on the buckets only: a slice runs from the first bucket start at or behind its first slot
+    // to the first at or behind its end.  Every thread looks at its own few bucket starts (a binary
+    // search would be two dozen dependent reads for every thread).
+    int32_t* const bound = L.misc + 4;  // (scan scratch, free again)
+    const int j0 = tid * p.scan_chunk;
+    int prev = j0 ? int(L.starts[j0 - 1]) : -1;
+    for (int c = 0; c <= p.scan_chunk; ++c) {
+      const int j = j0 + c;
+      if (c == p.scan_chunk && tid != ts - 1) break;  // (entry nb_cap, the number of agents, belongs to the last thread)
+      const int v = int(L.starts[j]);
+      if (v >= q_begin && prev < q_begin) bound[0] = v;
+      if (v >= q_end && prev < q_end) bound[1] = v;
+      prev = v;
+    }
+    __syncthreads();
+    q_begin = bound[0];
+    q_end = bound[1];
   }
   // Two neighbouring lanes per agent: each searches half of the candidates and writes half of the
   // row (collecting a wave's rows in LDS and writing them out whole was measured: slower).

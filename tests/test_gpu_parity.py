@@ -653,15 +653,16 @@ def _extra_seed_chunks(per_chunk=20):
 @pytest.mark.parametrize("seeds", _extra_seed_chunks(), ids=lambda r: f"seeds{r.start}-{r.stop - 1}")
 def test_many_more_random_configurations(seeds):
     """Further random configurations, twenty to a test (WD_EXTRA_SEEDS of them in all, 240 by default):
-    every third with 384 .. 3073 agents in a few envs, the shapes that run in the large-env pair of
-    kernels or in wide workgroups, with K from 0 to 16."""
+    every third with 384 .. 8192 agents in a few envs, the shapes that run in either form of the
+    large-env pair of kernels or in wide workgroups, with K from 0 to 16."""
     for seed in seeds:
         kw = random_configuration(seed)
         large = seed % 3 == 0
         if large:
             rng = np.random.default_rng(77000 + seed)
-            n = int(rng.choice([384, 385, 640, 700, 1023, 1024, 1025, 1300, 2050, 3073]))
-            kw.update(num_agents=n, num_taggers=int(rng.integers(1, max(2, n // 8))), num_envs=int(rng.integers(1, 6)),
+            n = int(rng.choice([384, 385, 640, 700, 1023, 1024, 1025, 1300, 2050, 3073, 4100, 8192]))
+            taggers = int(rng.integers(1, n)) if rng.random() < 0.25 else int(rng.integers(1, max(2, n // 8)))
+            kw.update(num_agents=n, num_taggers=taggers, num_envs=int(rng.integers(1, 6)),
                       episode_length=int(rng.integers(1, 5)), obs_k=int(rng.choice([0, 1, 2, 3, 4, 5, 6, 8, 9, 16])))
             kw.pop("obs_mode", None)
         try:
