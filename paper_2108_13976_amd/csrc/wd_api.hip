@@ -278,6 +278,24 @@ bool plan_env_kernels(const wd_config& c, wd::Params* p, bool big, bool big_tabl
       p->dead_dx = int32_t(shift);
     }
   }
+  // The variants with 32-bit keys and K = 1 .. 8 compiled in (small layout) sort by strip and keep the
+  // positions of that list scaled by 2^h per axis (2 h >= idx_bits), so that the squared length of a
+  // packed 16-bit difference is the key's distance part where it belongs; an entry out of play has y
+  // field 0x7FFF.  That needs room in 16 bits: the keys of such entries, at least (32767 - A)^2 with
+  // A = (G - 1) << h, must lie above every key of a live pair, below 2 A^2 + 2^(2 h).  Larger grids
+  // take 64-bit keys and the bucket rings.
+  if (narrow && !big && c.obs_mode == WD_OBS_PARTIAL && p->K >= 1 && p->K <= wd::kMaxRegisterK) {
+    const int h = (p->idx_bits + 1) / 2;
+    const int64_t A = int64_t(G - 1) << h;
+    const int64_t dead_min = A < 32767 ? (32767 - A) * (32767 - A) : 0;
+    if (A < 32767 && 2 * A * A + (int64_t(1) << (2 * h)) <= dead_min) {
+      p->pos_shift = h;
+      p->key_shift = 2 * h;
+      p->dead_key_min = uint32_t(dead_min);
+    } else {
+      narrow = false;
+    }
+  }
   // Else, in the large-env layout: keys that need all 32 bits, the dead mark moved into bit 15
   // of the index array.  Else 64-bit keys.
   const bool flagged32 = !narrow && big && p->idx_bits <= 15 && G <= 32767 &&

@@ -14,6 +14,14 @@
 // beyond a window is at least as far in x as that window's last entry, and an agent of any other
 // strip is beyond the far edge of the neighbouring strip.  Agents whose windows do not settle it
 // (a few per cent) are queued for an exact block search over the same list.
+//
+// Positions in this list are kept scaled: x << h | (y << h) << 16 with 2 h = key_shift >= idx_bits.
+// The packed difference to the agent's own entry is then (dx << h, dy << h), and its dot product
+// with itself, accumulated onto the candidate's index, IS the key (d^2 << key_shift) + index: two
+// vector instructions per candidate in front of the insertion instead of three.  An entry out of
+// play (tagged in this step, or a pad) has y field 0x7FFF: its keys are at least
+// Params.dead_key_min, above every key of a live pair (the host checks that the grid is small
+// enough for that: (G - 1) << h at most about 13 500).
 #ifndef WD_DEV_STRIPS_H
 #define WD_DEV_STRIPS_H
 
@@ -24,6 +32,7 @@
 namespace wd {
 namespace dev {
 
+constexpr uint32_t kStripDeadY = 0x7FFFu;     // y field of a list entry that is out of play
 constexpr int kFar = 32767;                  // "no bound on this side", in cells
 constexpr uint32_t kFarSq = 32767u * 32767u;  // its square: above every squared distance of 32-bit keys
 
@@ -33,6 +42,8 @@ struct Strips {
   int C;         // columns per strip
   int cshift;    // column of cell x: x >> cshift
   int hu;        // cells in the shortest strip
+  int h;         // list positions are scaled by 2^h per axis
+  uint32_t dead_min;  // keys from here on belong to entries out of play (or are empty)
 };
 
 // Strips for n_live agents: about strip_scale * sqrt(n) of them (the expected distance of the
@@ -48,6 +59,8 @@ __device__ __forceinline__ Strips choose_strips(const Params& p, int n_live) {
   s.cshift = p.cshift;
   uint32_t w = 65536u / s.mul;
   s.hu = int(max(w, 1u));
+  s.h = p.pos_shift;
+  s.dead_min = p.dead_key_min;
   return s;
 }
 
@@ -59,6 +72,8 @@ __device__ __forceinline__ Strips strips_of_env(const Params& p, uint32_t mul, i
   s.C = p.strip_C;
   s.cshift = p.cshift;
   s.hu = int(max(65536u / max(mul, 1u), 1u));
+  s.h = p.pos_shift;
+  s.dead_min = p.dead_key_min;
   return s;
 }
 
@@ -127,7 +142,8 @@ __device__ __forceinline__ void strip_scan_and_scatter(const Params& p, const Ta
     }
   __syncthreads();
   if (act) {
-    const uint32_t pad = uint32_t(p.dead_dx) << 16;
+    const uint32_t pad = kStripDeadY << 16;
+    const int h = p.pos_shift;
     for (int j = lt; j < p.pad_l + p.pad_r; j += ts) {
       const int at = j < p.pad_l ? -1 - j : total + (j - p.pad_l);
       L.sorted.pos[at] = pad;
@@ -143,7 +159,7 @@ __device__ __forceinline__ void strip_scan_and_scatter(const Params& p, const Ta
           if (!(v[j] & kDeadBit)) {
             const int x = pos_x_of(v[j]), y = pos_y_of(v[j]);
             const uint32_t at = strip_take_slot(tw, strip_bin(x, y, sg));
-            L.sorted.put(at, x, y, i0 + j);
+            L.sorted.put(at, x << h, y << h, i0 + j);
             L.slot[i0 + j] = uint16_t(at);
           }
         }
@@ -167,7 +183,7 @@ __device__ __forceinline__ void strip_tag_scan(const Params& p, const Tables& L,
       const uint32_t pv = L.sorted.pos[q];
       const int j = int(L.sorted.id[q]);
       if (j < p.N_tag) continue;
-      const int dx = int(pv & 0xFFFFu) - x, dy = int(pv >> 16) - y;
+      const int dx = int((pv & 0xFFFFu) >> p.pos_shift) - x, dy = int(pv >> (16 + p.pos_shift)) - y;
       const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
       if (d2 <= uint32_t(p.tag_r2)) atomicMin(&L.best[j], (d2 << p.idx_bits) | uint32_t(i));
     }
@@ -194,6 +210,13 @@ __device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)"
 // ties a value loaded by lds_read_u16 to the lds_wait() in front of it
 __device__ __forceinline__ void lds_loaded(uint32_t& v) { asm volatile("" : "+v"(v)); }
 
+// Key of a candidate: squared length of the packed, scaled difference plus the candidate's index.
+__device__ __forceinline__ uint32_t strip_key(short2v d, uint32_t index) {
+  uint32_t r;
+  asm("v_dot2_i32_i16 %0, %1, %1, %2" : "=v"(r) : "v"(d), "v"(index));
+  return r;
+}
+
 // kN consecutive slots from slot kFirst of `wp` / `wi` on as candidates (one chunk of a window).
 template <int K, int kFirst, int... J>
 __device__ __forceinline__ void scan_chunk(uint32_t (&keys)[K], const uint32_t* __restrict__ wp, const uint16_t* wi,
@@ -205,7 +228,7 @@ __device__ __forceinline__ void scan_chunk(uint32_t (&keys)[K], const uint32_t* 
   ((iv[J] = lds_read_u16<2 * (kFirst + J)>(wi)), ...);
   lds_wait();
   (lds_loaded(iv[J]), ...);
-  (insert_key<K>(keys, (squared_length(__builtin_bit_cast(short2v, pv[J]) - mev) << ib) | iv[J]), ...);
+  (insert_key<K>(keys, strip_key(__builtin_bit_cast(short2v, pv[J]) - mev, iv[J])), ...);
   first = pv[0];
   last = pv[kN - 1];
 }
@@ -247,7 +270,7 @@ __device__ __forceinline__ bool strip_window_search(uint32_t (&keys)[K], uint32_
                                                     const uint16_t* __restrict__ edges) {
   constexpr int kLevels = HF > 0 ? 2 : 1;
   const short2v mev = __builtin_bit_cast(short2v, me);
-  const int X = int(me & 0xFFFFu), Y = int(me >> 16);
+  const int X = int((me & 0xFFFFu) >> sg.h), Y = int(me >> (16 + sg.h));
   const int r = strip_of(Y, sg);
   const uint32_t cm = (1u << sg.cshift) - 1u;
   const int C = sg.C;
@@ -270,8 +293,8 @@ __device__ __forceinline__ bool strip_window_search(uint32_t (&keys)[K], uint32_
       scan_slots<K, HO>(keys, pos + (q - HO), id + (q - HO), mev, ib, first, unused);
       scan_slots<K, HO>(keys, pos + (q + 1), id + (q + 1), mev, ib, unused, last);
     }
-    const int bl = side_bound(!below || q - HO <= s_own, X - int((first & 0xFFFFu) | cm));
-    const int br = side_bound(!above || q + HO >= e_own - 1, int((last & 0xFFFFu) & ~cm) - X);
+    const int bl = side_bound(!below || q - HO <= s_own, X - int(((first & 0xFFFFu) >> sg.h) | cm));
+    const int br = side_bound(!above || q + HO >= e_own - 1, int(((last & 0xFFFFu) >> sg.h) & ~cm) - X);
     const int b = min(bl, br);
     reach2 = uint32_t(__mul24(b, b));
     lo_edge = min(s_own, q - HO);
@@ -304,8 +327,8 @@ __device__ __forceinline__ bool strip_window_search(uint32_t (&keys)[K], uint32_
         scan_slots<K, 2 * (HF > 0 ? HF : kNone)>(keys, pos + a, id + a, mev, ib, first, last);
       const bool done_l = up ? a <= near_end : a <= far_end;
       const bool done_r = up ? a + 2 * H >= far_end : a + 2 * H >= near_end;
-      const int bl = side_bound(done_l, X - int((first & 0xFFFFu) | cm));
-      const int br = side_bound(done_r, int((last & 0xFFFFu) & ~cm) - X);
+      const int bl = side_bound(done_l, X - int(((first & 0xFFFFu) >> sg.h) | cm));
+      const int br = side_bound(done_r, int(((last & 0xFFFFu) >> sg.h) & ~cm) - X);
       const int b = lost ? 0 : min(bl, br);
       const uint32_t bound = uint32_t(__mul24(b, b)) + uint32_t(__mul24(gap, gap));
       reach2 = min(reach2, has ? bound : kFarSq);
@@ -333,7 +356,7 @@ __device__ __forceinline__ bool strip_window_search(uint32_t (&keys)[K], uint32_
   }
   const uint32_t kth = keys[K - 1];
   // (nothing unseen anywhere: the list is complete even if it holds fewer than K agents)
-  return reach2 >= kFarSq || (!(kth & kDeadBit) && (kth >> ib) < reach2);
+  return reach2 >= kFarSq || (kth < sg.dead_min && (kth >> ib) < reach2);
 }
 
 // A list of a few dozen agents: every entry is a candidate (exact without any bound; every lane
@@ -352,7 +375,7 @@ __device__ __forceinline__ void scan_all_chunk(uint32_t (&keys)[K1], const uint3
   ((iv[J] = lds_read_u16<2 * J>(wi)), ...);
   lds_wait();
   (lds_loaded(iv[J]), ...);
-  (insert_key<K1>(keys, (squared_length(__builtin_bit_cast(short2v, pv[J]) - mev) << ib) | iv[J]), ...);
+  (insert_key<K1>(keys, strip_key(__builtin_bit_cast(short2v, pv[J]) - mev, iv[J])), ...);
 }
 
 template <int K>
@@ -382,7 +405,7 @@ __device__ __forceinline__ void strip_block_search(uint32_t (&keys)[K], uint32_t
                                                    const uint16_t* __restrict__ id, const uint16_t* __restrict__ T,
                                                    const uint16_t* __restrict__ edges) {
   const short2v mev = __builtin_bit_cast(short2v, me);
-  const int X = int(me & 0xFFFFu), Y = int(me >> 16);
+  const int X = int((me & 0xFFFFu) >> sg.h), Y = int(me >> (16 + sg.h));
   for (int m = 2;; m *= 2) {
     const int half = min(m * sg.hu, kFar);
     const int c0 = max(X - half, 0) >> sg.cshift, c1 = min(X + half, G - 1) >> sg.cshift;
@@ -392,7 +415,7 @@ __device__ __forceinline__ void strip_block_search(uint32_t (&keys)[K], uint32_t
     for (int row = r0; row <= r1; ++row) {
       const uint32_t qe = T[row * sg.C + c1 + 1];
       for (uint32_t s = T[row * sg.C + c0]; s < qe; ++s) {
-        const uint32_t key = (squared_length(__builtin_bit_cast(short2v, pos[s]) - mev) << ib) | uint32_t(id[s]);
+        const uint32_t key = strip_key(__builtin_bit_cast(short2v, pos[s]) - mev, uint32_t(id[s]));
         insert_key<K>(keys, s == q ? ~0u : key);
       }
     }
@@ -403,7 +426,7 @@ __device__ __forceinline__ void strip_block_search(uint32_t (&keys)[K], uint32_t
     if (r1 < sg.R - 1) reach = min(reach, int(edges[r1 + 1]) - Y);
     if (reach == kFar) return;  // the block covers the grid
     const uint32_t kth = keys[K - 1];
-    if (!(kth & kDeadBit) && (kth >> ib) < uint32_t(__mul24(reach, reach))) return;
+    if (kth < sg.dead_min && (kth >> ib) < uint32_t(__mul24(reach, reach))) return;
   }
 }
 

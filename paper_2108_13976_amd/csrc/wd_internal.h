@@ -94,6 +94,9 @@ struct Params {
   int32_t strip_rmax;    // most strips the table holds (and the grid has rows for)
   float strip_scale;     // strips aimed at = strip_scale * sqrt(live agents)
   int32_t pad_l, pad_r;  // entries in front of and behind the list that read as "no agent"
+  int32_t pos_shift;     // positions in the list are scaled by 2^pos_shift per axis, so that the squared length
+  int32_t key_shift;     // of a packed difference is the squared distance << key_shift (= 2 pos_shift >= idx_bits)
+  uint32_t dead_key_min; // keys of list entries out of play start here, above every key of a live pair
   // LDS map.  Per team: a kept part (positions, scalars); an X part (bucket-sorted entries
   // and bucket starts) that the row staging area overlays once the neighbour search is done;
   // a Y part (slots, tag keys, credits, bucket counters) that the neighbour lists overlay

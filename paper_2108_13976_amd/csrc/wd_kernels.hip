@@ -277,7 +277,10 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
               if (b != key_none<Key>()) {
                 me |= kDeadBit;
                 L.pl[i] = me;
-                L.sorted.mark_dead(L.slot[i]);
+                if constexpr (STRIP)
+                  L.sorted.pos[L.slot[i]] |= kStripDeadY << 16;
+                else
+                  L.sorted.mark_dead(L.slot[i]);
                 atomicAdd(&L.credits[int(b & idx_mask)], 1);
                 ++my_tags;
                 any = true;
@@ -445,18 +448,23 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
     // every live agent tries the 3x3 buckets around it; the few that this does not settle
     // (sparse spots, grid borders) queue up and are searched with widening rings afterwards,
     // packed into full waves, so that a wave of the first pass never waits for one such lane.
+    // (a key of the strip search is empty, or an entry's that is out of play, from dead_key_min on)
+    const auto is_none = [&](Key k) {
+      if constexpr (STRIP) return k >= Key(p.dead_key_min);
+      return key_is_none<WIDE>(k);
+    };
     const auto put_neighbours_of = [&](const TeamLds<WIDE, BIG>& Lt, uint32_t me, const Key(&keys)[KT]) {
       if constexpr (CN) {
         uint32_t id[4];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) id[kk] = key_is_none<WIDE>(keys[kk]) ? kCompactNone : uint32_t(keys[kk] & idx_mask);
+        for (int kk = 0; kk < 4; ++kk) id[kk] = is_none(keys[kk]) ? kCompactNone : uint32_t(keys[kk] & idx_mask);
         Lt.nbr_lo[me] = id[0] | (id[1] << 10) | (id[2] << 20) | (id[3] << 30);
         Lt.nbr_hi[me] = uint8_t(id[3] >> 2);
       } else {
 #pragma unroll
         for (int kk = 0; kk < KT; ++kk)
           if (kk < K)
-            Lt.nbr[me * K + kk] = key_is_none<WIDE>(keys[kk]) ? uint16_t(kNoNeighbour) : uint16_t(keys[kk] & idx_mask);
+            Lt.nbr[me * K + kk] = is_none(keys[kk]) ? uint16_t(kNoNeighbour) : uint16_t(keys[kk] & idx_mask);
       }
     };
     const auto put_neighbours = [&](uint32_t me, const Key(&keys)[KT]) { put_neighbours_of(L, me, keys); };
@@ -499,13 +507,13 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
         const bool few = n_sorted <= kStripScanAll;  // (uniform: an env's whole list is cheaper than its windows)
         for (int q = wave_lane; q < n_sorted; q += wave_stride) {
           const uint32_t me = Lt.sorted.pos[q];
-          if (int(me >> 16) < p.dead_dx) {  // not tagged in this step
+          if ((me >> 16) != kStripDeadY) {  // not tagged in this step
             Key keys[KT];
             if (few) {
-              strip_scan_all<KX>(keys, me, uint32_t(q), uint32_t(n_sorted), p.idx_bits, Lt.sorted.pos, Lt.sorted.id);
+              strip_scan_all<KX>(keys, me, uint32_t(q), uint32_t(n_sorted), p.key_shift, Lt.sorted.pos, Lt.sorted.id);
               put_neighbours_of(Lt, Lt.sorted.id[q], keys);
             } else if (strip_window_search<KX, strip_half_own(KX), strip_half_adj(KX), 0, false>(
-                           keys, me, q, 0, st, p.idx_bits, n_sorted, p.pad_l, Lt.sorted.pos, Lt.sorted.id, Lt.starts,
+                           keys, me, q, 0, st, p.key_shift, n_sorted, p.pad_l, Lt.sorted.pos, Lt.sorted.id, Lt.starts,
                            Lt.edges)) {
               put_neighbours_of(Lt, Lt.sorted.id[q], keys);
             } else {
@@ -534,14 +542,14 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
         const uint32_t me = Lt.sorted.pos[q];
         Key keys[KT];
         bool ok = strip_window_search<KX, strip_half_own2(KX), strip_half_adj2(KX), strip_half_far2(KX), true>(
-            keys, me, q, side, st, p.idx_bits, n_sorted, p.pad_l, Lt.sorted.pos, Lt.sorted.id, Lt.starts, Lt.edges);
+            keys, me, q, side, st, p.key_shift, n_sorted, p.pad_l, Lt.sorted.pos, Lt.sorted.id, Lt.starts, Lt.edges);
         if (side) return;  // the even lane goes on for both
         if (!ok) {
           const int at = atomicAdd(&Lt.misc[kMiscQueue2], 1);
           if (at < kStripQueue2) {
             reinterpret_cast<uint16_t*>(Lt.misc + 4)[at] = uint16_t(q);  // (the scan scratch, idle by now)
           } else {  // the queue is full: search here and now
-            strip_block_search<KX>(keys, me, uint32_t(q), st, p.idx_bits, G, Lt.sorted.pos, Lt.sorted.id, Lt.starts,
+            strip_block_search<KX>(keys, me, uint32_t(q), st, p.key_shift, G, Lt.sorted.pos, Lt.sorted.id, Lt.starts,
                                    Lt.edges);
             ok = true;
           }
@@ -602,7 +610,7 @@ __device__ __forceinline__ void env_body(KernargParams pk, const StepOut out, co
         for (int j = wave_lane; j < n_wait; j += wave_stride) {
           const uint32_t q = queue2[j];
           Key keys[KT];
-          strip_block_search<KX>(keys, Lt.sorted.pos[q], q, st, p.idx_bits, G, Lt.sorted.pos, Lt.sorted.id, Lt.starts,
+          strip_block_search<KX>(keys, Lt.sorted.pos[q], q, st, p.key_shift, G, Lt.sorted.pos, Lt.sorted.id, Lt.starts,
                                  Lt.edges);
           put_neighbours_of(Lt, Lt.sorted.id[q], keys);
         }
