@@ -40,6 +40,7 @@ constexpr int kMaxGrid = 32767;
 // spread form of the large-env pair: while its observation kernel has a compute unit per workgroup to spare
 constexpr int kSpreadMaxWorkgroups = 192;
 constexpr int kSpreadMinAgents = 1024;
+constexpr int kWaveEnvsMaxBatch = 4096;  // envs; beyond that the general kernel's throughput counts, not its latency
 
 int bits_for(uint32_t v) {  // bits needed to hold values 0..v
   int b = 1;
@@ -398,6 +399,10 @@ void plan_spread(const wd_config& c, wd::Params* p) {
       int64_t(c.num_envs) * p->big_slices > kSpreadMaxWorkgroups)
     return;
   p->big_spread = 1;
+  // The second kernel's slices: as many as the chip has compute units for, down to 256 agents each (every
+  // slice sorts the whole env, so narrower slices only shorten the search and the row stores:
+  // tag_10x8192 with 12 / 16 / 20 / 25 slices per env: 30.6 / 28.6 / 28.2 / 28.0 us per iteration).
+  p->big_slices = std::max<int64_t>(p->big_slices, std::min<int64_t>(std::min<int64_t>(64, c.num_agents / 256), 250 / c.num_envs));
   p->spread_slices = (p->NG + wd::kSpreadMoveThreads - 1) / wd::kSpreadMoveThreads;
   // coarse cells of the taggers' table: at least a tag radius wide, so that a runner looks at no
   // more than three per axis, and at most kSpreadTagSide per grid side
@@ -473,6 +478,12 @@ int fill_params(const wd_config& c, const wd_buffers& b, wd::Params* p) {
   }
   if (!planned || !wd::env_kernel_available(*p)) return WD_E_UNSUPPORTED;
   plan_spread(c, p);
+  // Envs that fit a wave, in a batch that cannot fill the chip anyway: a wave per env, a lane per agent
+  // (keys of 32 bits: squared distance << 6 | index).
+  p->wave_envs = (!p->big && c.num_agents <= wd::kWaveSize && c.num_envs <= kWaveEnvsMaxBatch &&
+                  c.obs_mode == WD_OBS_PARTIAL && p->K <= wd::kMaxRegisterK && c.grid_size <= 4096)
+                     ? 1
+                     : 0;
   return WD_OK;
 }
 

@@ -132,6 +132,7 @@ struct Params {
   uint32_t* g_acc;         // [2][E][g_stride_acc]: credits per tagger, number of tags
   int64_t g_stride_acc;
   int32_t acc_credits, acc_tags;  // word offsets inside one env's accumulators
+  int32_t wave_envs;     // 1: envs of at most 64 agents in a small batch run in wave_env_kernel, a wave per env
   // device buffers (borrowed from the caller)
   int32_t *pos_x, *pos_y, *pos_x0, *pos_y0, *live, *action;
   float* reward;

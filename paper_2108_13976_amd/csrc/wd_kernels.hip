@@ -9,6 +9,7 @@
 // in LDS, the pairwise passes (tag check, K-nearest search) run over a bucket-sorted copy
 // of the live agents instead of over all pairs, and observation rows leave through an LDS
 // transpose so that HBM sees whole lines.
+#include <cstring>
 #include <type_traits>
 
 #include "wd_dev_common.h"
@@ -1467,6 +1468,195 @@ __global__ __launch_bounds__(kMaxEnvWorkgroupSize)
   if (roll.obs) copy_words(roll.obs + (last + first) * p.D, p.obs + first * p.D, count * p.D);
 }
 
+// ----------------------------------------------------------------------------------
+// Small envs of a small batch: one wave per env, one lane per agent, everything in registers.
+// Such a batch is bound by the latency of one workgroup's chain of phases, not by any pipe (the
+// regime in which the paper's own throughput grows linearly with the number of envs, Sec. 5.3), and
+// the general kernel's chain (tables in LDS, a dozen workgroup barriers) is long for an env that
+// fits a wave.  Here a lane reads any other agent's position with a lane read: the tag check is
+// a loop over the taggers (a runner keeps the smallest (distance, tagger) key in range, credits
+// are counted by votes), the K nearest a loop over the agents in play with the same sorted
+// insertion as elsewhere; rows go to memory straight from registers.  Several iterations per launch
+// (wd_rollout) keep the whole state in registers in between.  Same results as env_kernel.
+// ----------------------------------------------------------------------------------
+struct WaveArgs {
+  Params p;
+  Roll roll;           // a single call: steps = 1, ring_len = 1, no slices but roll.done = p.done_log
+  const float* probs;  // the ring's base, or the one array of a single call
+  uint64_t g0;
+  int32_t mode;
+};
+
+template <int KC>
+__global__ __launch_bounds__(kWaveSize) void wave_env_kernel(const WaveArgs args) {
+  const Params& p = args.p;
+  const Roll& roll = args.roll;
+  constexpr int KT = KC > 0 ? KC : kMaxRegisterK;
+  const int a = threadIdx.x, e = blockIdx.x;
+  const int N = p.N, N_tag = p.N_tag, G = p.G;
+  const int K = KC > 0 ? KC : p.K;
+  const int64_t D = 5 + 4 * K;
+  const bool active = a < N;
+  const int64_t EN = int64_t(p.E) * N, ai = int64_t(e) * N + (active ? a : 0);
+  const int mode = args.mode;
+  const bool stepping = mode == kModeStep || mode == kModeIterate;
+  int x = 0, y = 0;
+  bool lv = false;
+  int done = 0, t = 0, nlr = 0, tags_out = -1;  // (tags_out < 0: tags_step keeps its value)
+  if (mode != kModeResetAll) {
+    if (active) {
+      x = min(max(p.pos_x[ai], 0), G - 1);
+      y = min(max(p.pos_y[ai], 0), G - 1);
+      lv = p.live[ai] != 0;
+    }
+    done = p.done[e];
+    t = p.t[e];
+    nlr = p.n_live_runners[e];
+  }
+  // (the first four probabilities decide a draw, the fifth action is the fall-through; those of the
+  // next iteration are requested while this one runs)
+  const auto load_probs = [&](int s, float (&f)[4]) {
+    const float* pr = args.probs + int64_t((roll.ring_pos + s) % roll.ring_len) * EN * kNumActions + ai * kNumActions;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) f[c] = active ? pr[c] : 0.0f;
+  };
+  float f_next[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (mode == kModeIterate) load_probs(0, f_next);
+  for (int s = 0; s < roll.steps; ++s) {
+    const bool last = s + 1 == roll.steps;
+    const uint64_t g = args.g0 + uint64_t(s);
+    int act = 0;
+    if (mode == kModeIterate) {
+      const float f[4] = {f_next[0], f_next[1], f_next[2], f_next[3]};
+      if (!last) load_probs(s + 1, f_next);
+      const Block4 r = random_block(p, uint32_t(e), uint32_t(a >> 2), uint32_t(g), uint32_t(g >> 32), kStreamAction);
+      const uint32_t w = (a & 2) ? ((a & 1) ? r.w[3] : r.w[2]) : ((a & 1) ? r.w[1] : r.w[0]);
+      act = sample_action(f[0], f[1], f[2], f[3], w);
+      if (active) {
+        if (last) p.action[ai] = act;
+        if (roll.action) roll.action[int64_t(s) * EN + ai] = act;
+      }
+    } else if (stepping && active) {
+      act = p.action[ai];
+    }
+    bool out_act = false;
+    if (stepping && !done) {
+      if (active && lv) {
+        x = min(max(x + (act == 4) - (act == 3), 0), G - 1);
+        y = min(max(y + (act == 1) - (act == 2), 0), G - 1);
+      }
+      uint32_t best = ~0u;
+      if (p.tag_r2 >= 0)
+        for (int tg = 0; tg < N_tag; ++tg) {
+          const int dx = __builtin_amdgcn_readlane(x, tg) - x, dy = __builtin_amdgcn_readlane(y, tg) - y;
+          const uint32_t d2 = uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy));
+          if (d2 <= uint32_t(p.tag_r2)) best = min(best, (d2 << 6) | uint32_t(tg));
+        }
+      const bool tagged = active && a >= N_tag && lv && best != ~0u;
+      const int tags = __popcll(__ballot(tagged));
+      int credit = 0;
+      if (tags)
+        for (int tg = 0; tg < N_tag; ++tg) {
+          const int c = __popcll(__ballot(tagged && int(best & 63u) == tg));
+          if (a == tg) credit = c;
+        }
+      if (tagged) lv = false;
+      if (active) {
+        const float rew = a < N_tag ? static_cast<float>(credit) * p.tag_reward : (tagged ? p.tag_penalty : 0.0f);
+        if (last) p.reward[ai] = rew;
+        if (roll.reward) roll.reward[int64_t(s) * EN + ai] = rew;
+      }
+      nlr -= tags;
+      t += 1;
+      done = (nlr == 0 || t >= p.T) ? 1 : 0;
+      tags_out = tags;
+      out_act = true;
+    }
+    if (mode != kModeStep) {
+      if (roll.done && a == 0) roll.done[int64_t(s) * p.E + e] = done;  // the flag before the reset clears it
+      if (mode == kModeResetAll || done) {
+        if (active) {
+          x = min(max(p.pos_x0[ai], 0), G - 1);
+          y = min(max(p.pos_y0[ai], 0), G - 1);
+        }
+        lv = active;
+        t = 0;
+        nlr = N - N_tag;
+        done = 0;
+        tags_out = 0;
+        out_act = true;
+      }
+    }
+    if (!out_act) continue;  // this env keeps its rows
+    // ---- observations: the K nearest agents in play, by (squared distance, index) ----
+    const uint64_t in_play = __ballot(active && lv);
+    uint32_t keys[KT];
+#pragma unroll
+    for (int kk = 0; kk < KT; ++kk) keys[kk] = ~0u;
+    if (K > 0)
+      for (int j = 0; j < N; ++j) {
+        if (!((in_play >> j) & 1ull)) continue;
+        const int dx = __builtin_amdgcn_readlane(x, j) - x, dy = __builtin_amdgcn_readlane(y, j) - y;
+        const uint32_t key = ((uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy))) << 6) | uint32_t(j);
+        insert_key<KT>(keys, j == a ? ~0u : key);
+      }
+    float* const rows[2] = {last ? p.obs + ai * D : nullptr, roll.obs ? roll.obs + (int64_t(s) * EN + ai) * D : nullptr};
+    const float t_frac = static_cast<float>(t) * p.inv_T;
+    const float own[5] = {static_cast<float>(x) * p.inv_G, static_cast<float>(y) * p.inv_G, a < N_tag ? 1.0f : 0.0f,
+                          lv ? 1.0f : 0.0f, t_frac};
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+      if (active && rows[r]) {
+#pragma unroll
+        for (int c = 0; c < 5; ++c) rows[r][c] = own[c];
+      }
+#pragma unroll
+    for (int kk = 0; kk < KT; ++kk) {
+      if (kk < K) {
+        // no branch: an empty slot looks up the agent itself, whose offsets are zero
+        const bool none = !lv || keys[kk] == ~0u;
+        const int j = none ? a : int(keys[kk] & 63u);
+        const int ox = __shfl(x, j), oy = __shfl(y, j);
+        const float slot[4] = {static_cast<float>(ox - x) * p.inv_G, static_cast<float>(oy - y) * p.inv_G,
+                               (!none && j < N_tag) ? 1.0f : 0.0f, none ? 0.0f : 1.0f};
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+          if (active && rows[r]) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) rows[r][5 + 4 * kk + c] = slot[c];
+          }
+      }
+    }
+  }
+  // the state, once per launch (an env that was neither stepped nor reset gets its own values back)
+  if (active) {
+    p.pos_x[ai] = x;
+    p.pos_y[ai] = y;
+    p.live[ai] = lv ? 1 : 0;
+  }
+  if (a == 0) {
+    p.t[e] = t;
+    p.n_live_runners[e] = nlr;
+    p.done[e] = done;
+    if (tags_out >= 0) p.tags_step[e] = tags_out;
+  }
+}
+
+hipError_t launch_wave_kernel(const Params& p, int mode, const Roll& roll, const float* probs, uint64_t g,
+                              hipStream_t stream) {
+  WaveArgs args;
+  args.p = p;
+  args.roll = roll;
+  args.probs = probs;
+  args.g0 = g;
+  args.mode = mode;
+  if (p.K == 4)
+    hipLaunchKernelGGL(wave_env_kernel<4>, dim3(p.E), dim3(kWaveSize), 0, stream, args);
+  else
+    hipLaunchKernelGGL(wave_env_kernel<0>, dim3(p.E), dim3(kWaveSize), 0, stream, args);
+  return hipGetLastError();
+}
+
 // The limit on a kernel's dynamic LDS is a property of the kernel function on a device, not of a
 // handle: it is raised whenever a launch needs more than any launch before it on that device.
 constexpr int kMaxDevicesTracked = 64;
@@ -1604,12 +1794,21 @@ int variant_of(const Params& p) {
 
 hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint64_t g, hipStream_t stream,
                              const ObsPipe* pipe) {
+  if (p.wave_envs) {
+    Roll one;
+    std::memset(&one, 0, sizeof(one));
+    one.steps = 1;
+    one.ring_len = 1;
+    one.done = p.done_log;
+    return launch_wave_kernel(p, mode, one, probs, g, stream);
+  }
   WD_DISPATCH(launch_env_variant, mode, probs, g, stream, pipe);
 }
 
 bool rollout_available(const Params& p) { return !p.big && p.obs_mode == 0 && p.K <= kMaxRegisterK; }
 
 hipError_t launch_rollout(const Params& p, const Roll& roll, const float* ring, uint64_t g, hipStream_t stream) {
+  if (p.wave_envs) return launch_wave_kernel(p, kModeIterate, roll, ring, g, stream);
   const int kx = variant_of(p);
   if (!p.wide) {
     if (kx == 4 && p.compact_nbr) return launch_rollout_variant<false, 4, true>(p, roll, ring, g, stream);

@@ -512,10 +512,13 @@ def test_multi_step_rollout_equals_single_iterations(name, k, rounds):
 @pytest.mark.parametrize("name,k", [("large_env_k_two", 3), ("full_obs_fifty", 4), ("k_all_others", 5),
                                     ("fifteen_hundred_many_envs", 4), ("thirty_five_hundred_many_envs", 3),
                                     ("k_one_packed_envs", 5), ("k_two_odd_agent_count", 4), ("k_three", 6),
-                                    ("k_eight", 5), ("k_seven_packed_envs", 4)])
+                                    ("k_eight", 5), ("k_seven_packed_envs", 4), ("k_three_one_workgroup", 6),
+                                    ("k_eight_one_workgroup", 5), ("wave_full", 5), ("wave_k_seven", 4), ("wave_two_agents", 7),
+                                    ("beyond_wave_batch", 4), ("many_small_envs_k_two", 3)])
 def test_multi_step_rollout_of_other_launch_shapes(name, k):
     """Large-env layout, full observations, K > 8 (wd_rollout runs one launch per iteration), the
-    multi-step kernel in 512- and 1024-thread workgroups and its variants for other K than 4: slices
+    multi-step kernel in 512- and 1024-thread workgroups and its variants for other K than 4, the
+    kernel with a wave per env: slices
     and final state against k calls of wd_iterate."""
     import paper_2108_13976_amd as wd
 
@@ -633,6 +636,10 @@ def random_configuration(seed):
     # more envs than that, so that the workgroups that hold several envs are exercised as well
     if seed % 2 == 1 and N <= 129 and kw.get("obs_mode", 0) == 0:
         kw["num_envs"] = 257 + int(rng.integers(0, 300))
+        # envs of at most 64 agents in batches of at most 4096 envs run a wave per env: every other of these
+        # configurations gets a batch beyond that, which the workgroups of several small envs serve
+        if seed % 4 == 1 and N <= 64:
+            kw["num_envs"] += 4096
     return kw
 
 
@@ -814,6 +821,8 @@ EDGE = {
     "k_zero": dict(num_envs=33, num_agents=12, num_taggers=3, grid_size=7, episode_length=15, obs_k=0),
     "k_three": dict(num_envs=9, num_agents=40, num_taggers=5, grid_size=13, episode_length=30, obs_k=3),
     "k_eight": dict(num_envs=9, num_agents=40, num_taggers=5, grid_size=11, episode_length=30, obs_k=8),
+    "k_three_one_workgroup": dict(num_envs=9, num_agents=70, num_taggers=8, grid_size=15, episode_length=30, obs_k=3),
+    "k_eight_one_workgroup": dict(num_envs=9, num_agents=70, num_taggers=8, grid_size=13, episode_length=30, obs_k=8),
     "k_twelve": dict(num_envs=7, num_agents=60, num_taggers=6, grid_size=14, episode_length=25, obs_k=12),
     "k_sixteen_wide_keys": dict(num_envs=3, num_agents=200, num_taggers=15, grid_size=9000, episode_length=8, obs_k=16,
                                 tag_r2=10**7),
@@ -886,6 +895,18 @@ EDGE = {
     "large_env_odd_taggers": dict(num_envs=3, num_agents=4099, num_taggers=513, grid_size=210, episode_length=4, obs_k=4,
                                   tag_r2=5),
     "large_env_crowded": dict(num_envs=2, num_agents=4200, num_taggers=100, grid_size=16, episode_length=6, tag_r2=0),
+    # a wave per env (at most 64 agents, 4096 envs, a grid of 4096 cells a side, K <= 8), and the general kernel just beyond
+    "wave_full": dict(num_envs=7, num_agents=64, num_taggers=63, grid_size=30, episode_length=12, obs_k=8),
+    "wave_sixty_four_runners": dict(num_envs=5, num_agents=64, num_taggers=1, grid_size=9, episode_length=30, obs_k=4, tag_r2=1),
+    "wave_two_agents": dict(num_envs=9, num_agents=2, num_taggers=1, grid_size=3, episode_length=6, obs_k=1),
+    "wave_k_zero": dict(num_envs=5, num_agents=33, num_taggers=5, grid_size=20, episode_length=9, obs_k=0),
+    "wave_k_seven": dict(num_envs=5, num_agents=9, num_taggers=2, grid_size=7, episode_length=9, obs_k=7),
+    "wave_grid_limit": dict(num_envs=3, num_agents=40, num_taggers=4, grid_size=4096, episode_length=8, obs_k=4, tag_r2=10**6),
+    "wave_batch_limit": dict(num_envs=4096, num_agents=6, num_taggers=2, grid_size=8, episode_length=6, obs_k=4),
+    "beyond_wave_batch": dict(num_envs=4097, num_agents=6, num_taggers=2, grid_size=8, episode_length=6, obs_k=4),
+    "beyond_wave_agents": dict(num_envs=300, num_agents=65, num_taggers=7, grid_size=25, episode_length=10, obs_k=4),
+    "beyond_wave_grid": dict(num_envs=3, num_agents=40, num_taggers=4, grid_size=4097, episode_length=8, obs_k=4, tag_r2=10**6),
+    "many_small_envs_k_two": dict(num_envs=4500, num_agents=30, num_taggers=3, grid_size=12, episode_length=8, obs_k=2),
     "large_env_two_thousand": dict(num_envs=4, num_agents=2000, num_taggers=2000 - 1, grid_size=64, episode_length=3, obs_k=8),
 }
 
