@@ -1023,15 +1023,14 @@ __global__ __launch_bounds__(kBigObsWorkgroupSize) void big_obs_kernel(const Par
 // Large envs of a small batch: the step spread over many workgroups (Sec. 4.5 item 4 holds the step
 // at constant time only while an env has a thread per agent; this is the layout past that point).
 //
-// spread_move_kernel, workgroup (e, s): lane l owns group 128 s + l of env e: samples (iterate
-// mode), moves, checks its live runners against the taggers and counts its live agents into the
-// env's buckets.  The tag check needs every tagger's position after the move, and a tagger's
-// position is written in place by nobody in this kernel (a workgroup reading it could otherwise meet
-// the new value): every workgroup moves all taggers of its env itself, into a table in LDS (taggers
-// chained by coarse cell), and the second kernel writes their positions.  A runner then takes the
-// smallest (distance, tagger) pair in range, which is what the tagger-side scan with a minimum per
-// runner gives.  Global atomics collect credits, the number of tags and the bucket counts; the
-// value an agent's count returns is its rank inside its bucket.
+// spread_move_kernel, workgroup (e, s): lane l of the first two waves owns group 128 s + l of env
+// e: samples (iterate mode), moves, and checks its live runners against the taggers.  The tag check
+// needs every tagger's position after the move, and a tagger's position is written in place by
+// nobody in this kernel (a workgroup reading it could otherwise meet the new value): every
+// workgroup moves all taggers of its env itself, in its other two waves, into a table in LDS
+// (taggers chained by coarse cell), and the second kernel writes their positions.  A runner then
+// takes the smallest (distance, tagger) pair in range, which is what the tagger-side scan with a
+// minimum per runner gives.  Global atomics collect credits and the number of tags.
 // ----------------------------------------------------------------------------------
 struct GroupInput {  // what a group's move needs from memory
   float f[20];
@@ -1085,13 +1084,16 @@ __device__ __forceinline__ void move_group(const Params& p, int mode, int e, int
   }
 }
 
-__global__ __launch_bounds__(kSpreadMoveThreads) void spread_move_kernel(const Params p, const int mode,
-                                                                         const float* __restrict__ probs, uint32_t g_lo,
-                                                                         uint32_t g_hi) {
+__global__ __launch_bounds__(2 * kSpreadMoveThreads) void spread_move_kernel(const Params p, const int mode,
+                                                                             const float* __restrict__ probs, uint32_t g_lo,
+                                                                             uint32_t g_hi) {
   __shared__ int32_t head[kSpreadTagSide * kSpreadTagSide];  // last tagger put into each coarse cell, -1: none
   __shared__ uint32_t tagger_pos[kSpreadMaxTaggers];         // x | y << 16 after the move
   __shared__ int16_t next_in_cell[kSpreadMaxTaggers];
-  const int tid = threadIdx.x;
+  // Two halves of kSpreadMoveThreads lanes: the first moves and checks the slice's own groups, the
+  // second moves the env's taggers into the table meanwhile (half the chain of either doing both).
+  const int tid = threadIdx.x, lt = tid & (kSpreadMoveThreads - 1);
+  const bool tagger_half = tid >= kSpreadMoveThreads;
   const int e = blockIdx.x / p.spread_slices, s = blockIdx.x - e * p.spread_slices;
   const int done_in = p.done[e], t_in = p.t[e], nlr_in = p.n_live_runners[e];
   if (s == 0 && tid == 0) {  // the second kernel overwrites these while its other workgroups still need them
@@ -1101,12 +1103,12 @@ __global__ __launch_bounds__(kSpreadMoveThreads) void spread_move_kernel(const P
   }
   if (mode != kModeStep && mode != kModeIterate) return;
   const int N = p.N, N_tag = p.N_tag;
-  // this lane's group, and its first group of taggers: all loads go out before anything waits
-  const int grp = s * kSpreadMoveThreads + tid;
-  const bool have = grp < p.NG, have_tagger = p.tag_r2 >= 0 && 4 * tid < N_tag;
-  GroupInput in_mine, in_tagger;
-  if (have) load_group(p, mode, probs, e, grp, in_mine);
-  if (have_tagger) load_group(p, mode, probs, e, tid, in_tagger);
+  // this lane's group (own half) or its first group of taggers (other half): the loads go out before anything waits
+  const int grp = s * kSpreadMoveThreads + lt;
+  const bool have = !tagger_half && grp < p.NG, have_tagger = tagger_half && p.tag_r2 >= 0 && 4 * lt < N_tag;
+  GroupInput in;
+  if (have) load_group(p, mode, probs, e, grp, in);
+  if (have_tagger) load_group(p, mode, probs, e, lt, in);
   const bool step_act = !done_in;
   const bool tagging = step_act && p.tag_r2 >= 0;
   Buckets tb;
@@ -1114,24 +1116,24 @@ __global__ __launch_bounds__(kSpreadMoveThreads) void spread_move_kernel(const P
   tb.nbx = p.tag_nbx;
   tb.bmin = 0;
   if (tagging)
-    for (int j = tid; j < tb.nbx * tb.nbx; j += kSpreadMoveThreads) head[j] = -1;
-  MovedGroup mine, tagger;
+    for (int j = tid; j < tb.nbx * tb.nbx; j += 2 * kSpreadMoveThreads) head[j] = -1;
+  MovedGroup mine;
   mine.n = 0;
-  if (have) move_group(p, mode, e, grp, g_lo, g_hi, step_act, in_mine, mine);
-  if (have_tagger) move_group(p, mode, e, tid, g_lo, g_hi, step_act, in_tagger, tagger);
+  if (have) move_group(p, mode, e, grp, g_lo, g_hi, step_act, in, mine);
+  if (have_tagger) move_group(p, mode, e, lt, g_lo, g_hi, step_act, in, mine);
   __syncthreads();
-  if (tagging) {
-    for (int tg = tid; 4 * tg < N_tag; tg += kSpreadMoveThreads) {
-      if (tg != tid) {  // more taggers than one group per lane
-        load_group(p, mode, probs, e, tg, in_tagger);
-        move_group(p, mode, e, tg, g_lo, g_hi, true, in_tagger, tagger);
+  if (tagging && tagger_half) {
+    for (int tg = lt; 4 * tg < N_tag; tg += kSpreadMoveThreads) {
+      if (tg != lt) {  // more taggers than one group per lane
+        load_group(p, mode, probs, e, tg, in);
+        move_group(p, mode, e, tg, g_lo, g_hi, true, in, mine);
       }
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int i = 4 * tg + j;
         if (i < N_tag) {
-          tagger_pos[i] = uint32_t(tagger.x[j]) | (uint32_t(tagger.y[j]) << 16);
-          next_in_cell[i] = int16_t(atomicExch(&head[bucket_of(tagger.x[j], tagger.y[j], tb)], i));
+          tagger_pos[i] = uint32_t(mine.x[j]) | (uint32_t(mine.y[j]) << 16);
+          next_in_cell[i] = int16_t(atomicExch(&head[bucket_of(mine.x[j], mine.y[j], tb)], i));
         }
       }
     }
@@ -1688,7 +1690,7 @@ hipError_t launch_env_variant(const Params& p, int mode, const float* probs, uin
     if (p.big_spread) {  // both kernels on the caller's stream: the next call's first kernel needs what the second leaves
       hipError_t err = ensure_dynamic_lds(&spread_obs_kernel<WIDE, KX>, p.lds_bytes);
       if (err != hipSuccess) return err;
-      hipLaunchKernelGGL(spread_move_kernel, dim3(p.E * p.spread_slices), dim3(kSpreadMoveThreads), 0, stream, p, mode,
+      hipLaunchKernelGGL(spread_move_kernel, dim3(p.E * p.spread_slices), dim3(2 * kSpreadMoveThreads), 0, stream, p, mode,
                          probs, uint32_t(g), uint32_t(g >> 32));
       err = hipGetLastError();
       if (err != hipSuccess) return err;
