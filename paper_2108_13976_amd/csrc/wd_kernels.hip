@@ -1596,8 +1596,8 @@ __global__ __launch_bounds__(kWaveSize) void wave_env_kernel(const WaveArgs args
 #pragma unroll
     for (int kk = 0; kk < KT; ++kk) keys[kk] = ~0u;
     if (K > 0)
-      for (int j = 0; j < N; ++j) {
-        if (!((in_play >> j) & 1ull)) continue;
+      for (uint64_t left = in_play; left != 0; left &= left - 1) {  // the agents in play, in index order
+        const int j = __builtin_ctzll(left);
         const int dx = __builtin_amdgcn_readlane(x, j) - x, dy = __builtin_amdgcn_readlane(y, j) - y;
         const uint32_t key = ((uint32_t(__mul24(dx, dx)) + uint32_t(__mul24(dy, dy))) << 6) | uint32_t(j);
         insert_key<KT>(keys, j == a ? ~0u : key);
