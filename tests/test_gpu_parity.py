@@ -678,10 +678,17 @@ def test_many_more_random_configurations(seeds):
             raise AssertionError(f"seed {seed}, configuration {kw}: {err}") from err
 
 
-@pytest.mark.parametrize("seed", range(100, 116))
+def _multi_step_seeds():
+    import os
+
+    return range(100, 116 + int(os.environ.get("WD_EXTRA_ROLLOUT_SEEDS", "0")))
+
+
+@pytest.mark.parametrize("seed", _multi_step_seeds())
 def test_random_configuration_multi_step(seed):
     """wd_rollout on a random configuration: every recorded slice and the final state against one
-    wd_iterate per iteration, the final state also against the oracle."""
+    wd_iterate per iteration, the final state also against the oracle (WD_EXTRA_ROLLOUT_SEEDS runs
+    that many further seeds)."""
     import paper_2108_13976_amd as wd
 
     kw = random_configuration(seed)
