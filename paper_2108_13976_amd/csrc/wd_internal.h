@@ -30,11 +30,13 @@ constexpr int register_list_size(int kx) { return kx > 0 ? kx : (kx == -2 ? kMax
 // the agents that these do not settle, a second try with windows twice as wide and two more
 // strips.  Simulated at the headline density (strips 1.5 expected K-th-neighbour distances tall): the first
 // try settles 95 % of the agents, the second all but about one in ten thousand.
-constexpr int strip_half_own(int k) { return k + 3; }
-constexpr int strip_half_adj(int k) { return k + 2; }
-constexpr int strip_half_own2(int k) { return 2 * k + 6; }
-constexpr int strip_half_adj2(int k) { return 2 * k + 4; }
-constexpr int strip_half_far2(int k) { return 2 * k; }
+// (K = 1 takes the windows of K = 2: with its own, too many agents go on to the later tries)
+constexpr int strip_window_k(int k) { return k < 2 ? 2 : k; }
+constexpr int strip_half_own(int k) { return strip_window_k(k) + 3; }
+constexpr int strip_half_adj(int k) { return strip_window_k(k) + 2; }
+constexpr int strip_half_own2(int k) { return 2 * strip_window_k(k) + 6; }
+constexpr int strip_half_adj2(int k) { return 2 * strip_window_k(k) + 4; }
+constexpr int strip_half_far2(int k) { return 2 * strip_window_k(k); }
 constexpr int strip_pad(int k) {
   const int a = strip_half_own(k) + 2 * strip_half_adj(k), b = 2 * strip_half_adj2(k), c = strip_half_own2(k);
   return a > b ? (a > c ? a : c) : (b > c ? b : c);
