@@ -610,7 +610,9 @@ int wdc_create(const wdc_config* cfg, const wdc_buffers* bufs, wdc_handle** out)
   p.T = cfg->episode_length;
   p.K = cfg->obs_k;
   p.D = 8 + 6 * cfg->obs_k;
-  p.threads = p.N <= 256 ? 256 : (p.N + 63) / 64 * 64;
+  // (envs that fit a wave, in a batch of at most a quarter of a million agents: workgroups of one wave,
+  // whose barriers cost nothing and which spread over more compute units)
+  p.threads = (p.N <= 64 && int64_t(p.E) * p.N <= 262144) ? 64 : (p.N <= 256 ? 256 : (p.N + 63) / 64 * 64);
   p.envs_per_wg = p.threads / p.N;
   p.env_offset = uint32_t(cfg->env_offset);
   p.seed_lo = uint32_t(cfg->seed);
