@@ -636,10 +636,10 @@ def random_configuration(seed):
     # more envs than that, so that the workgroups that hold several envs are exercised as well
     if seed % 2 == 1 and N <= 129 and kw.get("obs_mode", 0) == 0:
         kw["num_envs"] = 257 + int(rng.integers(0, 300))
-        # envs of at most 64 agents in batches of at most 4096 envs run a wave per env: every other of these
+        # envs of at most 64 agents in batches of at most 8192 envs run a wave per env: every other of these
         # configurations gets a batch beyond that, which the workgroups of several small envs serve
         if seed % 4 == 1 and N <= 64:
-            kw["num_envs"] += 4096
+            kw["num_envs"] += 8192
     return kw
 
 
@@ -902,18 +902,18 @@ EDGE = {
     "large_env_odd_taggers": dict(num_envs=3, num_agents=4099, num_taggers=513, grid_size=210, episode_length=4, obs_k=4,
                                   tag_r2=5),
     "large_env_crowded": dict(num_envs=2, num_agents=4200, num_taggers=100, grid_size=16, episode_length=6, tag_r2=0),
-    # a wave per env (at most 64 agents, 4096 envs, a grid of 4096 cells a side, K <= 8), and the general kernel just beyond
+    # a wave per env (at most 64 agents, 8192 envs, a grid of 4096 cells a side, K <= 8), and the general kernel just beyond
     "wave_full": dict(num_envs=7, num_agents=64, num_taggers=63, grid_size=30, episode_length=12, obs_k=8),
     "wave_sixty_four_runners": dict(num_envs=5, num_agents=64, num_taggers=1, grid_size=9, episode_length=30, obs_k=4, tag_r2=1),
     "wave_two_agents": dict(num_envs=9, num_agents=2, num_taggers=1, grid_size=3, episode_length=6, obs_k=1),
     "wave_k_zero": dict(num_envs=5, num_agents=33, num_taggers=5, grid_size=20, episode_length=9, obs_k=0),
     "wave_k_seven": dict(num_envs=5, num_agents=9, num_taggers=2, grid_size=7, episode_length=9, obs_k=7),
     "wave_grid_limit": dict(num_envs=3, num_agents=40, num_taggers=4, grid_size=4096, episode_length=8, obs_k=4, tag_r2=10**6),
-    "wave_batch_limit": dict(num_envs=4096, num_agents=6, num_taggers=2, grid_size=8, episode_length=6, obs_k=4),
-    "beyond_wave_batch": dict(num_envs=4097, num_agents=6, num_taggers=2, grid_size=8, episode_length=6, obs_k=4),
+    "wave_batch_limit": dict(num_envs=8192, num_agents=6, num_taggers=2, grid_size=8, episode_length=6, obs_k=4),
+    "beyond_wave_batch": dict(num_envs=8193, num_agents=6, num_taggers=2, grid_size=8, episode_length=6, obs_k=4),
     "beyond_wave_agents": dict(num_envs=300, num_agents=65, num_taggers=7, grid_size=25, episode_length=10, obs_k=4),
     "beyond_wave_grid": dict(num_envs=3, num_agents=40, num_taggers=4, grid_size=4097, episode_length=8, obs_k=4, tag_r2=10**6),
-    "many_small_envs_k_two": dict(num_envs=4500, num_agents=30, num_taggers=3, grid_size=12, episode_length=8, obs_k=2),
+    "many_small_envs_k_two": dict(num_envs=8500, num_agents=30, num_taggers=3, grid_size=12, episode_length=8, obs_k=2),
     "large_env_two_thousand": dict(num_envs=4, num_agents=2000, num_taggers=2000 - 1, grid_size=64, episode_length=3, obs_k=8),
 }
 
