@@ -17,6 +17,8 @@ LARGE = dict(num_envs=6, num_agents=2000, num_taggers=150, grid_size=300, episod
 SMALLER = dict(num_envs=3, num_agents=700, num_taggers=60, grid_size=120, episode_length=5, seed=12)
 # small layout (no work tables at all)
 PLAIN = dict(num_envs=40, num_agents=90, num_taggers=9, grid_size=30, episode_length=7, seed=13)
+# envs that fit a wave (the kernel with a wave per env; no work tables either)
+WAVE = dict(num_envs=33, num_agents=20, num_taggers=4, grid_size=9, episode_length=6, seed=14)
 
 
 def run_both(kw, iterations):
@@ -48,3 +50,4 @@ def test_static_entry_point_equals_wd_iterate_two_calls_in_a_row():
     run_both(LARGE, 14)
     run_both(SMALLER, 12)  # smaller input on the same static array, which still holds the first run's tables
     run_both(PLAIN, 16)
+    run_both(WAVE, 14)
