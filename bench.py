@@ -582,6 +582,18 @@ def main():
                                     "resets_per_iteration": w["resets_per_iteration"]}
                 del other_ring
             extras["configs"] = per_config
+            # the paper's other discrete-Tag shape (Sec. 5.3 quotes its throughput at 2000 envs x 5 agents as well):
+            # tag_10x5 with 2000 envs, same windows
+            import dataclasses
+            small = dataclasses.replace(CONFIGS["tag_10x5"], name="tag_2000x5", num_envs=2000, seed=5)
+            small_ring = device_probs_ring(small.seed, RING, small.num_envs, small.num_agents, "cuda:0")
+            w = contract_window(small, small_ring, repetitions=3)
+            _, ev_roll, _, _, _ = time_gpu(small, small_ring, w["iterations"], 50, "rollout", 25)
+            extras["tag_2000x5"] = {"us_per_iteration": w["avg_launch_us"], "env_steps_per_s": w["env_steps_per_s"],
+                                    "rollout_us_per_iteration": ev_roll / w["iterations"] * 1e6,
+                                    "rollout_env_steps_per_s": small.num_envs / (ev_roll / w["iterations"]),
+                                    "iterations": w["iterations"]}
+            del small_ring
             # continuous Tag (paper Sec. 5.1, second variant): its three workloads, 2 T iterations after 50
             from workloads import CTAG_CONFIGS
             extras["continuous_tag"] = {name: continuous_figures(c) for name, c in CTAG_CONFIGS.items()}
