@@ -484,7 +484,7 @@ int fill_params(const wd_config& c, const wd_buffers& b, wd::Params* p) {
   // Envs that fit a wave, in a batch that cannot fill the chip anyway: a wave per env, a lane per agent
   // (keys of 32 bits: squared distance << 6 | index).
   p->wave_envs = (!p->big && c.num_agents <= wd::kWaveSize && c.num_envs <= kWaveEnvsMaxBatch &&
-                  c.obs_mode == WD_OBS_PARTIAL && p->K <= wd::kMaxRegisterK && c.grid_size <= 4096)
+                  c.obs_mode == WD_OBS_PARTIAL && p->K <= wd::kMaxRegisterK2 && c.grid_size <= 4096)
                      ? 1
                      : 0;
   return WD_OK;

@@ -1493,7 +1493,7 @@ template <int KC>
 __global__ __launch_bounds__(kWaveSize) void wave_env_kernel(const WaveArgs args) {
   const Params& p = args.p;
   const Roll& roll = args.roll;
-  constexpr int KT = KC > 0 ? KC : kMaxRegisterK;
+  constexpr int KT = register_list_size(KC);  // KC > 0: K compiled in; 0: K <= 8 at run time; -2: K <= 16
   const int a = threadIdx.x, e = blockIdx.x;
   const int N = p.N, N_tag = p.N_tag, G = p.G;
   const int K = KC > 0 ? KC : p.K;
@@ -1654,8 +1654,10 @@ hipError_t launch_wave_kernel(const Params& p, int mode, const Roll& roll, const
   args.mode = mode;
   if (p.K == 4)
     hipLaunchKernelGGL(wave_env_kernel<4>, dim3(p.E), dim3(kWaveSize), 0, stream, args);
-  else
+  else if (p.K <= kMaxRegisterK)
     hipLaunchKernelGGL(wave_env_kernel<0>, dim3(p.E), dim3(kWaveSize), 0, stream, args);
+  else
+    hipLaunchKernelGGL(wave_env_kernel<-2>, dim3(p.E), dim3(kWaveSize), 0, stream, args);
   return hipGetLastError();
 }
 
@@ -1807,7 +1809,7 @@ hipError_t launch_env_kernel(const Params& p, int mode, const float* probs, uint
   WD_DISPATCH(launch_env_variant, mode, probs, g, stream, pipe);
 }
 
-bool rollout_available(const Params& p) { return !p.big && p.obs_mode == 0 && p.K <= kMaxRegisterK; }
+bool rollout_available(const Params& p) { return p.wave_envs || (!p.big && p.obs_mode == 0 && p.K <= kMaxRegisterK); }
 
 hipError_t launch_rollout(const Params& p, const Roll& roll, const float* ring, uint64_t g, hipStream_t stream) {
   if (p.wave_envs) return launch_wave_kernel(p, kModeIterate, roll, ring, g, stream);

@@ -513,7 +513,7 @@ def test_multi_step_rollout_equals_single_iterations(name, k, rounds):
                                     ("fifteen_hundred_many_envs", 4), ("thirty_five_hundred_many_envs", 3),
                                     ("k_one_packed_envs", 5), ("k_two_odd_agent_count", 4), ("k_three", 6),
                                     ("k_eight", 5), ("k_seven_packed_envs", 4), ("k_three_one_workgroup", 6),
-                                    ("k_eight_one_workgroup", 5), ("wave_full", 5), ("wave_k_seven", 4), ("wave_two_agents", 7),
+                                    ("k_eight_one_workgroup", 5), ("wave_full", 5), ("wave_k_seven", 4), ("wave_two_agents", 7), ("wave_k_sixteen", 4),
                                     ("beyond_wave_batch", 4), ("many_small_envs_k_two", 3)])
 def test_multi_step_rollout_of_other_launch_shapes(name, k):
     """Large-env layout, full observations, K > 8 (wd_rollout runs one launch per iteration), the
@@ -902,12 +902,15 @@ EDGE = {
     "large_env_odd_taggers": dict(num_envs=3, num_agents=4099, num_taggers=513, grid_size=210, episode_length=4, obs_k=4,
                                   tag_r2=5),
     "large_env_crowded": dict(num_envs=2, num_agents=4200, num_taggers=100, grid_size=16, episode_length=6, tag_r2=0),
-    # a wave per env (at most 64 agents, 8192 envs, a grid of 4096 cells a side, K <= 8), and the general kernel just beyond
+    # a wave per env (at most 64 agents, 8192 envs, a grid of 4096 cells a side, K <= 16), and the general kernel just beyond
     "wave_full": dict(num_envs=7, num_agents=64, num_taggers=63, grid_size=30, episode_length=12, obs_k=8),
     "wave_sixty_four_runners": dict(num_envs=5, num_agents=64, num_taggers=1, grid_size=9, episode_length=30, obs_k=4, tag_r2=1),
     "wave_two_agents": dict(num_envs=9, num_agents=2, num_taggers=1, grid_size=3, episode_length=6, obs_k=1),
     "wave_k_zero": dict(num_envs=5, num_agents=33, num_taggers=5, grid_size=20, episode_length=9, obs_k=0),
     "wave_k_seven": dict(num_envs=5, num_agents=9, num_taggers=2, grid_size=7, episode_length=9, obs_k=7),
+    "k_twelve_small_layout": dict(num_envs=5, num_agents=100, num_taggers=9, grid_size=20, episode_length=9, obs_k=12),
+    "wave_k_sixteen": dict(num_envs=6, num_agents=40, num_taggers=5, grid_size=12, episode_length=9, obs_k=16),
+    "wave_k_nine_few_agents": dict(num_envs=6, num_agents=10, num_taggers=2, grid_size=5, episode_length=9, obs_k=9),
     "wave_grid_limit": dict(num_envs=3, num_agents=40, num_taggers=4, grid_size=4096, episode_length=8, obs_k=4, tag_r2=10**6),
     "wave_batch_limit": dict(num_envs=8192, num_agents=6, num_taggers=2, grid_size=8, episode_length=6, obs_k=4),
     "beyond_wave_batch": dict(num_envs=8193, num_agents=6, num_taggers=2, grid_size=8, episode_length=6, obs_k=4),
