@@ -1606,11 +1606,12 @@ __global__ __launch_bounds__(kWaveSize) void wave_env_kernel(const WaveArgs args
     const float t_frac = static_cast<float>(t) * p.inv_T;
     const float own[5] = {static_cast<float>(x) * p.inv_G, static_cast<float>(y) * p.inv_G, a < N_tag ? 1.0f : 0.0f,
                           lv ? 1.0f : 0.0f, t_frac};
+    // (a row starts on a 4-byte boundary: its floats leave four at a time, at that alignment)
 #pragma unroll
     for (int r = 0; r < 2; ++r)
       if (active && rows[r]) {
-#pragma unroll
-        for (int c = 0; c < 5; ++c) rows[r][c] = own[c];
+        *reinterpret_cast<Slot4*>(rows[r]) = Slot4{own[0], own[1], own[2], own[3]};
+        rows[r][4] = own[4];
       }
 #pragma unroll
     for (int kk = 0; kk < KT; ++kk) {
@@ -1623,10 +1624,7 @@ __global__ __launch_bounds__(kWaveSize) void wave_env_kernel(const WaveArgs args
                                (!none && j < N_tag) ? 1.0f : 0.0f, none ? 0.0f : 1.0f};
 #pragma unroll
         for (int r = 0; r < 2; ++r)
-          if (active && rows[r]) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) rows[r][5 + 4 * kk + c] = slot[c];
-          }
+          if (active && rows[r]) *reinterpret_cast<Slot4*>(rows[r] + 5 + 4 * kk) = Slot4{slot[0], slot[1], slot[2], slot[3]};
       }
     }
   }
